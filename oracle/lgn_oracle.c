@@ -1,0 +1,549 @@
+/*
+ * lgn_oracle.c -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.
+ *
+ * A plain, slow, CPU-only statement of what the lognormal gradient-compression path computes,
+ * written from the paper ("Neural gradients are near-lognormal: improved quantized and sparse
+ * training").  It exists so that the GPU library can be checked against something that can be
+ * read next to the paper by eye.  Only tests, the smoke check and the benchmark's cpu_baseline
+ * leg may call it.  It shares no code, header, table or constant with the GPU library; it has
+ * its own struct layouts and its own names.
+ *
+ * Every function states the passage it follows.  Scalar mathematics is in double precision;
+ * the per-element operators work in the value domain (frexp / ldexp / comparisons of values),
+ * not on bit patterns.  Loops over elements carry an OpenMP pragma because elements are
+ * independent; nothing else is done for speed.
+ *
+ * Conventions the paper leaves open (all listed in the design document):
+ *   - statistics use the population standard deviation over finite non-zero entries;
+ *   - the uniform variable of stochastic pruning has 24 bits, u = k / 2^24, and the comparison
+ *     value alpha*u is one IEEE single-precision product;
+ *   - random words come from Philox4x32-10 (Salmon et al., SC'11) keyed by the 64-bit seed, with
+ *     counter (lo32(j>>2), hi32(j>>2), purpose, 0) and word index j&3 for global element j;
+ *   - an FP(1,e,m) word has exponent field c in [1, 2^e-1] meaning E = c - 2^(e-1), field 0 is
+ *     zero; saturation goes to the largest finite code; underflow flushes to zero and is decided
+ *     on the exponent before rounding.
+ *
+ * Pins (tests/test_oracle_*.py): Philox known-answer vectors; Table 2 of the paper for the
+ * format choice; quadrature of the sparsity definition (the expectation over the uniform
+ * variable of the lognormal CDF) and Monte-Carlo pruning for the threshold; exhaustive
+ * enumeration of all FP-n codes for the quantizer; exact results on powers of two for the
+ * statistics.  Parity unpinned (pure conventions): the 0.997 default quantile of the scale rule,
+ * the tie rule of nearest rounding, the 24-bit width of u.
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- enumerations (oracle's own; values are part of the documented C interface) ---------- */
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_ROUND_NEAREST_EVEN = 0, ORC_ROUND_STOCHASTIC = 1 };
+enum { ORC_OUT_VALUE = 0, ORC_OUT_CODE8 = 1, ORC_OUT_PACKED = 2 };
+enum { ORC_SCALE_QUANTILE = 0, ORC_SCALE_MAX = 1, ORC_SCALE_CENTER = 2 };
+enum { ORC_SIGMA_PAPER_LITERAL = 0, ORC_SIGMA_BASE2 = 1 };
+enum {
+    ORC_ST_EMPTY = 1u,             /* no finite non-zero element                          */
+    ORC_ST_SIGMA0 = 2u,            /* all finite non-zero magnitudes equal                */
+    ORC_ST_NOTHING_TO_PRUNE = 4u,  /* target sparsity already met by existing zeros       */
+    ORC_ST_NOT_CONVERGED = 8u,
+    ORC_ST_ALPHA_BELOW_FP_RANGE = 16u,
+    ORC_ST_HAS_NONFINITE = 32u
+};
+
+typedef struct {
+    uint64_t n, nnz, n_nonfinite;
+    double mu, sigma;          /* of ln|g| over finite non-zero entries, population std */
+    float max_abs, min_abs_nz; /* over finite non-zero entries; 0 when there is none    */
+    uint32_t status;
+} orc_stats_t;
+
+typedef struct {
+    float alpha;   /* threshold, already rounded to the tensor dtype             */
+    double s_eff;  /* S' : sparsity asked of the non-zero part                    */
+    double s_pred; /* closed-form sparsity of the non-zero part at the rounded alpha */
+    uint32_t status;
+} orc_prune_params_t;
+
+typedef struct {
+    int32_t n_bits, e_bits, m_bits, scale_exp;
+    double eta; /* expected relative error of the chosen split */
+    uint32_t status;
+} orc_fp_params_t;
+
+static int g_threads = 1;
+void orc_set_threads(int t) { g_threads = t < 1 ? 1 : t; }
+int orc_get_threads(void) { return g_threads; }
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_num_procs();
+#else
+    return 1;
+#endif
+}
+
+/* ---- element access ---------------------------------------------------------------------- */
+static float bf16_to_float(uint16_t h)
+{
+    uint32_t b = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &b, 4);
+    return f;
+}
+/* fp32 -> bf16, round to nearest, ties to even; only ever applied to values that are exactly
+ * representable, and to alpha. */
+static uint16_t float_to_bf16(float f)
+{
+    uint32_t b;
+    memcpy(&b, &f, 4);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((b >> 16) | 0x40u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+static float load_elem(const void *g, uint64_t i, int dtype)
+{
+    return dtype == ORC_F32 ? ((const float *)g)[i] : bf16_to_float(((const uint16_t *)g)[i]);
+}
+static void store_elem(void *out, uint64_t i, int dtype, float v)
+{
+    if (dtype == ORC_F32) ((float *)out)[i] = v;
+    else ((uint16_t *)out)[i] = float_to_bf16(v);
+}
+
+/* ==========================================================================================
+ * Step 1.  Lognormal parameters (Section "Neural gradients distribution": the fit is made on
+ * the absolute values, zero-valued entries excluded; appendix "Stochastic pruning complexity":
+ * mean and standard deviation, O(n)).
+ * mu = mean of ln|g|, sigma = population standard deviation of ln|g|, both over the entries
+ * that are finite and non-zero.  Two passes: mean first, then squared deviations.
+ * ========================================================================================== */
+void orc_stats(const void *g, uint64_t n, int dtype, orc_stats_t *out)
+{
+    uint64_t nnz = 0, nonfinite = 0;
+    long double sum = 0.0L;
+    float mx = 0.0f, mn = INFINITY;
+    int64_t i, N = (int64_t)n;
+#pragma omp parallel for num_threads(g_threads) reduction(+ : nnz, nonfinite, sum) \
+    reduction(max : mx) reduction(min : mn)
+    for (i = 0; i < N; ++i) {
+        float x = load_elem(g, (uint64_t)i, dtype);
+        if (!isfinite(x)) { ++nonfinite; continue; }
+        if (x == 0.0f) continue;
+        float a = fabsf(x);
+        ++nnz;
+        sum += (long double)log((double)a);
+        if (a > mx) mx = a;
+        if (a < mn) mn = a;
+    }
+    memset(out, 0, sizeof *out);
+    out->n = n;
+    out->nnz = nnz;
+    out->n_nonfinite = nonfinite;
+    if (nonfinite) out->status |= ORC_ST_HAS_NONFINITE;
+    if (nnz == 0) {
+        out->mu = NAN;
+        out->sigma = NAN;
+        out->max_abs = 0.0f;
+        out->min_abs_nz = 0.0f;
+        out->status |= ORC_ST_EMPTY;
+        return;
+    }
+    double mu = (double)(sum / (long double)nnz);
+    long double ss = 0.0L;
+#pragma omp parallel for num_threads(g_threads) reduction(+ : ss)
+    for (i = 0; i < N; ++i) {
+        float x = load_elem(g, (uint64_t)i, dtype);
+        if (!isfinite(x) || x == 0.0f) continue;
+        long double d = (long double)log((double)fabsf(x)) - (long double)mu;
+        ss += d * d;
+    }
+    out->mu = mu;
+    out->sigma = sqrt((double)(ss / (long double)nnz));
+    out->max_abs = mx;
+    out->min_abs_nz = mn;
+    if (mx == mn) out->status |= ORC_ST_SIGMA0;
+}
+
+/* ==========================================================================================
+ * Step 2a.  Sparsity as a function of the threshold (Section "Analytical derivation of
+ * Sparsity", the closed form that follows the integral over the uniform variable; derivation
+ * in the appendix "From sparsity to the threshold").  With L = ln(alpha / e^mu):
+ *
+ *   S = 1/2 + (e^mu / 2 alpha) [ e^{sigma^2/2} erf(sigma/sqrt2 - L/(sqrt2 sigma))
+ *                                + (alpha/e^mu) erf(L/(sqrt2 sigma)) - e^{sigma^2/2} ]
+ *
+ * The two terms that carry e^{sigma^2/2} are combined as erf(a) - 1 = -erfc(a) so that nothing
+ * cancels, and the product e^{sigma^2/2 - L} erfc(a) is formed as exp of a sum of logarithms so
+ * that it neither overflows nor turns into inf * 0.
+ * ========================================================================================== */
+double orc_sparsity_of_log_alpha(double mu, double sigma, double v)
+{
+    double L = v - mu;
+    double a = sigma / M_SQRT2 - L / (M_SQRT2 * sigma);
+    double tail = erfc(a);
+    double second = tail > 0.0 ? exp(0.5 * sigma * sigma - L + log(tail)) : 0.0;
+    return 0.5 + 0.5 * erf(L / (M_SQRT2 * sigma)) - 0.5 * second;
+}
+double orc_sparsity_of_alpha(double mu, double sigma, double alpha)
+{
+    return orc_sparsity_of_log_alpha(mu, sigma, log(alpha));
+}
+
+/* Standard normal quantile by bisection on the CDF (used by the scale rule only). */
+static double normal_cdf(double z) { return 0.5 * erfc(-z / M_SQRT2); }
+double orc_normal_quantile(double q)
+{
+    double lo = -40.0, hi = 40.0;
+    for (int it = 0; it < 200; ++it) {
+        double mid = 0.5 * (lo + hi);
+        if (normal_cdf(mid) < q) lo = mid; else hi = mid;
+        if (hi - lo <= 1e-16 * fmax(1.0, fabs(mid))) break;
+    }
+    return 0.5 * (lo + hi);
+}
+
+/* ==========================================================================================
+ * Step 2b.  Threshold for a target sparsity (Section "Stochastic pruning", problem
+ * formulation: find alpha that induces sparsity S; the closed form "can easily be solved
+ * numerically").  The target S is the zero fraction of the whole output tensor, so the
+ * non-zero part must be pruned to S' = (S - l)/(1 - l) with l the fraction already zero
+ * (appendix "Algorithm for bi-Modal lognormal pruning", step 2).
+ * Solved by bisection on v = ln(alpha); S is increasing in v.
+ * ========================================================================================== */
+void orc_threshold(const orc_stats_t *st, double target_sparsity, int alpha_dtype,
+                   orc_prune_params_t *out)
+{
+    memset(out, 0, sizeof *out);
+    out->status = st->status & (ORC_ST_EMPTY | ORC_ST_SIGMA0 | ORC_ST_HAS_NONFINITE);
+    if (st->nnz == 0) {
+        out->alpha = 0.0f;
+        out->s_eff = 0.0;
+        out->s_pred = 0.0;
+        return;
+    }
+    double n = (double)st->n, nnz = (double)st->nnz;
+    double s_eff = (target_sparsity * n - (n - nnz)) / nnz;
+    out->s_eff = s_eff;
+    if (!(s_eff > 0.0)) {
+        out->alpha = 0.0f;
+        out->s_pred = 0.0;
+        out->status |= ORC_ST_NOTHING_TO_PRUNE;
+        return;
+    }
+    double mu = st->mu, sigma = st->sigma, v;
+    if (sigma < 1e-12) {
+        /* point mass at c = e^mu: the fraction zeroed is P(c < alpha u) = 1 - c/alpha */
+        v = mu - log1p(-s_eff);
+        out->status |= ORC_ST_SIGMA0;
+    } else {
+        double lo = mu - 40.0 * sigma, hi = mu + 40.0 * sigma + sigma * sigma + 50.0;
+        if (!(orc_sparsity_of_log_alpha(mu, sigma, lo) < s_eff &&
+              orc_sparsity_of_log_alpha(mu, sigma, hi) > s_eff))
+            out->status |= ORC_ST_NOT_CONVERGED;
+        for (int it = 0; it < 400; ++it) {
+            double mid = 0.5 * (lo + hi);
+            if (orc_sparsity_of_log_alpha(mu, sigma, mid) < s_eff) lo = mid; else hi = mid;
+            if (hi - lo <= 1e-15 * fmax(1.0, fabs(mid))) break;
+        }
+        v = 0.5 * (lo + hi);
+    }
+    double alpha = exp(v);
+    float af = alpha >= (double)FLT_MAX ? FLT_MAX : (float)alpha;
+    if (alpha_dtype == ORC_BF16) {
+        af = bf16_to_float(float_to_bf16(af));
+        if (!isfinite(af)) af = bf16_to_float(0x7f7f);
+    }
+    out->alpha = af;
+    if (af > 0.0f)
+        out->s_pred = sigma < 1e-12 ? fmax(0.0, 1.0 - exp(mu) / (double)af)
+                                    : orc_sparsity_of_alpha(mu, sigma, (double)af);
+}
+
+/* ==========================================================================================
+ * Step 3a.  Expected relative error of an FP(1, e, m) quantizer on lognormal data (Section
+ * "Analytical derivation of the relative error", the closed form, and its appendix).  Three
+ * contributions: mantissa noise when the exponent is in range, saturation above, flush below.
+ * E_max = 2^(e-1).  The mantissa term uses 2^m levels (spacing 1/2^m as the problem
+ * formulation states); the printed denominator 2^m - 1 would make every m = 0 split infinitely
+ * bad, against the paper's own table of optimal formats.
+ * ========================================================================================== */
+double orc_expected_relative_error(double sigma, int e_bits, int m_bits)
+{
+    double emax = ldexp(1.0, e_bits - 1);
+    double phi = normal_cdf(emax / sigma);
+    double mantissa = (2.0 * phi - 1.0) / (8.0 * M_LN2 * ldexp(1.0, m_bits));
+    double z = sigma * M_LN2 / M_SQRT2 + emax / (M_SQRT2 * sigma);
+    double tail = erfc(z);
+    /* 2^(E_max-1) e^{sigma^2 ln^2 2 / 2} (erf(z) - 1), formed in the log domain */
+    double over = tail > 0.0
+                      ? -exp((emax - 1.0) * M_LN2 + 0.5 * sigma * sigma * M_LN2 * M_LN2 + log(tail))
+                      : 0.0;
+    return mantissa + over - 0.5 * erf(emax / (M_SQRT2 * sigma)) + 1.5 - phi;
+}
+
+/* ==========================================================================================
+ * Step 3b.  Exponent/mantissa split and power-of-two scale.
+ * Split (Section "The optimal mantissa-exponent representation"): the e in [1, N-1] that
+ * minimises the expected relative error with m = N-1-e; ties go to the smaller e.
+ * Scale (Section "Per-Layer Gradient scaling" and the appendix algorithm "Gradient scaling"):
+ * an integer exponent s such that the tensor is quantized as 2^s Q(x / 2^s), chosen so that the
+ * largest gradients land in the top binade 2^(E_max-1):
+ *   MAX       s = floor(log2 max|x|)                      - (E_max - 1)
+ *   QUANTILE  s = floor(log2 of the q-quantile of the fitted lognormal) - (E_max - 1)
+ *             (the appendix on truncated lognormals takes a high quantile, e.g. 0.997,
+ *              because the sample maximum is a noisy estimator)
+ *   CENTER    s = round(mu / ln 2)
+ * ========================================================================================== */
+void orc_fp_params(const orc_stats_t *st, int n_bits, int e_bits, int scale_mode, double scale_arg,
+                   int sigma_units, orc_fp_params_t *out)
+{
+    memset(out, 0, sizeof *out);
+    out->n_bits = n_bits;
+    out->status = st->status & (ORC_ST_EMPTY | ORC_ST_SIGMA0 | ORC_ST_HAS_NONFINITE);
+    int e;
+    if (e_bits >= 1) {
+        e = e_bits;
+        out->eta = (st->nnz && st->sigma >= 1e-12)
+                       ? orc_expected_relative_error(
+                             sigma_units == ORC_SIGMA_BASE2 ? st->sigma / M_LN2 : st->sigma, e,
+                             n_bits - 1 - e)
+                       : 0.0;
+    } else if (st->nnz == 0 || st->sigma < 1e-12) {
+        e = 1; /* no spread: every bit to the mantissa */
+        out->eta = 0.0;
+    } else {
+        double sg = sigma_units == ORC_SIGMA_BASE2 ? st->sigma / M_LN2 : st->sigma;
+        double best = INFINITY;
+        e = 1;
+        for (int c = 1; c <= n_bits - 1; ++c) {
+            double eta = orc_expected_relative_error(sg, c, n_bits - 1 - c);
+            if (eta < best) { best = eta; e = c; }
+        }
+        out->eta = best;
+    }
+    out->e_bits = e;
+    out->m_bits = n_bits - 1 - e;
+    int etop = (1 << (e - 1)) - 1;
+    if (st->nnz == 0) { out->scale_exp = 0; return; }
+    double top_log2;
+    if (scale_mode == ORC_SCALE_MAX) {
+        int ex;
+        frexp((double)st->max_abs, &ex); /* max = f 2^ex, f in [1/2,1)  =>  floor(log2 max) = ex-1 */
+        out->scale_exp = (ex - 1) - etop;
+        return;
+    } else if (scale_mode == ORC_SCALE_CENTER) {
+        out->scale_exp = (int)floor(st->mu / M_LN2 + 0.5);
+        return;
+    }
+    top_log2 = (st->mu + orc_normal_quantile(scale_arg) * st->sigma) / M_LN2;
+    out->scale_exp = (int)floor(top_log2) - etop;
+}
+
+/* ==========================================================================================
+ * Random words: Philox4x32-10 as published (Salmon, Moraes, Dror, Shaw, "Parallel random
+ * numbers: as easy as 1, 2, 3", SC'11): ten rounds; per round the two products
+ * 0xD2511F53 * c0 and 0xCD9E8D57 * c2 are split in high and low halves and recombined with the
+ * other two counter words and the key; the key advances by the Weyl constants between rounds.
+ * ========================================================================================== */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The word that global element j draws for a purpose (0 = pruning, 1 = rounding). */
+uint32_t orc_random_word(uint64_t seed, uint64_t j, uint32_t purpose)
+{
+    uint64_t q = j >> 2;
+    uint32_t ctr[4] = { (uint32_t)q, (uint32_t)(q >> 32), purpose, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t w[4];
+    orc_philox4x32_10(ctr, key, w);
+    return w[j & 3u];
+}
+
+/* ==========================================================================================
+ * Step 4.  Stochastic pruning T_{alpha,eps} (Section "Stochastic pruning", the three-case
+ * definition):  |x| > alpha -> x;  alpha eps <= |x| <= alpha -> sign(x) alpha;
+ * |x| < alpha eps -> 0.   eps = u = (w >> 8) / 2^24 and alpha*u is one single-precision product.
+ * Exact zeros stay zero whatever u is, NaN passes through.
+ * ========================================================================================== */
+static float prune_one(float x, float alpha, uint32_t w)
+{
+    if (isnan(x)) return x;
+    float a = fabsf(x);
+    if (a == 0.0f) return 0.0f;
+    if (a > alpha) return x;
+    float u = (float)(w >> 8) * 0x1p-24f;
+    float t = (float)((double)alpha * (double)u); /* exact product, one rounding to single */
+    if (a < t) return 0.0f;
+    return copysignf(alpha, x);
+}
+
+void orc_prune(const void *g, uint64_t n, int dtype, float alpha, uint64_t seed,
+               uint64_t elem_offset, void *out)
+{
+    int64_t i, N = (int64_t)n;
+#pragma omp parallel for num_threads(g_threads)
+    for (i = 0; i < N; ++i) {
+        float x = load_elem(g, (uint64_t)i, dtype);
+        uint32_t w = orc_random_word(seed, elem_offset + (uint64_t)i, 0u);
+        float y = prune_one(x, alpha, w);
+        if (dtype == ORC_F32) ((float *)out)[i] = y; /* keeps NaN payloads */
+        else if (isnan(y)) ((uint16_t *)out)[i] = ((const uint16_t *)g)[i];
+        else store_elem(out, (uint64_t)i, dtype, y);
+    }
+}
+
+/* ==========================================================================================
+ * Step 5.  FP(1,e,m) quantizer with scale 2^s (Section "Problem formulation" of the
+ * quantization application: decomposition x = M 2^E with M in [1,2); saturate above, flush
+ * below, mantissa on 2^m levels; appendix algorithm "Gradient scaling": X_Q = 2^s Q(X / 2^s)).
+ * Returns the N-bit code:  sign << (e+m) | (E + E_max) << m | k.
+ * ========================================================================================== */
+static uint32_t quantize_one(float x, int e, int m, int s, int rounding, uint32_t w)
+{
+    int emax = 1 << (e - 1), etop = emax - 1, emin = 1 - emax;
+    uint32_t sign = signbit(x) ? 1u << (e + m) : 0u;
+    uint32_t maxmag = (1u << (e + m)) - 1u;
+    if (isnan(x) || x == 0.0f) return 0u;
+    if (isinf(x)) return sign | maxmag;
+    int ex;
+    double M = 2.0 * frexp(fabs((double)x), &ex); /* |x| = M 2^(ex-1), M in [1,2) */
+    int E = (ex - 1) - s;
+    if (E < emin) return 0u;
+    if (E > etop) return sign | maxmag;
+    double levels = ldexp(1.0, m);
+    double k = floor((M - 1.0) * levels);
+    /* what is cut off, in units of the input's own last mantissa place (2^-23) */
+    double f = (M - 1.0) * 8388608.0 - k * ldexp(1.0, 23 - m);
+    double unit = ldexp(1.0, 23 - m);
+    int up;
+    if (rounding == ORC_ROUND_STOCHASTIC) {
+        double r = (double)(w >> (9 + m));
+        up = f + r >= unit;
+    } else {
+        uint32_t code_below = ((uint32_t)(E + emax) << m) | (uint32_t)k;
+        up = f > 0.5 * unit || (f == 0.5 * unit && (code_below & 1u));
+    }
+    if (up) {
+        k += 1.0;
+        if (k == levels) { k = 0.0; E += 1; }
+        if (E > etop) return sign | maxmag;
+    }
+    return sign | ((uint32_t)(E + emax) << m) | (uint32_t)k;
+}
+
+/* Value of a code: exponent field 0 is zero whatever the other bits say. */
+double orc_decode(uint32_t code, int e, int m, int s)
+{
+    int emax = 1 << (e - 1);
+    uint32_t c = (code >> m) & ((1u << e) - 1u);
+    uint32_t k = code & ((1u << m) - 1u);
+    if (c == 0) return 0.0;
+    double v = ldexp(1.0 + (double)k / ldexp(1.0, m), (int)c - emax + s);
+    return ((code >> (e + m)) & 1u) ? -v : v;
+}
+
+uint64_t orc_packed_bytes(uint64_t n, int n_bits) { return (n * (uint64_t)n_bits + 7u) / 8u; }
+
+/* Little-endian bit stream: bit b of code i is bit i*N + b of the stream. */
+void orc_pack(const uint8_t *codes, uint64_t n, int n_bits, uint8_t *out)
+{
+    memset(out, 0, orc_packed_bytes(n, n_bits));
+    for (uint64_t i = 0; i < n; ++i)
+        for (int b = 0; b < n_bits; ++b)
+            if ((codes[i] >> b) & 1u) {
+                uint64_t pos = i * (uint64_t)n_bits + (uint64_t)b;
+                out[pos >> 3] |= (uint8_t)(1u << (pos & 7u));
+            }
+}
+void orc_unpack(const uint8_t *packed, uint64_t n, int n_bits, uint8_t *codes)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        uint8_t c = 0;
+        for (int b = 0; b < n_bits; ++b) {
+            uint64_t pos = i * (uint64_t)n_bits + (uint64_t)b;
+            if ((packed[pos >> 3] >> (pos & 7u)) & 1u) c |= (uint8_t)(1u << b);
+        }
+        codes[i] = c;
+    }
+}
+
+static void emit(void *out, uint64_t i, int dtype, int out_kind, const void *g, float x,
+                 uint32_t code, int e, int m, int s, uint8_t *codes)
+{
+    if (out_kind == ORC_OUT_VALUE) {
+        if (isnan(x)) {
+            if (dtype == ORC_F32) ((float *)out)[i] = x;
+            else ((uint16_t *)out)[i] = g ? ((const uint16_t *)g)[i] : 0x7fc0;
+        } else {
+            store_elem(out, i, dtype, (float)orc_decode(code, e, m, s));
+        }
+    } else {
+        codes[i] = (uint8_t)code;
+    }
+}
+
+/* Quantize (and optionally prune first).  For PACKED output `scratch_codes` must hold n bytes. */
+static void quantize_impl(const void *g, uint64_t n, int dtype, int do_prune, float alpha, int e,
+                          int m, int s, int rounding, uint64_t seed, uint64_t elem_offset,
+                          void *out, int out_kind, uint8_t *scratch_codes)
+{
+    uint8_t *codes = out_kind == ORC_OUT_CODE8 ? (uint8_t *)out : scratch_codes;
+    int64_t i, N = (int64_t)n;
+#pragma omp parallel for num_threads(g_threads)
+    for (i = 0; i < N; ++i) {
+        uint64_t j = elem_offset + (uint64_t)i;
+        float x = load_elem(g, (uint64_t)i, dtype);
+        if (do_prune) x = prune_one(x, alpha, orc_random_word(seed, j, 0u));
+        uint32_t w = rounding == ORC_ROUND_STOCHASTIC ? orc_random_word(seed, j, 1u) : 0u;
+        uint32_t code = quantize_one(x, e, m, s, rounding, w);
+        emit(out, (uint64_t)i, dtype, out_kind, g, x, code, e, m, s, codes);
+    }
+    if (out_kind == ORC_OUT_PACKED) orc_pack(codes, n, 1 + e + m, (uint8_t *)out);
+}
+
+void orc_fp_quantize(const void *g, uint64_t n, int dtype, int e, int m, int s, int rounding,
+                     uint64_t seed, uint64_t elem_offset, void *out, int out_kind,
+                     uint8_t *scratch_codes)
+{
+    quantize_impl(g, n, dtype, 0, 0.0f, e, m, s, rounding, seed, elem_offset, out, out_kind,
+                  scratch_codes);
+}
+
+/* Step 6 (composition): prune, then quantize what pruning returned, with independent words. */
+void orc_prune_quantize(const void *g, uint64_t n, int dtype, float alpha, int e, int m, int s,
+                        int rounding, uint64_t seed, uint64_t elem_offset, void *out, int out_kind,
+                        uint8_t *scratch_codes)
+{
+    quantize_impl(g, n, dtype, 1, alpha, e, m, s, rounding, seed, elem_offset, out, out_kind,
+                  scratch_codes);
+}
+
+void orc_dequantize(const uint8_t *codes, uint64_t n, int e, int m, int s, int dtype, void *out)
+{
+    for (uint64_t i = 0; i < n; ++i) store_elem(out, i, dtype, (float)orc_decode(codes[i], e, m, s));
+}
+
+/* single-element entry points for exhaustive tests */
+uint32_t orc_quantize_one(float x, int e, int m, int s, int rounding, uint32_t w)
+{
+    return quantize_one(x, e, m, s, rounding, w);
+}
+float orc_prune_one(float x, float alpha, uint32_t w) { return prune_one(x, alpha, w); }
