@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the lognormal gradient-compression hot path on one MI355X.
+
+One step = one pass of the whole path over one gradient tensor already resident in HBM:
+
+    lgn_stats -> lgn_threshold -> lgn_fp_params -> lgn_prune_quantize_fused
+
+Workload (default): the ResNet-50-style activation gradient of the benchmark configurations,
+256x256x56x56 = 205 520 896 fp32 elements, 40 % exact zeros, ln|g| ~ N(-13, 2^2) (seeded
+synthetic data standing in for ImageNet gradients); target sparsity 0.85, FP6 with the
+closed-form exponent/mantissa split and quantile scale, stochastic rounding, one byte per code.
+
+Metric: GB/s of ALGORITHMIC bytes = (2 reads of the tensor + 1 write of the codes) / time.
+Prints exactly one JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM traffic of the dominant kernel per launch measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE, scaled by the same counters on a copy kernel of known size); see profiles/.
+# None until measured for the workload at hand.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c4", "c5"])
+    ap.add_argument("--n", type=int, default=None, help="override the element count")
+    ap.add_argument("--out-kind", default="code8", choices=["code8", "packed", "value"])
+    ap.add_argument("--rounding", default="stochastic", choices=["stochastic", "nearest"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="print per-kernel times to stderr")
+    return ap.parse_args()
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (the path needs no communication; "
+                 "see DESIGN.md for how it would shard). Run with --gpus 1.")
+    import numpy as np
+    import torch
+
+    import paper_2006_08173_amd as lgn
+    import synth_inputs as SI
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    lgn.load()
+
+    cfg = {"c1": SI.config_c1, "c2": SI.config_c2, "c4": SI.config_c4, "c5": SI.config_c5}[args.workload]()
+    if args.n:
+        cfg["n"] = args.n
+    n = cfg["n"]
+    sparsity = cfg.get("sparsity", 0.85)
+    n_bits = cfg.get("n_bits", 6)
+    rounding = lgn.LGN_ROUND_STOCHASTIC if args.rounding == "stochastic" else lgn.LGN_ROUND_NEAREST_EVEN
+    out_kind = {"code8": lgn.LGN_OUT_CODE8, "packed": lgn.LGN_OUT_PACKED, "value": lgn.LGN_OUT_VALUE}[args.out_kind]
+    seed = cfg["rng_seed"]
+
+    t0 = time.time()
+    if cfg["dtype"] == SI.F32:
+        d = torch.empty(n, dtype=torch.float32, device="cuda")
+        view = d
+    else:
+        d = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        view = d.view(torch.int16)
+    # generate in slices so host memory stays bounded; upload once
+    step = 1 << 26
+    for s0 in range(0, n, step):
+        part = SI.make(cfg, n=min(step, n - s0), start=s0)
+        if part.dtype == np.uint16:
+            part = part.view(np.int16)
+        view[s0:s0 + part.size].copy_(torch.from_numpy(part))
+    torch.cuda.synchronize()
+    log(f"[bench] generated {n} {cfg['dtype']} elements in {time.time() - t0:.1f}s")
+
+    in_bytes = 4 if cfg["dtype"] == SI.F32 else 2
+    out_bytes_per_elem = {lgn.LGN_OUT_CODE8: 1.0, lgn.LGN_OUT_PACKED: n_bits / 8.0,
+                          lgn.LGN_OUT_VALUE: float(in_bytes)}[out_kind]
+    if out_kind == lgn.LGN_OUT_VALUE:
+        out = torch.empty_like(d)
+    elif out_kind == lgn.LGN_OUT_CODE8:
+        out = torch.empty(n, dtype=torch.uint8, device="cuda")
+    else:
+        out = torch.empty(lgn.lgn_packed_bytes(n, n_bits), dtype=torch.uint8, device="cuda")
+    st = torch.empty(72, dtype=torch.uint8, device="cuda")
+    pp = torch.empty(24, dtype=torch.uint8, device="cuda")
+    fp = torch.empty(32, dtype=torch.uint8, device="cuda")
+    ws = lgn.workspace(d.device)
+
+    def one_step(ev=None):
+        if ev:
+            ev[0].record()
+        lgn.lgn_stats(d, out=st, ws=ws)
+        if ev:
+            ev[1].record()
+        lgn.lgn_threshold(st, sparsity, lgn.LGN_F32 if in_bytes == 4 else lgn.LGN_BF16, out=pp)
+        lgn.lgn_fp_params(st, n_bits, out=fp)
+        if ev:
+            ev[2].record()
+        lgn.lgn_prune_quantize_fused(d, pp, fp, rounding, seed, 0, out=out, out_kind=out_kind)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        one_step(events[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    t_stats = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    t_solve = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    t_fused = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+
+    alg_bytes_step = n * (2 * in_bytes + out_bytes_per_elem)
+    value = alg_bytes_step / (ms_per_step * 1e-3) / 1e9
+    fused_bytes = n * (in_bytes + out_bytes_per_elem)
+    stats_bytes = n * in_bytes
+    fused_gbs = fused_bytes / (t_fused * 1e-3) / 1e9
+    stats_gbs = stats_bytes / (t_stats * 1e-3) / 1e9
+    hp, hf, hs = lgn.read_prune_params(pp), lgn.read_fp_params(fp), lgn.read_stats(st)
+    log(f"[bench] mu={hs.mu:.5f} sigma={hs.sigma:.5f} nnz={hs.nnz} alpha={hp.alpha:.6e} "
+        f"format=1-{hf.e_bits}-{hf.m_bits} s={hf.scale_exp}")
+    log(f"[bench] per step {ms_per_step:.4f} ms: stats {t_stats:.4f} ms ({stats_gbs:.0f} GB/s), "
+        f"solve {t_solve:.4f} ms, fused {t_fused:.4f} ms ({fused_gbs:.0f} GB/s)")
+
+    # dominant kernel = the one that takes longer
+    if t_fused >= t_stats:
+        dom = dict(kernel="stream_kernel (fused prune+quantize)", achieved=fused_gbs,
+                   bytes=fused_bytes, ms=t_fused)
+    else:
+        dom = dict(kernel="stats_stage1", achieved=stats_gbs, bytes=stats_bytes, ms=t_stats)
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, args.out_kind, args.rounding, dom["kernel"]))
+    roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": round(dom["achieved"], 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom["achieved"] / HBM_PEAK_GBS, 4),
+                "traffic": traffic, "algorithmic_bytes": int(dom["bytes"]),
+                "avg_launch_ms": round(dom["ms"], 4),
+                "other_kernels": {"stats_ms": round(t_stats, 4), "stats_GBps": round(stats_gbs, 1),
+                                  "solve_ms": round(t_solve, 4), "fused_ms": round(t_fused, 4),
+                                  "fused_GBps": round(fused_gbs, 1)}}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as O
+        threads = O.max_threads()
+        O.set_threads(threads)
+        m = min(n, 1 << 24)
+        sample = SI.make(cfg, n=m)
+        t1 = time.perf_counter()
+        ost = O.stats(sample)
+        op = O.threshold(ost, sparsity, O.F32 if in_bytes == 4 else O.BF16)
+        of = O.fp_params(ost, n_bits)
+        O.prune_quantize(sample, op.alpha, of.e_bits, of.m_bits, of.scale_exp,
+                         O.ROUND_STOCHASTIC if rounding == lgn.LGN_ROUND_STOCHASTIC else O.ROUND_NEAREST_EVEN,
+                         seed, 0, {lgn.LGN_OUT_CODE8: O.OUT_CODE8, lgn.LGN_OUT_PACKED: O.OUT_PACKED,
+                                   lgn.LGN_OUT_VALUE: O.OUT_VALUE}[out_kind])
+        dt = time.perf_counter() - t1
+        cpu = {"value": round(m * (2 * in_bytes + out_bytes_per_elem) / dt / 1e9, 3), "unit": "GB/s",
+               "cores": threads, "kind": "oracle",
+               "sample": f"first {m} elements of the same tensor, whole chain, {dt:.2f} s"}
+        log(f"[bench] cpu oracle: {cpu}")
+
+    line = {
+        "metric": "GB/s and % HBM peak for fused lognormal-stats+prune+FP-n quantize",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u32" if in_bytes == 4 else "u32(bf16 in)",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: {n} {cfg['dtype']} elements, zeros {cfg['zero_frac']}, "
+                               f"ln|g|~N({cfg['mu']},{cfg['sigma']}^2); stats+threshold(S={sparsity})"
+                               f"+FP{n_bits} format+fused prune/quantize, {args.rounding} rounding, "
+                               f"{args.out_kind} output",
+                   "elements": n, "elements_per_s": round(n / (ms_per_step * 1e-3)),
+                   "algorithmic_bytes_per_step": int(alg_bytes_step),
+                   "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

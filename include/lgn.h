@@ -1,0 +1,212 @@
+/*
+ * lgn.h -- C interface of the MI355X (gfx950) library for on-the-fly compression of neural
+ * gradients after "Neural gradients are near-lognormal: improved quantized and sparse training"
+ * (Chmiel et al., ICLR 2021).
+ *
+ * The path, per gradient tensor g (contiguous, 1-D view, fp32 or bf16):
+ *
+ *   lgn_stats      lognormal parameters: mean and standard deviation of ln|g| over the non-zero
+ *                  entries, plus counts and extrema                      (Section 3)
+ *   lgn_threshold  stochastic-pruning threshold alpha for a target sparsity, from the closed form
+ *                  S(alpha)                                              (Section 5.1-5.2)
+ *   lgn_fp_params  exponent/mantissa split that minimises the expected relative error, and the
+ *                  per-tensor power-of-two gradient scale                (Section 4.2-4.4, Alg. 1)
+ *   lgn_prune      stochastic pruning T_{alpha,eps}                      (Section 5, first equation)
+ *   lgn_fp_quantize  FP(1,e,m) quantization with scale 2^s               (Section 4.1, Alg. 1)
+ *   lgn_prune_quantize_fused   the two operators in one pass
+ *
+ * General rules
+ *   - Every pointer named g, in, out, codes, ws, st, p, f is a DEVICE pointer owned by the
+ *     caller.  The library never allocates, frees or keeps device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues kernels on that stream and returns; nothing synchronises with the host, and the
+ *     parameter structs are read and written on the device, so a whole chain
+ *     stats -> threshold -> fp_params -> fused runs without a host round trip.
+ *   - n is a 64-bit element count; n = 0 is allowed everywhere.
+ *   - Tensor pointers must be 16-byte aligned; CODE8 / PACKED outputs 4-byte aligned.
+ *   - Return value: LGN_OK or a negative LGN_ERR_* code; lgn_last_error() gives the text of the
+ *     last error on the calling thread.  Conditions that depend on the data (empty tensor, zero
+ *     spread, nothing to prune, ...) cannot be reported synchronously and are written to the
+ *     `status` bit field of the device structs.
+ *   - Random words: Philox4x32-10 keyed by `seed`.  Global element j = elem_offset + i draws word
+ *     (j & 3) of the block with counter (lo32(j>>2), hi32(j>>2), purpose, 0), purpose 0 for the
+ *     pruning variable and 1 for stochastic rounding.  Because the counter is the global index,
+ *     processing a tensor in several calls with the matching elem_offset gives the same bits as
+ *     one call.
+ */
+#ifndef LGN_H
+#define LGN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LGN_VERSION 100
+
+/* return codes */
+#define LGN_OK 0
+#define LGN_ERR_INVALID_ARG (-1) /* null pointer, misaligned pointer, value out of range */
+#define LGN_ERR_UNSUPPORTED (-2) /* unknown dtype / enum                                 */
+#define LGN_ERR_WORKSPACE (-3)   /* workspace missing or too small                       */
+#define LGN_ERR_DEVICE (-4)      /* the HIP runtime refused a launch                     */
+
+/* element types */
+#define LGN_F32 0
+#define LGN_BF16 1
+
+/* rounding of the mantissa */
+#define LGN_ROUND_NEAREST_EVEN 0 /* ties to the even FP-n code          */
+#define LGN_ROUND_STOCHASTIC 1   /* up with probability (cut-off part)/(spacing) */
+
+/* what a quantizing call writes */
+#define LGN_OUT_VALUE 0  /* n elements of the input dtype holding 2^s * q                     */
+#define LGN_OUT_CODE8 1  /* n bytes, the N-bit code in the low bits                           */
+#define LGN_OUT_PACKED 2 /* little-endian bit stream, code i at bits [i*N, (i+1)*N),          */
+                         /* lgn_packed_bytes(n, N) bytes, last byte zero padded               */
+
+/* scale rule (Alg. 1 and Appendix "Neural gradients lognormal distributions are truncated") */
+#define LGN_SCALE_QUANTILE 0 /* top binade holds the scale_arg-quantile of the fitted lognormal */
+#define LGN_SCALE_MAX 1      /* top binade holds max|g| (Alg. 1 as printed)                    */
+#define LGN_SCALE_CENTER 2   /* 2^s is the geometric mean: s = round(mu / ln 2)                */
+
+/* how sigma enters the expected relative error (Section 4.2) */
+#define LGN_SIGMA_PAPER_LITERAL 0 /* natural-log sigma used as printed; reproduces Table 2 */
+#define LGN_SIGMA_BASE2 1         /* sigma / ln 2, the spread of log2|g|                   */
+
+/* status bits written to the device structs */
+#define LGN_ST_EMPTY 1u            /* no finite non-zero element: mu, sigma are NaN, alpha = 0 */
+#define LGN_ST_SIGMA0 2u           /* all finite non-zero magnitudes are equal                 */
+#define LGN_ST_NOTHING_TO_PRUNE 4u /* existing zeros already reach the target: alpha = 0       */
+#define LGN_ST_NOT_CONVERGED 8u    /* the threshold solve hit its iteration limit              */
+#define LGN_ST_ALPHA_BELOW_FP_RANGE 16u /* reserved                                           */
+#define LGN_ST_HAS_NONFINITE 32u   /* Inf / NaN entries were seen (and skipped)                */
+
+/* Result of lgn_stats (device memory, 72 bytes, 8-byte aligned). */
+typedef struct lgn_stats_t {
+    uint64_t n;           /* elements scanned                                             */
+    uint64_t nnz;         /* finite non-zero elements                                     */
+    uint64_t n_nonfinite; /* Inf or NaN elements (skipped)                                */
+    double mean_log2;     /* mean of log2|g| over the nnz elements                        */
+    double m2_log2;       /* sum of squared deviations of log2|g| from that mean          */
+    double mu;            /* mean_log2 * ln 2                                             */
+    double sigma;         /* sqrt(m2_log2 / nnz) * ln 2   (population standard deviation) */
+    float max_abs;        /* largest finite |g|, 0 if nnz = 0                             */
+    float min_abs_nz;     /* smallest non-zero finite |g|, 0 if nnz = 0                   */
+    uint32_t status;
+    uint32_t reserved;
+} lgn_stats_t;
+
+/* Result of lgn_threshold (device memory, 24 bytes). */
+typedef struct lgn_prune_params_t {
+    float alpha;     /* threshold, rounded to the tensor dtype; 0 = prune nothing        */
+    uint32_t status;
+    double s_eff;    /* S' = (S n - (n - nnz)) / nnz, sparsity asked of the non-zero part */
+    double s_pred;   /* closed-form sparsity of the non-zero part at the rounded alpha    */
+} lgn_prune_params_t;
+
+/* Result of lgn_fp_params (device memory, 32 bytes). */
+typedef struct lgn_fp_params_t {
+    int32_t n_bits;    /* N = 1 + e_bits + m_bits                                */
+    int32_t e_bits;    /* exponent bits (the paper's n2)                         */
+    int32_t m_bits;    /* mantissa bits (the paper's n1)                         */
+    int32_t scale_exp; /* s: the tensor is quantized as 2^s * Q(g / 2^s)         */
+    double eta;        /* expected relative error of the split                   */
+    uint32_t status;
+    uint32_t reserved;
+} lgn_fp_params_t;
+
+/*
+ * FP(1,e,m) word (Section 4.1, with the encoding choices needed to fit N bits):
+ *   code = sign << (e+m) | c << m | k,   c in [1, 2^e - 1],  value = (1 + k/2^m) 2^(c - 2^(e-1) + s)
+ *   c = 0 encodes zero (whatever k and sign are).  No subnormal, Inf or NaN codes.
+ *   |g| >= 2^(2^(e-1) + s) saturates to the largest code; |g| < 2^(1 - 2^(e-1) + s) flushes to
+ *   zero, decided before rounding.  Zero and NaN inputs give code 0; with VALUE output NaN stays NaN.
+ */
+
+/* Bytes of workspace lgn_stats needs for n elements (a few tens of KiB, independent of n
+ * beyond a cap).  Host function, no device work. */
+size_t lgn_workspace_bytes(uint64_t n, int dtype);
+
+/* Bytes of a PACKED output: ceil(n * n_bits / 8). Host function. */
+size_t lgn_packed_bytes(uint64_t n, int n_bits);
+
+/*
+ * Lognormal statistics of g (Section 3: the fit is made on |g| excluding zero-valued entries;
+ * Appendix "Stochastic pruning complexity": mean and standard deviation, O(n)).
+ *   g        device, n elements of `dtype`, read once
+ *   out      device, one lgn_stats_t, written
+ *   ws       device workspace of at least lgn_workspace_bytes(n, dtype) bytes, 8-byte aligned;
+ *            contents on entry are irrelevant, contents on exit are unspecified
+ * Two launches: per-block partial moments, then a one-block combine.  Logarithms are taken in
+ * base 2 as (exponent field) + log2(mantissa) in fp32, accumulated in fp64 as deviations from a
+ * per-thread pivot and merged pairwise, so the result does not suffer from cancellation.
+ * Errors: INVALID_ARG (null/misaligned), UNSUPPORTED (dtype), WORKSPACE, DEVICE.
+ */
+int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, size_t ws_bytes,
+              void *stream);
+
+/*
+ * Threshold alpha such that stochastic pruning leaves a fraction `target_sparsity` of the WHOLE
+ * tensor at zero (Section 5.1: "find alpha that induces sparsity S"; closed form of Section 5.2;
+ * existing zeros are credited as in Appendix "Algorithm for bi-Modal lognormal pruning", step 2).
+ *   st              device, read
+ *   target_sparsity in [0, 1)
+ *   alpha_dtype     LGN_F32 or LGN_BF16: alpha is rounded to this type (it is compared with,
+ *                   and stored into, tensors of this type)
+ *   out             device, written
+ * One single-wave launch: safeguarded Newton iteration on ln(alpha) in fp64.
+ */
+int lgn_threshold(const lgn_stats_t *st, double target_sparsity, int alpha_dtype,
+                  lgn_prune_params_t *out, void *stream);
+
+/*
+ * FP-n format and scale (Section 4.3: minimise the expected relative error over the splits with
+ * e + m = n_bits - 1; Section 4.4 and Alg. 1: per-tensor power-of-two scale).
+ *   n_bits      total bits N in [2, 8]
+ *   e_bits      exponent bits in [1, N-1], or -1 to take the minimiser
+ *   scale_mode  LGN_SCALE_*;  scale_arg is the quantile (0,1) for LGN_SCALE_QUANTILE (the paper's
+ *               example is 0.997), ignored otherwise
+ *   sigma_units LGN_SIGMA_*
+ * One single-wave launch.
+ */
+int lgn_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode, double scale_arg,
+                  int sigma_units, lgn_fp_params_t *out, void *stream);
+
+/*
+ * Stochastic pruning (Section 5): out_i = g_i if |g_i| > alpha; else sign(g_i) alpha if
+ * |g_i| >= fl32(alpha * u_i); else 0, with u_i = (word >> 8) / 2^24.  Zeros stay zero; NaN and
+ * Inf pass through.  alpha is read from *p on the device (alpha = 0 copies the tensor).
+ *   out   device, n elements of `dtype`; may equal g (in place)
+ */
+int lgn_prune(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p, uint64_t seed,
+              uint64_t elem_offset, void *out, void *stream);
+
+/*
+ * FP(1,e,m) quantization with scale 2^s (Section 4.1; Alg. 1 last line).  (N, e, m, s) are read
+ * from *f on the device; the caller sizes a PACKED output with the N it asked lgn_fp_params for.
+ *   rounding  LGN_ROUND_*; stochastic rounding draws the purpose-1 word of each element
+ *   out       device; layout per out_kind (VALUE may be in place)
+ */
+int lgn_fp_quantize(const void *g, uint64_t n, int dtype, const lgn_fp_params_t *f, int rounding,
+                    uint64_t seed, uint64_t elem_offset, void *out, int out_kind, void *stream);
+
+/* Prune, then quantize what pruning returned, in one pass over g; bit-identical to
+ * lgn_fp_quantize(lgn_prune(g)) with the same seed and offset. */
+int lgn_prune_quantize_fused(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p,
+                             const lgn_fp_params_t *f, int rounding, uint64_t seed,
+                             uint64_t elem_offset, void *out, int out_kind, void *stream);
+
+/* Decode CODE8 or PACKED codes back to values 2^s * q of type `dtype`. */
+int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f, int dtype,
+                   void *out, void *stream);
+
+const char *lgn_last_error(void);
+int lgn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LGN_H */

@@ -1,0 +1,263 @@
+"""ctypes binding of `liblgn.so` (C interface: include/lgn.h).
+
+Argument marshalling only.  Tensors are torch CUDA tensors (device memory), the parameter
+structs live in device memory as small uint8 tensors, and every call is enqueued on torch's
+current stream.  There is no CPU fallback: if the HIP library cannot be loaded the import of a
+symbol fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+# ---- constants of include/lgn.h ---------------------------------------------------------------
+LGN_OK = 0
+LGN_ERR_INVALID_ARG, LGN_ERR_UNSUPPORTED, LGN_ERR_WORKSPACE, LGN_ERR_DEVICE = -1, -2, -3, -4
+LGN_F32, LGN_BF16 = 0, 1
+LGN_ROUND_NEAREST_EVEN, LGN_ROUND_STOCHASTIC = 0, 1
+LGN_OUT_VALUE, LGN_OUT_CODE8, LGN_OUT_PACKED = 0, 1, 2
+LGN_SCALE_QUANTILE, LGN_SCALE_MAX, LGN_SCALE_CENTER = 0, 1, 2
+LGN_SIGMA_PAPER_LITERAL, LGN_SIGMA_BASE2 = 0, 1
+LGN_ST_EMPTY, LGN_ST_SIGMA0, LGN_ST_NOTHING_TO_PRUNE, LGN_ST_NOT_CONVERGED = 1, 2, 4, 8
+LGN_ST_ALPHA_BELOW_FP_RANGE, LGN_ST_HAS_NONFINITE = 16, 32
+
+
+class LgnStats(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("nnz", C.c_uint64), ("n_nonfinite", C.c_uint64),
+                ("mean_log2", C.c_double), ("m2_log2", C.c_double),
+                ("mu", C.c_double), ("sigma", C.c_double),
+                ("max_abs", C.c_float), ("min_abs_nz", C.c_float),
+                ("status", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class LgnPruneParams(C.Structure):
+    _fields_ = [("alpha", C.c_float), ("status", C.c_uint32),
+                ("s_eff", C.c_double), ("s_pred", C.c_double)]
+
+
+class LgnFpParams(C.Structure):
+    _fields_ = [("n_bits", C.c_int32), ("e_bits", C.c_int32), ("m_bits", C.c_int32),
+                ("scale_exp", C.c_int32), ("eta", C.c_double),
+                ("status", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+assert C.sizeof(LgnStats) == 72 and C.sizeof(LgnPruneParams) == 24 and C.sizeof(LgnFpParams) == 32
+
+
+class LgnError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"lgn error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshold",
+           "lgn_fp_params", "lgn_prune", "lgn_fp_quantize", "lgn_prune_quantize_fused",
+           "lgn_dequantize", "lgn_last_error", "lgn_version")
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load liblgn.so (building it first if it was never built).  Raises if that fails."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build(force=True)
+    L = C.CDLL(_build.LIB)
+    vp, u64, i32, dbl, sz = C.c_void_p, C.c_uint64, C.c_int, C.c_double, C.c_size_t
+    L.lgn_workspace_bytes.argtypes = [u64, i32]
+    L.lgn_workspace_bytes.restype = sz
+    L.lgn_packed_bytes.argtypes = [u64, i32]
+    L.lgn_packed_bytes.restype = sz
+    L.lgn_stats.argtypes = [vp, u64, i32, vp, vp, sz, vp]
+    L.lgn_threshold.argtypes = [vp, dbl, i32, vp, vp]
+    L.lgn_fp_params.argtypes = [vp, i32, i32, i32, dbl, i32, vp, vp]
+    L.lgn_prune.argtypes = [vp, u64, i32, vp, u64, u64, vp, vp]
+    L.lgn_fp_quantize.argtypes = [vp, u64, i32, vp, i32, u64, u64, vp, i32, vp]
+    L.lgn_prune_quantize_fused.argtypes = [vp, u64, i32, vp, vp, i32, u64, u64, vp, i32, vp]
+    L.lgn_dequantize.argtypes = [vp, u64, i32, vp, i32, vp, vp]
+    L.lgn_last_error.restype = C.c_char_p
+    L.lgn_version.restype = i32
+    for name in EXPORTS[2:9]:
+        getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != LGN_OK:
+        raise LgnError(rc, load().lgn_last_error().decode())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor, dtype=None) -> int:
+    if dtype is not None:
+        return int(dtype)
+    if t.dtype == torch.float32:
+        return LGN_F32
+    if t.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        return LGN_BF16  # 16-bit integer tensors are taken as bf16 bit patterns
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _flat(t: torch.Tensor) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError("tensors must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    return t
+
+
+def _struct_buf(size, device):
+    return torch.empty(size, dtype=torch.uint8, device=device)
+
+
+_ws_cache = {}
+
+
+def workspace(device) -> torch.Tensor:
+    """Per-device scratch tensor for lgn_stats (allocated once by torch)."""
+    key = torch.device(device).index if torch.device(device).index is not None else torch.cuda.current_device()
+    ws = _ws_cache.get(key)
+    if ws is None:
+        ws = torch.empty(lgn_workspace_bytes(0, LGN_F32), dtype=torch.uint8, device=f"cuda:{key}")
+        _ws_cache[key] = ws
+    return ws
+
+
+# ---- same names as the C interface ------------------------------------------------------------
+def lgn_version() -> int:
+    return int(load().lgn_version())
+
+
+def lgn_workspace_bytes(n: int, dtype: int) -> int:
+    return int(load().lgn_workspace_bytes(int(n), int(dtype)))
+
+
+def lgn_packed_bytes(n: int, n_bits: int) -> int:
+    return int(load().lgn_packed_bytes(int(n), int(n_bits)))
+
+
+def lgn_stats(g: torch.Tensor, out: torch.Tensor = None, ws: torch.Tensor = None, dtype=None) -> torch.Tensor:
+    g = _flat(g)
+    if out is None:
+        out = _struct_buf(C.sizeof(LgnStats), g.device)
+    if ws is None:
+        ws = workspace(g.device)
+    _check(load().lgn_stats(g.data_ptr(), g.numel(), _dtype_code(g, dtype), out.data_ptr(),
+                            ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def lgn_threshold(st: torch.Tensor, target_sparsity: float, alpha_dtype: int = LGN_F32,
+                  out: torch.Tensor = None) -> torch.Tensor:
+    if out is None:
+        out = _struct_buf(C.sizeof(LgnPruneParams), st.device)
+    _check(load().lgn_threshold(st.data_ptr(), float(target_sparsity), int(alpha_dtype),
+                                out.data_ptr(), _stream()))
+    return out
+
+
+def lgn_fp_params(st: torch.Tensor, n_bits: int, e_bits: int = -1,
+                  scale_mode: int = LGN_SCALE_QUANTILE, scale_arg: float = 0.997,
+                  sigma_units: int = LGN_SIGMA_PAPER_LITERAL, out: torch.Tensor = None) -> torch.Tensor:
+    if out is None:
+        out = _struct_buf(C.sizeof(LgnFpParams), st.device)
+    _check(load().lgn_fp_params(st.data_ptr(), int(n_bits), int(e_bits), int(scale_mode),
+                                float(scale_arg), int(sigma_units), out.data_ptr(), _stream()))
+    return out
+
+
+def lgn_prune(g: torch.Tensor, p: torch.Tensor, seed: int, elem_offset: int = 0,
+              out: torch.Tensor = None, dtype=None) -> torch.Tensor:
+    g = _flat(g)
+    if out is None:
+        out = torch.empty_like(g)
+    _check(load().lgn_prune(g.data_ptr(), g.numel(), _dtype_code(g, dtype), p.data_ptr(),
+                            int(seed), int(elem_offset), out.data_ptr(), _stream()))
+    return out
+
+
+def _alloc_quant_out(g, out_kind, n_bits):
+    if out_kind == LGN_OUT_VALUE:
+        return torch.empty_like(g)
+    if out_kind == LGN_OUT_CODE8:
+        return torch.empty(g.numel(), dtype=torch.uint8, device=g.device)
+    if n_bits is None:
+        raise ValueError("n_bits is needed to size a PACKED output")
+    # rounded up to whole dwords so the tensor start and size stay 4-byte friendly
+    nbytes = lgn_packed_bytes(g.numel(), n_bits)
+    return torch.empty(nbytes, dtype=torch.uint8, device=g.device)
+
+
+def lgn_fp_quantize(g: torch.Tensor, f: torch.Tensor, rounding: int = LGN_ROUND_NEAREST_EVEN,
+                    seed: int = 0, elem_offset: int = 0, out: torch.Tensor = None,
+                    out_kind: int = LGN_OUT_VALUE, n_bits: int = None, dtype=None) -> torch.Tensor:
+    g = _flat(g)
+    if out is None:
+        out = _alloc_quant_out(g, out_kind, n_bits)
+    _check(load().lgn_fp_quantize(g.data_ptr(), g.numel(), _dtype_code(g, dtype), f.data_ptr(),
+                                  int(rounding), int(seed), int(elem_offset), out.data_ptr(),
+                                  int(out_kind), _stream()))
+    return out
+
+
+def lgn_prune_quantize_fused(g: torch.Tensor, p: torch.Tensor, f: torch.Tensor,
+                             rounding: int = LGN_ROUND_NEAREST_EVEN, seed: int = 0,
+                             elem_offset: int = 0, out: torch.Tensor = None,
+                             out_kind: int = LGN_OUT_VALUE, n_bits: int = None, dtype=None) -> torch.Tensor:
+    g = _flat(g)
+    if out is None:
+        out = _alloc_quant_out(g, out_kind, n_bits)
+    _check(load().lgn_prune_quantize_fused(g.data_ptr(), g.numel(), _dtype_code(g, dtype),
+                                           p.data_ptr(), f.data_ptr(), int(rounding), int(seed),
+                                           int(elem_offset), out.data_ptr(), int(out_kind),
+                                           _stream()))
+    return out
+
+
+def lgn_dequantize(codes: torch.Tensor, n: int, in_kind: int, f: torch.Tensor,
+                   dtype: int = LGN_F32, out: torch.Tensor = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(int(n), dtype=torch.float32 if dtype == LGN_F32 else torch.bfloat16,
+                          device=codes.device)
+    _check(load().lgn_dequantize(codes.data_ptr(), int(n), int(in_kind), f.data_ptr(), int(dtype),
+                                 out.data_ptr(), _stream()))
+    return out
+
+
+# ---- moving the small structs between host and device (tests, logging) ------------------------
+def _read(buf: torch.Tensor, cls):
+    raw = bytes(buf.cpu().numpy().tobytes())  # synchronises with the stream that wrote it
+    return cls.from_buffer_copy(raw)
+
+
+def read_stats(buf: torch.Tensor) -> LgnStats:
+    return _read(buf, LgnStats)
+
+
+def read_prune_params(buf: torch.Tensor) -> LgnPruneParams:
+    return _read(buf, LgnPruneParams)
+
+
+def read_fp_params(buf: torch.Tensor) -> LgnFpParams:
+    return _read(buf, LgnFpParams)
+
+
+def upload_struct(s: C.Structure, device="cuda") -> torch.Tensor:
+    """Copy a host-side struct into a fresh device buffer (to feed hand-made parameters)."""
+    import numpy as np
+    arr = np.frombuffer(bytes(s), dtype=np.uint8).copy()
+    return torch.from_numpy(arr).to(device)

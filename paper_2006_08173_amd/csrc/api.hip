@@ -1,0 +1,200 @@
+// C interface of the library (see include/lgn.h): argument checks and kernel launches only.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "lgn_device.hpp"
+
+namespace lgn {
+struct StreamArgs {
+    const void *g;
+    void *out;
+    uint64_t n;
+    uint64_t elem_offset;
+    const lgn_prune_params_t *p;
+    const lgn_fp_params_t *f;
+    uint32_t k0, k1;
+};
+hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws,
+                        hipStream_t stream);
+size_t stats_workspace_bytes();
+hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
+                            lgn_prune_params_t *out, hipStream_t stream);
+hipError_t launch_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
+                            double scale_arg, int sigma_units, lgn_fp_params_t *out,
+                            hipStream_t stream);
+hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int out_kind,
+                         const StreamArgs &args, int max_blocks, hipStream_t stream);
+hipError_t launch_dequant(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f,
+                          int dtype, void *out, hipStream_t stream);
+}  // namespace lgn
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int device_fail(const char *what, hipError_t e)
+{
+    return fail(LGN_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool dtype_ok(int d) { return d == LGN_F32 || d == LGN_BF16; }
+
+// Workgroups of a streaming launch: enough waves to fill every SIMD eight deep.
+int stream_blocks()
+{
+    static int cached = 0;
+    if (cached) return cached;
+    int per_cu = 8;
+    if (const char *e = getenv("LGN_STREAM_BLOCKS_PER_CU")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= 64) per_cu = v;
+    }
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+    }
+    cached = cus * per_cu;
+    return cached;
+}
+
+int check_stream_common(const void *g, uint64_t n, int dtype, const void *out, int out_kind)
+{
+    if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (out_kind != LGN_OUT_VALUE && out_kind != LGN_OUT_CODE8 && out_kind != LGN_OUT_PACKED)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown out_kind %d", out_kind);
+    if (n == 0) return LGN_OK;
+    if (!g || !out) return fail(LGN_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned(g, 16)) return fail(LGN_ERR_INVALID_ARG, "input tensor not 16-byte aligned");
+    if (!aligned(out, out_kind == LGN_OUT_VALUE ? 16 : 4))
+        return fail(LGN_ERR_INVALID_ARG, "output not %d-byte aligned", out_kind == LGN_OUT_VALUE ? 16 : 4);
+    if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
+    return LGN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lgn_workspace_bytes(uint64_t, int) { return lgn::stats_workspace_bytes(); }
+
+size_t lgn_packed_bytes(uint64_t n, int n_bits) { return (size_t)((n * (uint64_t)n_bits + 7) / 8); }
+
+const char *lgn_last_error(void) { return g_err; }
+
+int lgn_version(void) { return LGN_VERSION; }
+
+int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, size_t ws_bytes,
+              void *stream)
+{
+    if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (!out) return fail(LGN_ERR_INVALID_ARG, "null stats pointer");
+    if (!aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "stats struct not 8-byte aligned");
+    if (n && !g) return fail(LGN_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned(g, 16)) return fail(LGN_ERR_INVALID_ARG, "input tensor not 16-byte aligned");
+    if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
+    if (!ws || ws_bytes < lgn_workspace_bytes(n, dtype))
+        return fail(LGN_ERR_WORKSPACE, "workspace missing or smaller than %zu bytes",
+                    lgn_workspace_bytes(n, dtype));
+    if (!aligned(ws, 8)) return fail(LGN_ERR_WORKSPACE, "workspace not 8-byte aligned");
+    const hipError_t e = lgn::launch_stats(g, n, dtype, out, ws, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_stats", e);
+}
+
+int lgn_threshold(const lgn_stats_t *st, double target_sparsity, int alpha_dtype,
+                  lgn_prune_params_t *out, void *stream)
+{
+    if (!st || !out) return fail(LGN_ERR_INVALID_ARG, "null struct pointer");
+    if (!aligned(st, 8) || !aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "struct not 8-byte aligned");
+    if (!dtype_ok(alpha_dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown alpha dtype %d", alpha_dtype);
+    if (!(target_sparsity >= 0.0 && target_sparsity < 1.0))
+        return fail(LGN_ERR_INVALID_ARG, "target sparsity %g outside [0, 1)", target_sparsity);
+    const hipError_t e = lgn::launch_threshold(st, target_sparsity, alpha_dtype, out,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_threshold", e);
+}
+
+int lgn_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode, double scale_arg,
+                  int sigma_units, lgn_fp_params_t *out, void *stream)
+{
+    if (!st || !out) return fail(LGN_ERR_INVALID_ARG, "null struct pointer");
+    if (!aligned(st, 8) || !aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "struct not 8-byte aligned");
+    if (n_bits < 2 || n_bits > 8) return fail(LGN_ERR_INVALID_ARG, "n_bits %d outside [2, 8]", n_bits);
+    if (e_bits != -1 && (e_bits < 1 || e_bits > n_bits - 1))
+        return fail(LGN_ERR_INVALID_ARG, "e_bits %d outside [1, %d]", e_bits, n_bits - 1);
+    if (scale_mode != LGN_SCALE_QUANTILE && scale_mode != LGN_SCALE_MAX && scale_mode != LGN_SCALE_CENTER)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown scale mode %d", scale_mode);
+    if (scale_mode == LGN_SCALE_QUANTILE && !(scale_arg > 0.0 && scale_arg < 1.0))
+        return fail(LGN_ERR_INVALID_ARG, "quantile %g outside (0, 1)", scale_arg);
+    if (sigma_units != LGN_SIGMA_PAPER_LITERAL && sigma_units != LGN_SIGMA_BASE2)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown sigma units %d", sigma_units);
+    const hipError_t e = lgn::launch_fp_params(st, n_bits, e_bits, scale_mode, scale_arg,
+                                               sigma_units, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_fp_params", e);
+}
+
+int lgn_prune(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p, uint64_t seed,
+              uint64_t elem_offset, void *out, void *stream)
+{
+    if (int rc = check_stream_common(g, n, dtype, out, LGN_OUT_VALUE)) return rc;
+    if (!p) return fail(LGN_ERR_INVALID_ARG, "null prune params");
+    lgn::StreamArgs a = {g, out, n, elem_offset, p, nullptr, (uint32_t)seed, (uint32_t)(seed >> 32)};
+    const hipError_t e = lgn::launch_stream(dtype, true, false, 0, LGN_OUT_VALUE, a, stream_blocks(),
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_prune", e);
+}
+
+int lgn_fp_quantize(const void *g, uint64_t n, int dtype, const lgn_fp_params_t *f, int rounding,
+                    uint64_t seed, uint64_t elem_offset, void *out, int out_kind, void *stream)
+{
+    if (int rc = check_stream_common(g, n, dtype, out, out_kind)) return rc;
+    if (!f) return fail(LGN_ERR_INVALID_ARG, "null fp params");
+    if (rounding != LGN_ROUND_NEAREST_EVEN && rounding != LGN_ROUND_STOCHASTIC)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown rounding %d", rounding);
+    lgn::StreamArgs a = {g, out, n, elem_offset, nullptr, f, (uint32_t)seed, (uint32_t)(seed >> 32)};
+    const hipError_t e = lgn::launch_stream(dtype, false, true, rounding, out_kind, a,
+                                            stream_blocks(), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_fp_quantize", e);
+}
+
+int lgn_prune_quantize_fused(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p,
+                             const lgn_fp_params_t *f, int rounding, uint64_t seed,
+                             uint64_t elem_offset, void *out, int out_kind, void *stream)
+{
+    if (int rc = check_stream_common(g, n, dtype, out, out_kind)) return rc;
+    if (!p || !f) return fail(LGN_ERR_INVALID_ARG, "null params");
+    if (rounding != LGN_ROUND_NEAREST_EVEN && rounding != LGN_ROUND_STOCHASTIC)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown rounding %d", rounding);
+    lgn::StreamArgs a = {g, out, n, elem_offset, p, f, (uint32_t)seed, (uint32_t)(seed >> 32)};
+    const hipError_t e = lgn::launch_stream(dtype, true, true, rounding, out_kind, a,
+                                            stream_blocks(), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_prune_quantize_fused", e);
+}
+
+int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f, int dtype,
+                   void *out, void *stream)
+{
+    if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (in_kind != LGN_OUT_CODE8 && in_kind != LGN_OUT_PACKED)
+        return fail(LGN_ERR_UNSUPPORTED, "codes must be CODE8 or PACKED");
+    if (n == 0) return LGN_OK;
+    if (!codes || !out || !f) return fail(LGN_ERR_INVALID_ARG, "null pointer");
+    const hipError_t e = lgn::launch_dequant(codes, n, in_kind, f, dtype, out,
+                                             static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_dequantize", e);
+}
+
+}  // extern "C"

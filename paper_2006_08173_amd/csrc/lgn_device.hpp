@@ -1,0 +1,107 @@
+// Device-side helpers shared by the HIP kernels of the lognormal gradient-compression library
+// (gfx950 / CDNA4, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lgn.h"
+
+namespace lgn {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;            // threads per workgroup (4 waves, one per SIMD)
+constexpr int kMaxStatsBlocks = 2048;  // cap of stage-1 partials (fills 256 CUs x 8 waves/SIMD)
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  One block = four 32-bit words.  The multiplications are
+// written as 64-bit products so the compiler emits one v_mad_u64_u32 per product (both halves).
+// The key schedule depends only on the seed and is therefore wave-uniform (scalar registers).
+// ---------------------------------------------------------------------------------------------
+struct PhiloxKey {
+    uint32_t k0, k1;
+};
+
+__device__ __forceinline__ void philox_round(uint32_t &c0, uint32_t &c1, uint32_t &c2, uint32_t &c3,
+                                             uint32_t k0, uint32_t k1)
+{
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+}
+
+// Words of the block with counter (lo32(q), hi32(q), purpose, 0).
+__device__ __forceinline__ void philox_block(uint64_t q, uint32_t purpose, PhiloxKey key,
+                                             uint32_t w[4])
+{
+    uint32_t c0 = (uint32_t)q, c1 = (uint32_t)(q >> 32), c2 = purpose, c3 = 0u;
+    uint32_t k0 = key.k0, k1 = key.k1;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        philox_round(c0, c1, c2, c3, k0, k1);
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    w[0] = c0;
+    w[1] = c1;
+    w[2] = c2;
+    w[3] = c3;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Element access.  A "quad" is four consecutive elements: 16 bytes of fp32 or 8 bytes of bf16.
+// Elements are handled as fp32 bit patterns (bf16 widens exactly by a 16-bit shift), so nothing
+// below depends on the floating-point mode of the device.
+// ---------------------------------------------------------------------------------------------
+template <int DTYPE>
+__device__ __forceinline__ void load_quad(const void *g, uint64_t quad, uint32_t b[4])
+{
+    if (DTYPE == LGN_F32) {
+        const uint4 v = reinterpret_cast<const uint4 *>(g)[quad];
+        b[0] = v.x; b[1] = v.y; b[2] = v.z; b[3] = v.w;
+    } else {
+        const uint2 v = reinterpret_cast<const uint2 *>(g)[quad];
+        b[0] = v.x << 16; b[1] = v.x & 0xffff0000u; b[2] = v.y << 16; b[3] = v.y & 0xffff0000u;
+    }
+}
+
+template <int DTYPE>
+__device__ __forceinline__ uint32_t load_elem(const void *g, uint64_t i)
+{
+    if (DTYPE == LGN_F32) return reinterpret_cast<const uint32_t *>(g)[i];
+    return (uint32_t) reinterpret_cast<const uint16_t *>(g)[i] << 16;
+}
+
+// fp32 pattern -> bf16 pattern in the upper half, round to nearest even.  Everything the kernels
+// store is exactly representable in bf16 (a no-op then) except a saturated value whose scale puts
+// it below the bf16 subnormal range.
+__device__ __forceinline__ uint32_t bf16_round_hi(uint32_t b)
+{
+    return (b + 0x7fffu + ((b >> 16) & 1u)) & 0xffff0000u;
+}
+
+template <int DTYPE>
+__device__ __forceinline__ void store_quad(void *out, uint64_t quad, const uint32_t b[4])
+{
+    if (DTYPE == LGN_F32) {
+        reinterpret_cast<uint4 *>(out)[quad] = make_uint4(b[0], b[1], b[2], b[3]);
+    } else {
+        reinterpret_cast<uint2 *>(out)[quad] =
+            make_uint2((bf16_round_hi(b[0]) >> 16) | bf16_round_hi(b[1]),
+                       (bf16_round_hi(b[2]) >> 16) | bf16_round_hi(b[3]));
+    }
+}
+
+template <int DTYPE>
+__device__ __forceinline__ void store_elem(void *out, uint64_t i, uint32_t b)
+{
+    if (DTYPE == LGN_F32) reinterpret_cast<uint32_t *>(out)[i] = b;
+    else reinterpret_cast<uint16_t *>(out)[i] = (uint16_t)(bf16_round_hi(b) >> 16);
+}
+
+}  // namespace lgn

@@ -1,0 +1,331 @@
+// The streaming operators: stochastic pruning T_{alpha,eps} (Section 5, first equation), the
+// FP(1,e,m) quantizer with power-of-two scale (Section 4.1; Alg. 1), and both in one pass.
+//
+// One kernel template covers prune-only, quantize-only and the fused pass.  A wave owns tiles of
+// 256 consecutive elements; lane l owns elements 4l..4l+3 of the tile, i.e. exactly one Philox
+// block per purpose, one 16-byte load (fp32) and one 16-byte / 4-byte store.  Everything is
+// integer work on fp32 bit patterns (bf16 widens by a shift), except the one single-precision
+// product alpha * u that the pruning rule is defined with.
+//
+// PACKED output: the four N-bit codes of a lane form a 4N-bit chunk; the 64 chunks of a tile are
+// one contiguous run of 8N dwords.  Lane k < 8N assembles dword k from the (at most five) chunks
+// that overlap it, fetched with cross-lane reads, and the wave stores 8N consecutive dwords.
+#include "lgn_device.hpp"
+
+namespace lgn {
+
+struct StreamArgs {
+    const void *g;
+    void *out;
+    uint64_t n;
+    uint64_t elem_offset;
+    const lgn_prune_params_t *p;
+    const lgn_fp_params_t *f;
+    uint32_t k0, k1;
+};
+
+// wave-uniform quantizer constants
+struct QuantConst {
+    int n_bits, e, m, s;
+    int cbias;        // biased fp32 exponent that maps to exponent field 0
+    int cmax;         // largest exponent field, 2^e - 1
+    uint32_t maxmag;  // largest magnitude code, 2^(e+m) - 1
+};
+
+// Reads the format from device memory.  The fields are clamped to their legal ranges so that a
+// struct that was never filled in cannot cause out-of-range shifts; sizing a PACKED output for
+// the n_bits in the struct stays the caller's contract.
+__device__ __forceinline__ void load_quant_const(const lgn_fp_params_t *f, QuantConst &q)
+{
+    q.n_bits = min(max(f->n_bits, 2), 8);
+    q.e = min(max(f->e_bits, 1), q.n_bits - 1);
+    q.m = q.n_bits - 1 - q.e;
+    q.s = min(max(f->scale_exp, -400), 400);
+    q.cbias = 127 + q.s - (1 << (q.e - 1));
+    q.cmax = (1 << q.e) - 1;
+    q.maxmag = (1u << (q.e + q.m)) - 1u;
+}
+
+// Words of the four elements j0..j0+3 for a purpose; j0 need not be a multiple of four.
+__device__ __forceinline__ void quad_words(uint64_t j0, uint32_t purpose, PhiloxKey key,
+                                           uint32_t w[4])
+{
+    const uint32_t r = (uint32_t)j0 & 3u;  // wave-uniform: tiles start at multiples of four
+    uint32_t a[4];
+    philox_block(j0 >> 2, purpose, key, a);
+    if (r == 0u) {
+        w[0] = a[0]; w[1] = a[1]; w[2] = a[2]; w[3] = a[3];
+    } else {
+        uint32_t b[4];
+        philox_block((j0 >> 2) + 1, purpose, key, b);
+        if (r == 1u) { w[0] = a[1]; w[1] = a[2]; w[2] = a[3]; w[3] = b[0]; }
+        else if (r == 2u) { w[0] = a[2]; w[1] = a[3]; w[2] = b[0]; w[3] = b[1]; }
+        else { w[0] = a[3]; w[1] = b[0]; w[2] = b[1]; w[3] = b[2]; }
+    }
+}
+
+// T_{alpha,u}: |x| > alpha keeps x; |x| < fl32(alpha u) gives 0; otherwise sign(x) alpha.
+// Zero stays (+)zero for every u; NaN and Inf compare above any finite alpha and pass.
+__device__ __forceinline__ uint32_t prune_bits(uint32_t bits, uint32_t w, uint32_t alpha_bits,
+                                               float alpha)
+{
+    const uint32_t a = bits & 0x7fffffffu;
+    const float u = (float)(w >> 8) * 0x1p-24f;        // exact
+    const uint32_t t = __float_as_uint(alpha * u);     // one rounding
+    const uint32_t small = (a < t || a == 0u) ? 0u : (alpha_bits | (bits & 0x80000000u));
+    return a > alpha_bits ? bits : small;
+}
+
+// Magnitude-and-sign code of one element (Section 4.1 with the N-bit encoding of the header).
+template <int ROUND>
+__device__ __forceinline__ uint32_t quant_code(uint32_t bits, uint32_t w, const QuantConst &q)
+{
+    const uint32_t a = bits & 0x7fffffffu;
+    uint32_t frac = a & 0x7fffffu;
+    int be = (int)(a >> 23);
+    if (be == 0 && frac != 0u) {  // subnormal input: normalise with integer ops
+        const int sh = __clz(frac) - 8;
+        frac = (frac << sh) & 0x7fffffu;
+        be = 1 - sh;
+    }
+    const int c = be - q.cbias;
+    const int cut = 23 - q.m;
+    const uint32_t y = ((uint32_t)c << 23) | frac;  // meaningful only when 1 <= c <= cmax
+    uint32_t mag = y >> cut;
+    const uint32_t rem = y & ((1u << cut) - 1u);
+    bool up;
+    if (ROUND == LGN_ROUND_STOCHASTIC) {
+        up = rem + (w >> (9 + q.m)) >= (1u << cut);
+    } else {
+        const uint32_t half = 1u << (cut - 1);
+        up = rem > half || (rem == half && (mag & 1u));
+    }
+    mag += up ? 1u : 0u;
+    mag = min(mag, q.maxmag);                        // carry out of the top binade saturates
+    if (c > q.cmax || a == 0x7f800000u) mag = q.maxmag;
+    if (c < 1 || a == 0u || a > 0x7f800000u) return 0u;  // flush (before rounding), zero, NaN
+    return ((bits >> 31) << (q.e + q.m)) | mag;
+}
+
+// fp32 bit pattern of 2^s * (value of code); NaN inputs are passed through by the caller.
+__device__ __forceinline__ uint32_t code_value_bits(uint32_t code, const QuantConst &q)
+{
+    const uint32_t mag = code & q.maxmag;
+    const uint32_t c = mag >> q.m;
+    if (c == 0u) return 0u;
+    const uint32_t k = mag & ((1u << q.m) - 1u);
+    const uint32_t sign = (code >> (q.e + q.m)) << 31;
+    const int ef = (int)c + q.cbias;  // biased fp32 exponent of the result
+    const uint32_t mant = k << (23 - q.m);
+    if (ef >= 255) return sign | 0x7f800000u;
+    if (ef >= 1) return sign | ((uint32_t)ef << 23) | mant;
+    const int sh = 1 - ef;  // result is subnormal in fp32
+    return sh > 24 ? sign : sign | ((0x800000u | mant) >> sh);
+}
+
+template <int N>
+__device__ __forceinline__ void pack_store(uint32_t chunk, uint8_t *tile_out, uint64_t bytes_valid)
+{
+    constexpr int CB = 4 * N;  // bits per lane chunk
+    constexpr int ND = 8 * N;  // dwords per 256-element tile
+    constexpr int T = (CB - 1 + 32 + CB - 1) / CB;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int bit = 32 * lane;
+    const int c0 = bit / CB, sh = bit - c0 * CB;
+    uint64_t acc = 0;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const uint32_t v = __shfl(chunk, (c0 + t) & (kWave - 1));
+        if (c0 + t < kWave && t * CB < 64) acc |= (uint64_t)v << (t * CB);
+    }
+    const uint32_t dword = (uint32_t)(acc >> sh);
+    if (lane < ND) {
+        const uint64_t byte = 4ull * lane;
+        if (byte + 4 <= bytes_valid) {
+            reinterpret_cast<uint32_t *>(tile_out)[lane] = dword;
+        } else {
+            for (uint64_t b = byte; b < bytes_valid; ++b)
+                tile_out[b] = (uint8_t)(dword >> (8 * (b - byte)));
+        }
+    }
+}
+
+__device__ __forceinline__ void pack_store_n(int n_bits, uint32_t chunk, uint8_t *tile_out,
+                                             uint64_t bytes_valid)
+{
+    switch (n_bits) {  // wave-uniform
+    case 2: pack_store<2>(chunk, tile_out, bytes_valid); break;
+    case 3: pack_store<3>(chunk, tile_out, bytes_valid); break;
+    case 4: pack_store<4>(chunk, tile_out, bytes_valid); break;
+    case 5: pack_store<5>(chunk, tile_out, bytes_valid); break;
+    case 6: pack_store<6>(chunk, tile_out, bytes_valid); break;
+    case 7: pack_store<7>(chunk, tile_out, bytes_valid); break;
+    default: pack_store<8>(chunk, tile_out, bytes_valid); break;
+    }
+}
+
+template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
+__global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
+{
+    const PhiloxKey key = {a.k0, a.k1};
+    float alpha = 0.0f;
+    if (PRUNE) alpha = a.p->alpha;
+    const uint32_t alpha_bits = __float_as_uint(alpha);
+    QuantConst q = {8, 1, 6, 0, 0, 1, 255u};
+    if (QUANT) {
+        load_quant_const(a.f, q);
+    }
+    const uint64_t n = a.n;
+    const uint64_t ntiles = (n + 255) / 256;
+    const uint64_t nwaves = (uint64_t)gridDim.x * (kBlock / kWave);
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t wave = (uint64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const uint64_t packed_total = (n * (uint64_t)q.n_bits + 7) / 8;
+
+    for (uint64_t tile = wave; tile < ntiles; tile += nwaves) {
+        const uint64_t quad = tile * kWave + lane;  // index of this lane's four elements
+        const uint64_t i0 = quad * 4;
+        const bool full = (tile + 1) * 256 <= n;    // wave-uniform
+        uint32_t b[4];
+        if (full) {
+            load_quad<DTYPE>(a.g, quad, b);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) b[t] = i0 + t < n ? load_elem<DTYPE>(a.g, i0 + t) : 0u;
+        }
+        const uint64_t j0 = a.elem_offset + i0;
+        if (PRUNE && alpha_bits != 0u) {
+            uint32_t w[4];
+            quad_words(j0, 0u, key, w);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) b[t] = prune_bits(b[t], w[t], alpha_bits, alpha);
+        } else if (PRUNE) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) b[t] = (b[t] & 0x7fffffffu) ? b[t] : 0u;
+        }
+        if (!QUANT) {
+            if (full) {
+                store_quad<DTYPE>(a.out, quad, b);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (i0 + t < n) store_elem<DTYPE>(a.out, i0 + t, b[t]);
+            }
+            continue;
+        }
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (ROUND == LGN_ROUND_STOCHASTIC) quad_words(j0, 1u, key, w);
+        uint32_t code[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) code[t] = quant_code<ROUND>(b[t], w[t], q);
+        if (OUT == LGN_OUT_VALUE) {
+            uint32_t v[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                v[t] = (b[t] & 0x7fffffffu) > 0x7f800000u ? b[t] : code_value_bits(code[t], q);
+            if (full) {
+                store_quad<DTYPE>(a.out, quad, v);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (i0 + t < n) store_elem<DTYPE>(a.out, i0 + t, v[t]);
+            }
+        } else if (OUT == LGN_OUT_CODE8) {
+            if (full) {
+                reinterpret_cast<uint32_t *>(a.out)[quad] =
+                    code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (i0 + t < n) reinterpret_cast<uint8_t *>(a.out)[i0 + t] = (uint8_t)code[t];
+            }
+        } else {
+            const int N = q.n_bits;
+            const uint32_t chunk =
+                code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
+            const uint64_t tile_byte = tile * 32ull * (uint64_t)N;
+            pack_store_n(N, chunk, reinterpret_cast<uint8_t *>(a.out) + tile_byte,
+                         packed_total - tile_byte);
+        }
+    }
+}
+
+// ---- dequantize (not on the hot path): one element per thread ------------------------------
+template <int DTYPE, int IN_KIND>
+__global__ __launch_bounds__(kBlock) void dequant_kernel(const uint8_t *__restrict__ codes,
+                                                         uint64_t n, const lgn_fp_params_t *f,
+                                                         void *out)
+{
+    QuantConst q;
+    load_quant_const(f, q);
+    const uint64_t total_bytes = (n * (uint64_t)q.n_bits + 7) / 8;
+    const uint64_t gsize = (uint64_t)gridDim.x * kBlock;
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += gsize) {
+        uint32_t code;
+        if (IN_KIND == LGN_OUT_CODE8) {
+            code = codes[i];
+        } else {
+            const uint64_t bit = i * (uint64_t)q.n_bits, byte = bit >> 3;
+            uint32_t win = codes[byte];
+            if (byte + 1 < total_bytes) win |= (uint32_t)codes[byte + 1] << 8;
+            code = (win >> (bit & 7)) & ((1u << q.n_bits) - 1u);
+        }
+        store_elem<DTYPE>(out, i, code_value_bits(code, q));
+    }
+}
+
+using StreamKernel = void (*)(StreamArgs);
+
+template <int DTYPE, bool PRUNE, bool QUANT>
+static StreamKernel pick_round_out(int rounding, int out_kind)
+{
+    if (!QUANT) return stream_kernel<DTYPE, PRUNE, false, LGN_ROUND_NEAREST_EVEN, LGN_OUT_VALUE>;
+    if (rounding == LGN_ROUND_STOCHASTIC) {
+        if (out_kind == LGN_OUT_VALUE) return stream_kernel<DTYPE, PRUNE, true, LGN_ROUND_STOCHASTIC, LGN_OUT_VALUE>;
+        if (out_kind == LGN_OUT_CODE8) return stream_kernel<DTYPE, PRUNE, true, LGN_ROUND_STOCHASTIC, LGN_OUT_CODE8>;
+        return stream_kernel<DTYPE, PRUNE, true, LGN_ROUND_STOCHASTIC, LGN_OUT_PACKED>;
+    }
+    if (out_kind == LGN_OUT_VALUE) return stream_kernel<DTYPE, PRUNE, true, LGN_ROUND_NEAREST_EVEN, LGN_OUT_VALUE>;
+    if (out_kind == LGN_OUT_CODE8) return stream_kernel<DTYPE, PRUNE, true, LGN_ROUND_NEAREST_EVEN, LGN_OUT_CODE8>;
+    return stream_kernel<DTYPE, PRUNE, true, LGN_ROUND_NEAREST_EVEN, LGN_OUT_PACKED>;
+}
+
+hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int out_kind,
+                         const StreamArgs &args, int max_blocks, hipStream_t stream)
+{
+    if (args.n == 0) return hipSuccess;
+    StreamKernel k;
+    if (dtype == LGN_F32) {
+        k = prune ? (quant ? pick_round_out<LGN_F32, true, true>(rounding, out_kind)
+                           : pick_round_out<LGN_F32, true, false>(rounding, out_kind))
+                  : pick_round_out<LGN_F32, false, true>(rounding, out_kind);
+    } else {
+        k = prune ? (quant ? pick_round_out<LGN_BF16, true, true>(rounding, out_kind)
+                           : pick_round_out<LGN_BF16, true, false>(rounding, out_kind))
+                  : pick_round_out<LGN_BF16, false, true>(rounding, out_kind);
+    }
+    const uint64_t ntiles = (args.n + 255) / 256;
+    uint64_t blocks = (ntiles + (kBlock / kWave) - 1) / (kBlock / kWave);
+    if (blocks > (uint64_t)max_blocks) blocks = (uint64_t)max_blocks;
+    hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(kBlock), 0, stream, args);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f,
+                          int dtype, void *out, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    uint64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    const uint8_t *c = static_cast<const uint8_t *>(codes);
+    if (dtype == LGN_F32) {
+        if (in_kind == LGN_OUT_CODE8) dequant_kernel<LGN_F32, LGN_OUT_CODE8><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
+        else dequant_kernel<LGN_F32, LGN_OUT_PACKED><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
+    } else {
+        if (in_kind == LGN_OUT_CODE8) dequant_kernel<LGN_BF16, LGN_OUT_CODE8><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
+        else dequant_kernel<LGN_BF16, LGN_OUT_PACKED><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace lgn

@@ -27,3 +27,11 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True, scope="session")
+def _oracle_threads():
+    """The oracle's element loops are independent per element; use the host cores for speed."""
+    import oracle
+    oracle.set_threads(min(16, oracle.max_threads()))
+    yield

@@ -1,0 +1,375 @@
+"""Parity of the HIP path (through the C interface) with the CPU oracle, element by element on
+the same seeded inputs.  Bars: counts, extrema, alpha, (e, m, s) and every pruned / quantized
+element bit-exact; mu and sigma within 1e-6 relative (fp64 accumulation of fp32 logarithms)."""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+
+import oracle as O
+import synth_inputs as SI
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lgn():
+    import paper_2006_08173_amd as m
+    m.load()
+    return m
+
+
+# ------------------------------------------------------------------------------------ helpers
+def to_dev(a: np.ndarray):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t, like: np.ndarray = None) -> np.ndarray:
+    a = t.cpu().numpy()
+    if like is not None and like.dtype == np.uint16:
+        a = a.view(np.uint16)
+    return a
+
+
+def bits(a: np.ndarray) -> np.ndarray:
+    return a.view(np.uint32) if a.dtype == np.float32 else a.view(np.uint16)
+
+
+def dev_prune_params(lgn, alpha, status=0):
+    return lgn.upload_struct(lgn.LgnPruneParams(float(alpha), status, 0.0, 0.0))
+
+
+def dev_fp_params(lgn, e, m, s):
+    return lgn.upload_struct(lgn.LgnFpParams(1 + e + m, e, m, s, 0.0, 0, 0))
+
+
+def dev_stats_from_oracle(lgn, st: O.Stats):
+    ln2 = math.log(2.0)
+    mean_log2 = st.mu / ln2
+    m2 = (st.sigma / ln2) ** 2 * st.nnz if st.nnz else 0.0
+    return lgn.upload_struct(lgn.LgnStats(st.n, st.nnz, st.n_nonfinite, mean_log2, m2, st.mu,
+                                          st.sigma, st.max_abs, st.min_abs_nz, st.status, 0))
+
+
+def assert_stats_match(got, want: O.Stats, rel=1e-6):
+    assert (got.n, got.nnz, got.n_nonfinite) == (want.n, want.nnz, want.n_nonfinite)
+    assert np.float32(got.max_abs) == np.float32(want.max_abs)
+    assert np.float32(got.min_abs_nz) == np.float32(want.min_abs_nz)
+    assert got.status == want.status
+    if want.nnz == 0:
+        assert math.isnan(got.mu) and math.isnan(got.sigma)
+        return
+    assert abs(got.mu - want.mu) <= rel * abs(want.mu) + 1e-12
+    assert abs(got.sigma - want.sigma) <= rel * want.sigma + 1e-12
+    assert got.mu == pytest.approx(got.mean_log2 * math.log(2), rel=1e-15)
+
+
+SPECIALS = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-45, -1e-45, 1e-40, 3e-39, 1.17549435e-38,
+                     3.4028235e38, -3.4028235e38, 1.0, -1.0, 2.0 ** -20, 1.5 * 2.0 ** -13],
+                    dtype=np.float32)
+
+
+def mixed_tensor(n, seed, dtype=SI.F32, mu=-12.0, sigma=2.5, zero_frac=0.3):
+    g = SI.lognormal_tensor(n, seed=seed, mu=mu, sigma=sigma, zero_frac=zero_frac, dtype=dtype)
+    k = min(n, SPECIALS.size)
+    if k:
+        sp = SPECIALS[:k]
+        pos = np.random.default_rng(seed).choice(n, k, replace=False)
+        g[pos] = sp if dtype == SI.F32 else SI.f32_to_bf16_bits(sp)
+    return g
+
+
+# --------------------------------------------------------------------------------- statistics
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 255, 256, 257, 1023, 4099, 262_147, 1 << 20])
+@pytest.mark.parametrize("dtype", [SI.F32, SI.BF16])
+def test_stats_parity_sizes(lgn, n, dtype):
+    g = SI.lognormal_tensor(n, seed=100 + n % 97, mu=-12.0, sigma=2.0, zero_frac=0.3, dtype=dtype)
+    got = lgn.read_stats(lgn.lgn_stats(to_dev(g)))
+    assert_stats_match(got, O.stats(g))
+
+
+@pytest.mark.parametrize("dtype", [SI.F32, SI.BF16])
+def test_stats_parity_special_values(lgn, dtype):
+    g = mixed_tensor(70_001, 7, dtype)
+    want = O.stats(g)
+    assert want.n_nonfinite >= 3
+    assert_stats_match(lgn.read_stats(lgn.lgn_stats(to_dev(g))), want)
+    # only zeros / only non-finite / all equal / powers of two
+    for arr in (np.zeros(1000, np.float32), np.full(777, np.nan, np.float32),
+                np.full(5000, -3.25e-7, np.float32),
+                (2.0 ** np.arange(-140, 120, dtype=np.float64)).astype(np.float32)):
+        a = arr if dtype == SI.F32 else SI.f32_to_bf16_bits(arr)
+        got = lgn.read_stats(lgn.lgn_stats(to_dev(a)))
+        assert_stats_match(got, O.stats(a), rel=1e-9)
+    # all-equal input: zero spread exactly, not a cancellation residue
+    a = np.full(100_000, 1.2345e-5, np.float32)
+    got = lgn.read_stats(lgn.lgn_stats(to_dev(a)))
+    assert got.sigma == 0.0 and got.status & lgn.LGN_ST_SIGMA0
+
+
+def test_stats_config_c1_and_reproducible(lgn):
+    cfg = SI.config_c1()
+    g = SI.make(cfg)
+    d = to_dev(g)
+    a = lgn.read_stats(lgn.lgn_stats(d))
+    b = lgn.read_stats(lgn.lgn_stats(d))
+    assert bytes(a) == bytes(b)                       # same launch shape -> same bits
+    assert_stats_match(a, O.stats(g))
+    # population parameters of the recipe
+    assert abs(a.mu - cfg["mu"]) < 5 * cfg["sigma"] / math.sqrt(a.nnz)
+    assert abs(a.sigma - cfg["sigma"]) < 5 * cfg["sigma"] / math.sqrt(2 * a.nnz)
+
+
+def test_stats_argument_errors(lgn):
+    g = torch.zeros(1024, device="cuda")
+    with pytest.raises(lgn.LgnError) as e:
+        lgn.lgn_stats(g, ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == lgn.LGN_ERR_WORKSPACE
+    with pytest.raises(lgn.LgnError) as e:
+        lgn.lgn_stats(g[1:])                           # 4-byte offset: not 16-byte aligned
+    assert e.value.code == lgn.LGN_ERR_INVALID_ARG
+    with pytest.raises(lgn.LgnError) as e:
+        lgn.lgn_stats(g, dtype=7)
+    assert e.value.code == lgn.LGN_ERR_UNSUPPORTED
+    st = lgn.lgn_stats(g)
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_threshold(st, 1.0)
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_fp_params(st, 9)
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_fp_params(st, 6, e_bits=6)
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_fp_params(st, 6, scale_arg=1.0)
+
+
+# ------------------------------------------------------------------------------------- solver
+SOLVER_CASES = [(-12.0, 2.0), (-14.0, 2.5), (-20.0, 3.5), (0.0, 1.0), (-8.3, 1.5), (-16.0, 3.0),
+                (2.0, 0.4), (-10.0, 5.5), (-9.0, 0.05)]
+
+
+@pytest.mark.parametrize("mu,sigma", SOLVER_CASES)
+def test_threshold_parity_identical_inputs(lgn, mu, sigma):
+    for n, nnz in ((1 << 20, 734_235), (1000, 1000), (51_380_224, 25_690_112)):
+        for s in (0.31, 0.5, 0.7, 0.85, 0.9, 0.95, 0.999):
+            for adt in (O.F32, O.BF16):
+                st = O.make_stats(n, nnz, mu, sigma, 1.0, 1e-9)
+                want = O.threshold(st, s, adt)
+                got = lgn.read_prune_params(lgn.lgn_threshold(dev_stats_from_oracle(lgn, st), s, adt))
+                assert np.float32(got.alpha).view(np.uint32) == np.float32(want.alpha).view(np.uint32), (n, s, adt)
+                assert got.status == want.status
+                assert got.s_eff == pytest.approx(want.s_eff, rel=1e-14, abs=1e-300)
+                assert got.s_pred == pytest.approx(want.s_pred, abs=1e-13)
+
+
+def test_threshold_parity_degenerate(lgn):
+    cases = [O.make_stats(100, 0, float("nan"), float("nan"), status=O.ST_EMPTY),
+             O.make_stats(100, 100, math.log(3e-4), 0.0, 3e-4, 3e-4, status=O.ST_SIGMA0),
+             O.make_stats(1000, 400, -12.0, 2.0)]           # 60 % zeros already
+    for st in cases:
+        for s in (0.0, 0.3, 0.6, 0.75):
+            want = O.threshold(st, s)
+            got = lgn.read_prune_params(lgn.lgn_threshold(dev_stats_from_oracle(lgn, st), s))
+            assert np.float32(got.alpha).view(np.uint32) == np.float32(want.alpha).view(np.uint32)
+            assert got.status == want.status
+            assert got.s_pred == pytest.approx(want.s_pred, abs=1e-13)
+
+
+@pytest.mark.parametrize("mu,sigma", SOLVER_CASES + [(-12.0, 0.3), (-12.0, 9.0), (-12.0, 30.0)])
+def test_fp_params_parity_identical_inputs(lgn, mu, sigma):
+    st = O.make_stats(10_000, 9_000, mu, sigma, max_abs=math.exp(mu + 4 * sigma) if mu + 4 * sigma < 80 else 1e30,
+                      min_abs_nz=1e-30)
+    dst = dev_stats_from_oracle(lgn, st)
+    for n_bits in range(2, 9):
+        for e_bits in [-1] + list(range(1, n_bits)):
+            for mode, arg in ((O.SCALE_QUANTILE, 0.997), (O.SCALE_QUANTILE, 0.9), (O.SCALE_MAX, 0.0),
+                              (O.SCALE_CENTER, 0.0)):
+                for units in (O.SIGMA_PAPER_LITERAL, O.SIGMA_BASE2):
+                    want = O.fp_params(st, n_bits, e_bits, mode, arg, units)
+                    got = lgn.read_fp_params(lgn.lgn_fp_params(dst, n_bits, e_bits, mode, arg, units))
+                    assert (got.n_bits, got.e_bits, got.m_bits, got.scale_exp, got.status) == \
+                           (want.n_bits, want.e_bits, want.m_bits, want.scale_exp, want.status), \
+                           (n_bits, e_bits, mode, units)
+                    assert got.eta == pytest.approx(want.eta, rel=1e-9, abs=1e-15)
+
+
+def test_fp_params_reproduces_paper_table2_on_device(lgn):
+    rows = {4.0: [(3, 0), (4, 0), (4, 1), (4, 2), (5, 2)], 5.5: [(3, 0), (4, 0), (5, 0), (5, 1), (5, 2)]}
+    for sigma, fmts in rows.items():
+        dst = dev_stats_from_oracle(lgn, O.make_stats(10, 10, 0.0, sigma, 1.0, 1.0))
+        for n_bits, (e, m) in zip((4, 5, 6, 7, 8), fmts):
+            got = lgn.read_fp_params(lgn.lgn_fp_params(dst, n_bits))
+            assert (got.e_bits, got.m_bits) == (e, m)
+
+
+def test_fp_params_degenerate_and_max_scale(lgn):
+    for st in (O.make_stats(5, 0, float("nan"), float("nan"), status=O.ST_EMPTY),
+               O.make_stats(5, 5, -3.0, 0.0, 0.05, 0.05, status=O.ST_SIGMA0)):
+        for e_bits in (-1, 2):
+            want = O.fp_params(st, 6, e_bits, O.SCALE_MAX)
+            got = lgn.read_fp_params(lgn.lgn_fp_params(dev_stats_from_oracle(lgn, st), 6, e_bits, O.SCALE_MAX))
+            assert (got.e_bits, got.m_bits, got.scale_exp, got.status, got.eta) == \
+                   (want.e_bits, want.m_bits, want.scale_exp, want.status, want.eta)
+    for mx in (2.0 ** -149, 3e-40, 1.17549435e-38, 0.9999, 1.0, 3.4e38):
+        st = O.make_stats(5, 5, -3.0, 1.0, mx, mx)
+        want = O.fp_params(st, 8, 4, O.SCALE_MAX)
+        got = lgn.read_fp_params(lgn.lgn_fp_params(dev_stats_from_oracle(lgn, st), 8, 4, O.SCALE_MAX))
+        assert got.scale_exp == want.scale_exp
+
+
+# ---------------------------------------------------------------------------------- streaming
+SIZES = [0, 1, 2, 3, 4, 5, 63, 64, 255, 256, 257, 1000, 1024, 4099, 65_537, 300_001]
+
+
+@pytest.mark.parametrize("dtype", [SI.F32, SI.BF16])
+def test_prune_parity_sizes_offsets(lgn, dtype):
+    alpha = 9.3e-5 if dtype == SI.F32 else float(SI.bf16_bits_to_f32(SI.f32_to_bf16_bits(np.float32([9.3e-5])))[0])
+    p = dev_prune_params(lgn, alpha)
+    for n in SIZES:
+        g = mixed_tensor(n, 20 + n % 11, dtype)
+        for off in (0, 4, 1, 2, 3, (1 << 34) - 6, (1 << 40) + 5):
+            want = O.prune(g, alpha, 1234567890123, off)
+            got = to_host(lgn.lgn_prune(to_dev(g), p, 1234567890123, off), g)
+            assert np.array_equal(bits(got), bits(want)), (n, off)
+    # in place
+    g = mixed_tensor(100_003, 3, dtype)
+    d = to_dev(g)
+    lgn.lgn_prune(d, p, 5, 0, out=d)
+    assert np.array_equal(bits(to_host(d, g)), bits(O.prune(g, alpha, 5, 0)))
+    # alpha = 0 keeps every non-zero element
+    z = dev_prune_params(lgn, 0.0, lgn.LGN_ST_NOTHING_TO_PRUNE)
+    assert np.array_equal(bits(to_host(lgn.lgn_prune(to_dev(g), z, 5, 0), g)), bits(O.prune(g, 0.0, 5, 0)))
+
+
+def test_prune_parity_extreme_thresholds(lgn):
+    g = mixed_tensor(50_001, 9, SI.F32, mu=-80.0, sigma=6.0)       # reaches the subnormal range
+    for alpha in (1e-44, 1e-38, 3e-36, 1.0, 3.0e38):
+        got = to_host(lgn.lgn_prune(to_dev(g), dev_prune_params(lgn, alpha), 77, 8))
+        assert np.array_equal(bits(got), bits(O.prune(g, alpha, 77, 8))), alpha
+
+
+ALL_FORMATS = [(e, nb - 1 - e) for nb in range(2, 9) for e in range(1, nb)]
+
+
+@pytest.mark.parametrize("dtype", [SI.F32, SI.BF16])
+@pytest.mark.parametrize("rounding", [O.ROUND_NEAREST_EVEN, O.ROUND_STOCHASTIC])
+def test_quantize_parity_every_format(lgn, dtype, rounding):
+    g = mixed_tensor(20_003, 31, dtype)
+    d = to_dev(g)
+    for e, m in ALL_FORMATS:
+        s = -13 - (1 << (e - 1)) + 4
+        f = dev_fp_params(lgn, e, m, s)
+        nb = 1 + e + m
+        for kind in (O.OUT_CODE8, O.OUT_PACKED, O.OUT_VALUE):
+            want = O.fp_quantize(g, e, m, s, rounding, 42, 12, kind)
+            got = to_host(lgn.lgn_fp_quantize(d, f, rounding, 42, 12, out_kind=kind, n_bits=nb),
+                          g if kind == O.OUT_VALUE else None)
+            if kind == O.OUT_VALUE:
+                assert np.array_equal(bits(got), bits(want)), (e, m, kind)
+            else:
+                assert np.array_equal(got, want), (e, m, kind)
+
+
+@pytest.mark.parametrize("kind", [O.OUT_CODE8, O.OUT_PACKED, O.OUT_VALUE])
+def test_quantize_parity_sizes_and_scales(lgn, kind):
+    for n in SIZES:
+        g = mixed_tensor(n, 40 + n % 7, SI.F32)
+        for (e, m, s) in ((3, 2, -13), (5, 0, -20), (4, 1, -150), (2, 2, 100), (4, 3, 125), (7, 0, -80)):
+            f = dev_fp_params(lgn, e, m, s)
+            for rounding in (O.ROUND_NEAREST_EVEN, O.ROUND_STOCHASTIC):
+                want = O.fp_quantize(g, e, m, s, rounding, 9, 3, kind)
+                got = to_host(lgn.lgn_fp_quantize(to_dev(g), f, rounding, 9, 3, out_kind=kind, n_bits=1 + e + m))
+                if kind == O.OUT_VALUE:
+                    assert np.array_equal(bits(got), bits(want)), (n, e, m, s)
+                else:
+                    assert np.array_equal(got, want), (n, e, m, s)
+
+
+def test_quantize_subnormal_inputs_and_outputs(lgn):
+    rng = np.random.default_rng(1)
+    raw = rng.integers(0, 1 << 25, 40_000, dtype=np.uint32)          # subnormals and tiny normals
+    raw |= rng.integers(0, 2, raw.size, dtype=np.uint32) << 31
+    g = raw.view(np.float32)
+    for (e, m, s) in ((4, 3, -148), (5, 2, -140), (3, 2, -130), (7, 0, -100)):
+        f = dev_fp_params(lgn, e, m, s)
+        for rounding in (O.ROUND_NEAREST_EVEN, O.ROUND_STOCHASTIC):
+            for kind in (O.OUT_CODE8, O.OUT_VALUE):
+                want = O.fp_quantize(g, e, m, s, rounding, 1, 0, kind)
+                got = to_host(lgn.lgn_fp_quantize(to_dev(g), f, rounding, 1, 0, out_kind=kind))
+                assert np.array_equal(bits(got) if kind == O.OUT_VALUE else got,
+                                      bits(want) if kind == O.OUT_VALUE else want), (e, m, s)
+
+
+@pytest.mark.parametrize("dtype", [SI.F32, SI.BF16])
+@pytest.mark.parametrize("rounding", [O.ROUND_NEAREST_EVEN, O.ROUND_STOCHASTIC])
+def test_fused_parity_and_composition(lgn, dtype, rounding):
+    for n in (0, 5, 257, 70_001, 1 << 20):
+        g = mixed_tensor(n, 50 + n % 5, dtype, mu=-12.0, sigma=2.0)
+        alpha = float(SI.bf16_bits_to_f32(SI.f32_to_bf16_bits(np.float32([9.3e-5])))[0])
+        p = dev_prune_params(lgn, alpha)
+        d = to_dev(g)
+        for (e, m, s) in ((3, 2, -13), (4, 1, -22), (5, 0, -20)):
+            f = dev_fp_params(lgn, e, m, s)
+            nb = 1 + e + m
+            for kind in (O.OUT_CODE8, O.OUT_PACKED, O.OUT_VALUE):
+                for off in (0, 6):
+                    want = O.prune_quantize(g, alpha, e, m, s, rounding, 2024, off, kind)
+                    got = to_host(lgn.lgn_prune_quantize_fused(d, p, f, rounding, 2024, off, out_kind=kind, n_bits=nb),
+                                  g if kind == O.OUT_VALUE else None)
+                    two = to_host(lgn.lgn_fp_quantize(lgn.lgn_prune(d, p, 2024, off), f, rounding, 2024, off,
+                                                      out_kind=kind, n_bits=nb),
+                                  g if kind == O.OUT_VALUE else None)
+                    if kind == O.OUT_VALUE:
+                        assert np.array_equal(bits(got), bits(want)), (n, e, m, kind, off)
+                        assert np.array_equal(bits(got), bits(two))
+                    else:
+                        assert np.array_equal(got, want), (n, e, m, kind, off)
+                        assert np.array_equal(got, two)
+
+
+def test_shard_invariance_and_dequantize(lgn):
+    g = mixed_tensor(200_000, 61, SI.F32)
+    d = to_dev(g)
+    p = dev_prune_params(lgn, 1e-4)
+    f = dev_fp_params(lgn, 3, 2, -13)
+    whole = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 8, 0, out_kind=O.OUT_CODE8)
+    cut = 120_000                                        # multiple of 32: packed shards are byte aligned
+    a = lgn.lgn_prune_quantize_fused(d[:cut], p, f, O.ROUND_STOCHASTIC, 8, 0, out_kind=O.OUT_CODE8)
+    b = lgn.lgn_prune_quantize_fused(d[cut:], p, f, O.ROUND_STOCHASTIC, 8, cut, out_kind=O.OUT_CODE8)
+    assert torch.equal(whole, torch.cat([a, b]))
+    pk = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 8, 0, out_kind=O.OUT_PACKED, n_bits=6)
+    assert np.array_equal(to_host(pk), O.pack(to_host(whole), 6))
+    for kind, codes in ((O.OUT_CODE8, whole), (O.OUT_PACKED, pk)):
+        for dt, tdt in ((lgn.LGN_F32, np.float32), (lgn.LGN_BF16, np.uint16)):
+            deq = lgn.lgn_dequantize(codes, g.size, kind, f, dt)
+            want = O.dequantize(to_host(whole), 3, 2, -13, dt)
+            got = to_host(deq.view(torch.int16) if dt == lgn.LGN_BF16 else deq)
+            assert np.array_equal(got.view(want.dtype), want)
+
+
+def test_chain_on_device_matches_oracle_chain(lgn):
+    """stats -> threshold -> format -> fused, parameters never leaving the device."""
+    cfg = SI.config_c1()
+    g = SI.make(cfg)
+    d = to_dev(g)
+    st = lgn.lgn_stats(d)
+    p = lgn.lgn_threshold(st, cfg["sparsity"])
+    f = lgn.lgn_fp_params(st, cfg["n_bits"])
+    codes = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, cfg["rng_seed"], 0, out_kind=O.OUT_CODE8)
+    hs, hp, hf = lgn.read_stats(st), lgn.read_prune_params(p), lgn.read_fp_params(f)
+    ost = O.stats(g)
+    assert_stats_match(hs, ost)
+    op, of = O.threshold(ost, cfg["sparsity"]), O.fp_params(ost, cfg["n_bits"])
+    assert (hf.e_bits, hf.m_bits, hf.scale_exp) == (of.e_bits, of.m_bits, of.scale_exp) == (3, 2, of.scale_exp)
+    assert hp.alpha == pytest.approx(op.alpha, rel=2e-6)
+    # elements: bit-exact given the device's own threshold and format
+    want = O.prune_quantize(g, hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp, O.ROUND_STOCHASTIC,
+                            cfg["rng_seed"], 0, O.OUT_CODE8)
+    got = to_host(codes)
+    assert np.array_equal(got, want)
+    # and the paper's claims hold on the device output: achieved = required sparsity
+    achieved = np.mean((got & 0x1F) == 0)
+    assert abs(achieved - cfg["sparsity"]) < 6 * math.sqrt(0.85 * 0.15 / g.size) + 3 / math.sqrt(ost.nnz)
