@@ -15,8 +15,9 @@
  *
  * Conventions the paper leaves open (all listed in the design document):
  *   - statistics use the population standard deviation over finite non-zero entries;
- *   - the uniform variable of stochastic pruning has 24 bits, u = k / 2^24, and the comparison
- *     value alpha*u is one IEEE single-precision product;
+ *   - the uniform variable of stochastic pruning lives on a 23-bit midpoint grid,
+ *     u = (k + 1/2) / 2^23 with k the top 23 bits of the random word, so 0 < u < 1, and the
+ *     comparison value alpha*u is one IEEE single-precision product;
  *   - random words come from Philox4x32-10 (Salmon et al., SC'11) keyed by the 64-bit seed, with
  *     counter (lo32(j>>2), hi32(j>>2), purpose, 0) and word index j&3 for global element j;
  *   - an FP(1,e,m) word has exponent field c in [1, 2^e-1] meaning E = c - 2^(e-1), field 0 is
@@ -28,7 +29,7 @@
  * variable of the lognormal CDF) and Monte-Carlo pruning for the threshold; exhaustive
  * enumeration of all FP-n codes for the quantizer; exact results on powers of two for the
  * statistics.  Parity unpinned (pure conventions): the 0.997 default quantile of the scale rule,
- * the tie rule of nearest rounding, the 24-bit width of u.
+ * the tie rule of nearest rounding, the 23-bit midpoint grid of u.
  */
 #include <float.h>
 #include <math.h>
@@ -380,7 +381,7 @@ uint32_t orc_random_word(uint64_t seed, uint64_t j, uint32_t purpose)
 /* ==========================================================================================
  * Step 4.  Stochastic pruning T_{alpha,eps} (Section "Stochastic pruning", the three-case
  * definition):  |x| > alpha -> x;  alpha eps <= |x| <= alpha -> sign(x) alpha;
- * |x| < alpha eps -> 0.   eps = u = (w >> 8) / 2^24 and alpha*u is one single-precision product.
+ * |x| < alpha eps -> 0.   eps = u = ((w >> 9) + 1/2) / 2^23 and alpha*u is one single-precision product.
  * Exact zeros stay zero whatever u is, NaN passes through.
  * ========================================================================================== */
 static float prune_one(float x, float alpha, uint32_t w)
@@ -389,8 +390,8 @@ static float prune_one(float x, float alpha, uint32_t w)
     float a = fabsf(x);
     if (a == 0.0f) return 0.0f;
     if (a > alpha) return x;
-    float u = (float)(w >> 8) * 0x1p-24f;
-    float t = (float)((double)alpha * (double)u); /* exact product, one rounding to single */
+    double u = ((double)(w >> 9) + 0.5) / 8388608.0; /* 23-bit midpoint grid, 0 < u < 1 */
+    float t = (float)((double)alpha * u);             /* exact product, one rounding to single */
     if (a < t) return 0.0f;
     return copysignf(alpha, x);
 }

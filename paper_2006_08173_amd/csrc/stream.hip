@@ -7,6 +7,13 @@
 // integer work on fp32 bit patterns (bf16 widens by a shift), except the one single-precision
 // product alpha * u that the pruning rule is defined with.
 //
+// Two code paths per tile.  The fast path covers full tiles whose global quad indices share the
+// upper counter word, with elem_offset a multiple of four, a normal-range alpha and a scale that
+// flushes fp32 subnormals (the case for any sane gradient scale): there the first Philox rounds
+// run partly on the scalar unit, the three-way xors are single v_bitop3 instructions, and the
+// per-element work is about sixteen integer instructions.  Everything else (ragged tail tile,
+// unaligned offsets, exotic scales) takes the general path; both give identical bits.
+//
 // PACKED output: the four N-bit codes of a lane form a 4N-bit chunk; the 64 chunks of a tile are
 // one contiguous run of 8N dwords.  Lane k < 8N assembles dword k from the (at most five) chunks
 // that overlap it, fetched with cross-lane reads, and the wave stores 8N consecutive dwords.
@@ -64,14 +71,15 @@ __device__ __forceinline__ void quad_words(uint64_t j0, uint32_t purpose, Philox
     }
 }
 
-// T_{alpha,u}: |x| > alpha keeps x; |x| < fl32(alpha u) gives 0; otherwise sign(x) alpha.
-// Zero stays (+)zero for every u; NaN and Inf compare above any finite alpha and pass.
+// T_{alpha,u}: |x| > alpha keeps x; |x| < fl32(alpha u) gives 0; otherwise sign(x) alpha, with
+// u = ((w >> 9) + 1/2) / 2^23 in (0, 1).  Zero stays (+)zero whatever alpha u rounds to; NaN and
+// Inf compare above any finite alpha and pass.
 __device__ __forceinline__ uint32_t prune_bits(uint32_t bits, uint32_t w, uint32_t alpha_bits,
                                                float alpha)
 {
     const uint32_t a = bits & 0x7fffffffu;
-    const float u = (float)(w >> 8) * 0x1p-24f;        // exact
-    const uint32_t t = __float_as_uint(alpha * u);     // one rounding
+    const float u = (float)((w & 0xfffffe00u) | 0x100u) * 0x1p-32f;  // exact: 24 significant bits
+    const uint32_t t = __float_as_uint(alpha * u);                    // one rounding
     const uint32_t small = (a < t || a == 0u) ? 0u : (alpha_bits | (bits & 0x80000000u));
     return a > alpha_bits ? bits : small;
 }
@@ -164,6 +172,105 @@ __device__ __forceinline__ void pack_store_n(int n_bits, uint32_t chunk, uint8_t
     }
 }
 
+// ---- fast path ------------------------------------------------------------------------------
+// Wave-uniform constants of the fast path.
+struct FastConst {
+    uint32_t alpha_bits;
+    float alpha23;     // alpha * 2^-23 and alpha * 2^-24 (exact for the alphas the fast path
+    float alpha24;     // accepts): fl32(alpha u) = fma(k, alpha23, alpha24) for u = (k + 1/2) / 2^23
+    uint32_t sub;      // cbias << 23: subtracting it re-biases the exponent field
+    uint32_t lo_bits;  // smallest magnitude pattern that is not flushed
+    uint32_t span;     // magnitudes in [lo_bits, lo_bits + span) are finite and in range or above
+    uint32_t maxmag;
+    uint32_t cut;      // 23 - m
+    uint32_t rshift;   // 9 + m
+    uint32_t sshift;   // e + m: position of the sign bit in a code
+    uint32_t rnd;      // 2^(cut-1) - 1, the nearest-even increment before the parity bit
+};
+
+// One element of the fused / quantize-only fast path; returns the code (sign included).
+// `a` is |x| as a bit pattern, `keep` is false where pruning zeroed the element.
+template <int ROUND>
+__device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool keep, uint32_t w,
+                                              const FastConst &c)
+{
+    const uint32_t y = a - c.sub;
+    uint32_t mag;
+    if (ROUND == LGN_ROUND_STOCHASTIC) mag = (y + (w >> c.rshift)) >> c.cut;
+    else mag = (y + c.rnd + ((y >> c.cut) & 1u)) >> c.cut;
+    mag = min(mag, c.maxmag);
+    const bool valid = (a - c.lo_bits) < c.span;
+    const uint32_t code = ((bits >> 31) << c.sshift) | mag;
+    return (valid && keep) ? code : 0u;
+}
+
+// PRUNE: the call prunes; DO_PRUNE: alpha is non-zero, so pruning actually draws random words.
+template <int DTYPE, bool PRUNE, bool DO_PRUNE, bool QUANT, int ROUND, int OUT>
+__device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, uint64_t qbase,
+                                          int lane, PhiloxKey key, const FastConst &c,
+                                          const QuantConst &q)
+{
+    // scalar tile base + 32-bit lane offset
+    constexpr int QB = DTYPE == LGN_F32 ? 16 : 8;  // bytes per quad
+    const char *gin = reinterpret_cast<const char *>(a.g) + tile * (uint64_t)(kWave * QB);
+    uint32_t b[4];
+    load_quad<DTYPE>(gin, (uint32_t)lane, b);
+
+    const uint32_t q_lo = (uint32_t)qbase + (uint32_t)lane;  // no carry: checked by the caller
+    const uint32_t q_hi = (uint32_t)(qbase >> 32);
+    const uint64_t p0 = (uint64_t)kPhiloxM0 * q_lo;           // shared by both purposes
+    uint32_t w0[4] = {0u, 0u, 0u, 0u}, w1[4] = {0u, 0u, 0u, 0u};
+    if (DO_PRUNE) philox_finish<0u>((uint32_t)(p0 >> 32), (uint32_t)p0, q_hi, key, w0);
+    if (QUANT && ROUND == LGN_ROUND_STOCHASTIC)
+        philox_finish<1u>((uint32_t)(p0 >> 32), (uint32_t)p0, q_hi, key, w1);
+
+    uint32_t mag_in[4];
+    bool keep[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const uint32_t ab = b[t] & 0x7fffffffu;
+        mag_in[t] = ab;
+        keep[t] = true;
+        if (DO_PRUNE) {
+            const float kf = (float)(w0[t] >> 9);
+            const uint32_t thr = __float_as_uint(__builtin_fmaf(kf, c.alpha23, c.alpha24));
+            keep[t] = !(ab < thr);
+            if (QUANT) {
+                mag_in[t] = max(ab, c.alpha_bits);  // below alpha: the survivor is +-alpha
+            } else {
+                const uint32_t small = keep[t] ? (c.alpha_bits | (b[t] & 0x80000000u)) : 0u;
+                b[t] = ab > c.alpha_bits ? b[t] : small;
+            }
+        } else if (PRUNE && !QUANT) {
+            b[t] = ab ? b[t] : 0u;  // alpha = 0: only -0 changes
+        }
+    }
+    if (!QUANT) {
+        char *gout = reinterpret_cast<char *>(a.out) + tile * (uint64_t)(kWave * QB);
+        store_quad<DTYPE>(gout, (uint32_t)lane, b);
+        return;
+    }
+    uint32_t code[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) code[t] = fast_code<ROUND>(b[t], mag_in[t], keep[t], w1[t], c);
+    if (OUT == LGN_OUT_VALUE) {
+        uint32_t v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            v[t] = (b[t] & 0x7fffffffu) > 0x7f800000u ? b[t] : code_value_bits(code[t], q);
+        char *gout = reinterpret_cast<char *>(a.out) + tile * (uint64_t)(kWave * QB);
+        store_quad<DTYPE>(gout, (uint32_t)lane, v);
+    } else if (OUT == LGN_OUT_CODE8) {
+        uint32_t *gout = reinterpret_cast<uint32_t *>(a.out) + tile * (uint64_t)kWave;
+        gout[(uint32_t)lane] = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+    } else {
+        const int N = q.n_bits;
+        const uint32_t chunk = code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
+        pack_store_n(N, chunk, reinterpret_cast<uint8_t *>(a.out) + tile * 32ull * (uint64_t)N,
+                     ~0ull);
+    }
+}
+
 template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
 __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
 {
@@ -179,13 +286,39 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
     const uint64_t ntiles = (n + 255) / 256;
     const uint64_t nwaves = (uint64_t)gridDim.x * (kBlock / kWave);
     const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t wave = (uint64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const uint64_t wave = (uint64_t)blockIdx.x * (kBlock / kWave) +
+                          (uint64_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint64_t packed_total = (n * (uint64_t)q.n_bits + 7) / 8;
 
+    // Fast-path eligibility that does not depend on the tile (all wave-uniform).
+    FastConst c;
+    c.alpha_bits = alpha_bits;
+    c.alpha23 = alpha * 0x1p-23f;
+    c.alpha24 = alpha * 0x1p-24f;
+    c.sub = (uint32_t)max(q.cbias, 0) << 23;
+    c.lo_bits = (uint32_t)min(max(q.cbias + 1, 0), 256) << 23;
+    c.span = c.lo_bits <= 0x7f800000u ? 0x7f800001u - c.lo_bits : 0u;
+    c.maxmag = q.maxmag;
+    c.cut = 23u - (uint32_t)q.m;
+    c.rshift = 9u + (uint32_t)q.m;
+    c.sshift = (uint32_t)(q.e + q.m);
+    c.rnd = (1u << (c.cut - 1u)) - 1u;
+    const bool do_prune = PRUNE && alpha_bits != 0u;
+    const bool fast_ok = (a.elem_offset & 3ull) == 0ull &&
+                         (!QUANT || (q.cbias >= 0 && q.cbias <= 254)) &&
+                         (!do_prune || (alpha_bits >= 0x12000000u && alpha_bits < 0x7f800000u));
+    const uint64_t qoff = a.elem_offset >> 2;
+
     for (uint64_t tile = wave; tile < ntiles; tile += nwaves) {
+        const bool full = (tile + 1) * 256 <= n;    // wave-uniform
+        const uint64_t qbase = qoff + tile * kWave;  // global quad index of lane 0
+        if (fast_ok && full && (uint32_t)qbase <= 0xffffffffu - (uint32_t)kWave) {
+            if (do_prune) fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q);
+            else fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q);
+            continue;
+        }
         const uint64_t quad = tile * kWave + lane;  // index of this lane's four elements
         const uint64_t i0 = quad * 4;
-        const bool full = (tile + 1) * 256 <= n;    // wave-uniform
         uint32_t b[4];
         if (full) {
             load_quad<DTYPE>(a.g, quad, b);

@@ -88,21 +88,25 @@ def test_stats_special_values_and_bf16():
 # ----------------------------------------------------------------------- stochastic pruning
 def test_prune_three_cases_by_hand():
     alpha = np.float32(1.0)
-    w_of_u = lambda k: int(k) << 8            # u = k / 2^24
-    half = w_of_u(1 << 23)                    # u = 0.5
+    w_of_k = lambda k: int(k) << 9            # u = (k + 1/2) / 2^23
+    half = w_of_k(1 << 22)                    # u = 0.5 + 2^-24
+    u_half = np.float32(0.5 + 2.0 ** -24)
     assert O.prune_one(1.5, alpha, half) == 1.5            # above: untouched
     assert O.prune_one(-1.5, alpha, half) == -1.5
     assert O.prune_one(1.0, alpha, half) == 1.0            # |x| = alpha -> sign * alpha = x
     assert O.prune_one(0.75, alpha, half) == 1.0           # alpha*u <= |x| <= alpha
     assert O.prune_one(-0.75, alpha, half) == -1.0
-    assert O.prune_one(0.5, alpha, half) == 1.0            # |x| = alpha*u belongs to the middle case
+    assert O.prune_one(u_half, alpha, half) == 1.0         # |x| = alpha*u belongs to the middle case
+    assert O.prune_one(0.5, alpha, half) == 0.0            # just below alpha*u
     assert O.prune_one(0.25, alpha, half) == 0.0           # |x| < alpha*u
     assert O.prune_one(-0.25, alpha, half) == 0.0
-    # zeros stay zeros even when u = 0; low 8 bits of the word are not used
+    # zeros stay zeros for the smallest u; the low 9 bits of the word are not used
     assert O.prune_one(0.0, alpha, 0) == 0.0
     assert O.prune_one(-0.0, alpha, 0) == 0.0 and not math.copysign(1, O.prune_one(-0.0, alpha, 0)) < 0
-    assert O.prune_one(0.25, alpha, half | 0xFF) == 0.0
-    assert O.prune_one(1e-30, alpha, 0) == 1.0             # u = 0: everything non-zero survives
+    assert O.prune_one(0.25, alpha, half | 0x1FF) == 0.0
+    assert O.prune_one(2.0 ** -24, alpha, 0) == 1.0        # smallest u = 2^-24
+    assert O.prune_one(2.0 ** -25, alpha, 0) == 0.0        # u is never 0: tiny values can vanish
+    assert O.prune_one(1.0 - 2.0 ** -24, alpha, 0xFFFFFFFF) == 1.0   # largest u = 1 - 2^-24
     assert math.isnan(O.prune_one(float("nan"), alpha, half))
     assert O.prune_one(float("inf"), alpha, half) == float("inf")
     # alpha = 0 prunes nothing
@@ -112,11 +116,13 @@ def test_prune_three_cases_by_hand():
 def test_prune_threshold_product_is_single_precision():
     """alpha * u is rounded once to fp32 before the comparison."""
     alpha = np.float32(1.0 + 2.0 ** -23)
-    k = (1 << 24) - 1
-    t = np.float32(np.float64(alpha) * (k / 2.0 ** 24))     # exact product rounded once
+    k = (1 << 23) - 1
+    u = (k + 0.5) / 2.0 ** 23
+    t = np.float32(np.float64(alpha) * u)                   # exact product rounded once
+    assert float(t) != float(np.float64(alpha) * u)         # the product really needs rounding
     below = np.nextafter(t, np.float32(0))
-    assert O.prune_one(t, alpha, k << 8) == alpha
-    assert O.prune_one(below, alpha, k << 8) == 0.0
+    assert O.prune_one(t, alpha, k << 9) == alpha
+    assert O.prune_one(below, alpha, k << 9) == 0.0
 
 
 def test_prune_outputs_sparsity_and_mean():
@@ -148,15 +154,15 @@ def test_prune_outputs_sparsity_and_mean():
 
 
 def test_prune_keep_probability_exact():
-    """Over all 2^24 values of u, P(keep) = |x|/alpha up to the grid; check on a sample of k."""
+    """Over the 2^23 grid values of u, P(keep) = |x|/alpha up to the grid; check on a sample."""
     alpha, x = np.float32(0.8), np.float32(0.3)
-    ks = np.arange(0, 1 << 24, 4099)
-    kept = sum(O.prune_one(x, alpha, int(k) << 8) != 0 for k in ks)
+    ks = np.arange(0, 1 << 23, 2053)
+    kept = sum(O.prune_one(x, alpha, int(k) << 9) != 0 for k in ks)
     assert kept / ks.size == pytest.approx(0.3 / 0.8, abs=2e-3)
     # threshold index: kept iff alpha*u <= x
-    k_star = int(math.floor(float(x) / float(alpha) * 2 ** 24))
-    assert O.prune_one(x, alpha, (k_star - 2) << 8) != 0
-    assert O.prune_one(x, alpha, (k_star + 2) << 8) == 0
+    k_star = int(math.floor(float(x) / float(alpha) * 2 ** 23))
+    assert O.prune_one(x, alpha, (k_star - 2) << 9) != 0
+    assert O.prune_one(x, alpha, (k_star + 2) << 9) == 0
 
 
 def test_prune_elem_offset_and_bf16():
