@@ -16,7 +16,7 @@ struct StreamArgs {
     uint32_t k0, k1;
 };
 hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws,
-                        hipStream_t stream);
+                        int max_blocks, hipStream_t stream);
 size_t stats_workspace_bytes();
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
                             lgn_prune_params_t *out, hipStream_t stream);
@@ -71,6 +71,29 @@ int stream_blocks()
     return cached;
 }
 
+// Workgroups of the statistics pass (read-only streaming likes fewer, longer-lived waves).
+int stats_blocks_cap()
+{
+    static int cached = 0;
+    if (cached) return cached;
+    int per_cu = 8;
+    if (const char *e = getenv("LGN_STATS_BLOCKS_PER_CU")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= 8) per_cu = v;
+    }
+    cached = stream_blocks() / 8 * per_cu;  // stream_blocks() = CUs x 8 by default
+    if (getenv("LGN_STREAM_BLOCKS_PER_CU")) {
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) {
+            int v = 0;
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+        }
+        cached = cus * per_cu;
+    }
+    if (cached > 2048) cached = 2048;
+    return cached;
+}
+
 int check_stream_common(const void *g, uint64_t n, int dtype, const void *out, int out_kind)
 {
     if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
@@ -110,7 +133,8 @@ int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, 
         return fail(LGN_ERR_WORKSPACE, "workspace missing or smaller than %zu bytes",
                     lgn_workspace_bytes(n, dtype));
     if (!aligned(ws, 8)) return fail(LGN_ERR_WORKSPACE, "workspace not 8-byte aligned");
-    const hipError_t e = lgn::launch_stats(g, n, dtype, out, ws, static_cast<hipStream_t>(stream));
+    const hipError_t e = lgn::launch_stats(g, n, dtype, out, ws, stats_blocks_cap(),
+                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats", e);
 }
 

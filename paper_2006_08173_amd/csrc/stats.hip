@@ -1,17 +1,21 @@
 // lgn_stats: lognormal parameters of a gradient tensor (Section 3: fit on |g| without the zero
 // entries; Appendix "Stochastic pruning complexity": mean and standard deviation, O(n)).
 //
-// Two-stage grid reduction.  Stage 1 streams the tensor once with 16-byte loads; every thread
-// keeps (count, sum, sum of squares) of the deviations of log2|g| from a pivot -- the first
-// value that thread meets -- in fp64, so that no large common offset is squared.  Threads,
-// waves and workgroups are then merged pairwise as (count, mean, M2) with the exact parallel
-// update  M2 = M2a + M2b + d^2 na nb / n,  d = mean_b - mean_a.  Stage 2 merges the per-block
-// records in a fixed order, so results are reproducible for a given launch shape.
+// Two-stage grid reduction.  Stage 1 streams the tensor once with 16-byte loads, a batch of four
+// consecutive 1 KiB rows per wave, the next batch requested before the current one is reduced.
+// Per element: l = v_log_f32(|g|) (one hardware instruction, relative error about 1e-7, i.e. well
+// inside the 1e-6 budget on mu even if every rounding went the same way), minus a wave-uniform
+// pivot taken from the wave's first row, widened to fp64 and accumulated as sum and sum of
+// squares in fp64.  Subtracting the pivot before squaring keeps the squares small, so nothing
+// cancels when the moments are formed.  Waves and workgroups are merged pairwise as
+// (count, mean, M2) with the exact parallel update  M2 = M2a + M2b + d^2 na nb / n,
+// d = mean_b - mean_a.  Stage 2 merges the per-block records in a fixed order, so results are
+// reproducible for a given launch shape.
 //
-// log2|g| = (biased exponent field) + log2(mantissa in [1,2)); the first term is an integer, the
-// second one hardware v_log_f32 on a value in [1,2), i.e. an absolute error of about 1e-7 per
-// element instead of the 2e-6 that a single-precision log of the full value would have.
-// Subnormal inputs are normalised with integer operations.
+// The hot loop assumes finite, normal or zero inputs; a quad-row of the wave that contains an
+// Inf, NaN or subnormal is re-done by a careful path (wave-uniform branch) that normalises
+// subnormals with integer operations.  Zeros contribute a zero deviation and are counted out
+// with a ballot / popcount on the scalar unit.
 #include "lgn_device.hpp"
 
 namespace lgn {
@@ -23,7 +27,7 @@ struct Moments {
 struct Partial {  // one per stage-1 workgroup, 40 bytes
     double n, mean, m2;
     uint64_t nonfinite;
-    uint32_t mx, mn;
+    uint32_t mx, nmn;
 };
 
 __device__ __forceinline__ Moments merge(Moments a, Moments b)
@@ -42,12 +46,25 @@ __device__ __forceinline__ Moments merge(Moments a, Moments b)
     return r;
 }
 
-struct ThreadAcc {
-    double pivot, s1, s2;
-    uint32_t cnt, nonfinite, mx, mn;
+// Per-lane accumulators; the pivot and the fast-path count are wave-uniform.
+struct LaneAcc {
+    double s1, s2;       // sum and sum of squares of (log2|g| - pivot)
+    uint32_t mx;         // largest finite magnitude pattern
+    uint32_t nmn;        // max over (0 - a) of non-zero magnitudes, i.e. minus the smallest one
+    uint32_t slow_cnt;   // valid elements counted by the careful path (per lane)
+    uint32_t nonfinite;  // per lane
 };
 
-__device__ __forceinline__ void accumulate(uint32_t bits, ThreadAcc &t)
+// log2 of a finite, normal, non-zero magnitude pattern as exponent + log2(mantissa) in fp64
+// (careful path only).
+__device__ __forceinline__ double careful_log2(uint32_t a)
+{
+    const float m = __uint_as_float((a & 0x007fffffu) | 0x3f800000u);
+    return (double)((int)(a >> 23) - 127) + (double)__log2f(m);
+}
+
+// Careful per-element path: Inf/NaN counted and skipped, subnormals normalised.
+__device__ __forceinline__ void accumulate_careful(uint32_t bits, float pivot, LaneAcc &t)
 {
     const uint32_t a = bits & 0x7fffffffu;
     if (a >= 0x7f800000u) {
@@ -55,66 +72,90 @@ __device__ __forceinline__ void accumulate(uint32_t bits, ThreadAcc &t)
         return;
     }
     if (a == 0u) return;
-    uint32_t frac = a & 0x7fffffu;
-    int ex = (int)(a >> 23);
-    if (ex == 0) {  // subnormal: value = frac * 2^-149; bring the leading one to bit 23
-        const int sh = __clz(frac) - 8;
-        frac = (frac << sh) & 0x7fffffu;
-        ex = 1 - sh;
+    double l;
+    if (a < 0x00800000u) {  // subnormal: value = a * 2^-149; bring the leading one to bit 23
+        const int sh = __clz(a) - 8;
+        l = careful_log2(((a << sh) & 0x007fffffu) | 0x00800000u) - (double)sh;
+    } else {
+        l = careful_log2(a);
     }
-    const float lm = __log2f(__uint_as_float(0x3f800000u | frac));  // in [0, 1)
-    const double l = (double)ex + (double)lm;                        // log2|g| + 127
-    if (t.cnt == 0u) t.pivot = l;
-    const double d = l - t.pivot;
+    const double d = l - (double)pivot;
     t.s1 += d;
     t.s2 = fma(d, d, t.s2);
-    ++t.cnt;
+    ++t.slow_cnt;
     t.mx = max(t.mx, a);
-    t.mn = min(t.mn, a);
+    t.nmn = max(t.nmn, 0u - a);
+}
+
+// Four elements per lane.  Returns the number of valid elements the fast path counted for the
+// whole wave (wave-uniform), 0 if the careful path was taken.
+__device__ __forceinline__ uint32_t accumulate_quad(uint32_t b0, uint32_t b1, uint32_t b2,
+                                                    uint32_t b3, uint32_t pivot_bits, float pivot,
+                                                    LaneAcc &t)
+{
+    const uint32_t a0 = b0 & 0x7fffffffu, a1 = b1 & 0x7fffffffu;
+    const uint32_t a2 = b2 & 0x7fffffffu, a3 = b3 & 0x7fffffffu;
+    const bool v0 = a0 != 0u, v1 = a1 != 0u, v2 = a2 != 0u, v3 = a3 != 0u;
+    // Zeros are replaced by the pivot magnitude BEFORE the logarithm, so they come out as an
+    // exact zero deviation (one integer select instead of masking a double afterwards).
+    const float f0 = __builtin_amdgcn_logf(__uint_as_float(v0 ? a0 : pivot_bits)) - pivot;
+    const float f1 = __builtin_amdgcn_logf(__uint_as_float(v1 ? a1 : pivot_bits)) - pivot;
+    const float f2 = __builtin_amdgcn_logf(__uint_as_float(v2 ? a2 : pivot_bits)) - pivot;
+    const float f3 = __builtin_amdgcn_logf(__uint_as_float(v3 ? a3 : pivot_bits)) - pivot;
+    const uint32_t qmx = max(max(a0, a1), max(a2, a3));
+    // -a is large for small a and 0 for a = 0 (unsigned): its maximum tracks the smallest non-zero
+    const uint32_t qnmn = max(max(0u - a0, 0u - a1), max(0u - a2, 0u - a3));
+    // Inf / NaN have a >= 0x7f800000; a subnormal has 0 < a < 0x00800000
+    const bool odd = qmx >= 0x7f800000u || qnmn > 0xff800000u;
+    if (__builtin_amdgcn_ballot_w64(odd) != 0ull) {
+        accumulate_careful(b0, pivot, t);
+        accumulate_careful(b1, pivot, t);
+        accumulate_careful(b2, pivot, t);
+        accumulate_careful(b3, pivot, t);
+        return 0u;
+    }
+    const uint32_t cnt = (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(v0)) +
+                         (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(v1)) +
+                         (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(v2)) +
+                         (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(v3));
+    t.mx = max(t.mx, qmx);
+    t.nmn = max(t.nmn, qnmn);
+    const double d0 = (double)f0, d1 = (double)f1, d2 = (double)f2, d3 = (double)f3;
+    t.s1 += d0; t.s2 = fma(d0, d0, t.s2);
+    t.s1 += d1; t.s2 = fma(d1, d1, t.s2);
+    t.s1 += d2; t.s2 = fma(d2, d2, t.s2);
+    t.s1 += d3; t.s2 = fma(d3, d3, t.s2);
+    return cnt;
 }
 
 // 16 bytes = 4 fp32 or 8 bf16 elements
 template <int DTYPE>
-__device__ __forceinline__ void accumulate_vec(uint4 v, ThreadAcc &t)
+__device__ __forceinline__ uint32_t accumulate_vec(uint4 v, uint32_t pivot_bits, float pivot,
+                                                   LaneAcc &t)
 {
-    if (DTYPE == LGN_F32) {
-        accumulate(v.x, t); accumulate(v.y, t); accumulate(v.z, t); accumulate(v.w, t);
-    } else {
-        accumulate(v.x << 16, t); accumulate(v.x & 0xffff0000u, t);
-        accumulate(v.y << 16, t); accumulate(v.y & 0xffff0000u, t);
-        accumulate(v.z << 16, t); accumulate(v.z & 0xffff0000u, t);
-        accumulate(v.w << 16, t); accumulate(v.w & 0xffff0000u, t);
-    }
+    if (DTYPE == LGN_F32) return accumulate_quad(v.x, v.y, v.z, v.w, pivot_bits, pivot, t);
+    return accumulate_quad(v.x << 16, v.x & 0xffff0000u, v.y << 16, v.y & 0xffff0000u, pivot_bits, pivot, t) +
+           accumulate_quad(v.z << 16, v.z & 0xffff0000u, v.w << 16, v.w & 0xffff0000u, pivot_bits, pivot, t);
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_max(T v)
+{
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) v = max(v, (T)__shfl_xor(v, off));
+    return v;
 }
 
 struct BlockAcc {
     Moments m;
     double nonfinite;
-    uint32_t mx, mn;
+    uint32_t mx;
+    uint32_t nmn;  // max over (0 - a) of the non-zero magnitudes: 0 when there is none
 };
 
-__device__ __forceinline__ BlockAcc wave_reduce(BlockAcc v)
-{
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        Moments o;
-        o.n = __shfl_xor(v.m.n, off);
-        o.mean = __shfl_xor(v.m.mean, off);
-        o.m2 = __shfl_xor(v.m.m2, off);
-        // both partners must combine in the same order to stay bit-identical
-        const bool low = (threadIdx.x & off) == 0;
-        v.m = low ? merge(v.m, o) : merge(o, v.m);
-        v.nonfinite += __shfl_xor(v.nonfinite, off);
-        v.mx = max(v.mx, (uint32_t)__shfl_xor((int)v.mx, off));
-        v.mn = min(v.mn, (uint32_t)__shfl_xor((int)v.mn, off));
-    }
-    return v;
-}
-
-__device__ __forceinline__ BlockAcc block_reduce(BlockAcc v)
+__device__ __forceinline__ BlockAcc block_merge(BlockAcc v)  // one record per wave, in lane 0
 {
     __shared__ BlockAcc lds[kBlock / kWave];
-    v = wave_reduce(v);
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     if (lane == 0) lds[wave] = v;
     __syncthreads();
@@ -123,10 +164,17 @@ __device__ __forceinline__ BlockAcc block_reduce(BlockAcc v)
             v.m = merge(v.m, lds[w].m);
             v.nonfinite += lds[w].nonfinite;
             v.mx = max(v.mx, lds[w].mx);
-            v.mn = min(v.mn, lds[w].mn);
+            v.nmn = max(v.nmn, lds[w].nmn);
         }
     }
     return v;  // valid in thread 0
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off);
+    return v;  // the xor butterfly adds the same pairs in every lane: all lanes agree
 }
 
 template <int DTYPE>
@@ -134,47 +182,113 @@ __global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ 
                                                        Partial *__restrict__ partials)
 {
     constexpr int EPV = DTYPE == LGN_F32 ? 4 : 8;  // elements per 16-byte vector
+    constexpr int kWavesPerBlock = kBlock / kWave;
     const uint64_t nvec = n / EPV;
-    const uint64_t gsize = (uint64_t)gridDim.x * kBlock;
-    const uint64_t gtid = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t nrows = nvec / kWave;  // full rows of 64 vectors (1 KiB)
+    const uint64_t nwaves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock +
+                          (uint64_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint4 *__restrict__ gv = reinterpret_cast<const uint4 *>(g);
 
-    ThreadAcc t;
-    t.pivot = 0.0; t.s1 = 0.0; t.s2 = 0.0;
-    t.cnt = 0u; t.nonfinite = 0u; t.mx = 0u; t.mn = 0xffffffffu;
+    LaneAcc t;
+    t.s1 = 0.0; t.s2 = 0.0;
+    t.mx = 0u; t.nmn = 0u; t.slow_cnt = 0u; t.nonfinite = 0u;
+    uint32_t cnt = 0;  // wave-uniform; one wave sees far fewer than 2^32 elements
 
-    uint64_t v = gtid;
-    for (; v + 3 * gsize < nvec; v += 4 * gsize) {  // four independent loads in flight
-        const uint4 a = gv[v], b = gv[v + gsize], c = gv[v + 2 * gsize], d = gv[v + 3 * gsize];
-        accumulate_vec<DTYPE>(a, t);
-        accumulate_vec<DTYPE>(b, t);
-        accumulate_vec<DTYPE>(c, t);
-        accumulate_vec<DTYPE>(d, t);
+    // Pivot: the largest normal magnitude in the wave's first row (1.0 if there is none) and its
+    // log2 as the hardware instruction returns it.
+    uint32_t pivot_bits = 0x3f800000u;
+    if (wave < nrows) {
+        const uint4 v = gv[wave * kWave + lane];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t cand = 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = (DTYPE == LGN_F32 ? w[i] : w[i] << 16) & 0x7fffffffu;
+            const uint32_t hi = DTYPE == LGN_F32 ? 0u : w[i] & 0x7fff0000u;
+            if (lo < 0x7f800000u) cand = max(cand, lo);
+            if (hi < 0x7f800000u) cand = max(cand, hi);
+        }
+        cand = wave_max(cand);
+        if (cand >= 0x00800000u) pivot_bits = cand;
+        pivot_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)pivot_bits);
     }
-    for (; v < nvec; v += gsize) accumulate_vec<DTYPE>(gv[v], t);
-    // ragged tail: fewer than EPV elements
-    const uint64_t tail = nvec * EPV + gtid;
-    if (gtid < (uint64_t)EPV && tail < n) accumulate(load_elem<DTYPE>(g, tail), t);
+    const float pivot = __builtin_amdgcn_logf(__uint_as_float(pivot_bits));
 
+    // Full rows, wave-uniform control flow.  A batch is four CONSECUTIVE rows (4 KiB contiguous
+    // per wave): strides of a power-of-two number of rows between the loads of one wave alias in
+    // the memory channels and cost ~20 % of the read bandwidth.  The next batch is requested
+    // before the current one is reduced, so the arithmetic overlaps the memory latency.
+    const uint64_t nbatches = nrows / 4;
+    uint64_t batch = wave;
+    bool have = batch < nbatches;
+    uint4 va, vb, vc, vd;
+    if (have) {
+        const uint4 *p = gv + batch * (4 * kWave) + lane;
+        va = p[0]; vb = p[kWave]; vc = p[2 * kWave]; vd = p[3 * kWave];
+    }
+    while (have) {
+        const uint64_t nbatch = batch + nwaves;
+        const bool nhave = nbatch < nbatches;
+        uint4 na, nb, nc, nd;
+        if (nhave) {
+            const uint4 *p = gv + nbatch * (4 * kWave) + lane;
+            na = p[0]; nb = p[kWave]; nc = p[2 * kWave]; nd = p[3 * kWave];
+        }
+        cnt += accumulate_vec<DTYPE>(va, pivot_bits, pivot, t);
+        cnt += accumulate_vec<DTYPE>(vb, pivot_bits, pivot, t);
+        cnt += accumulate_vec<DTYPE>(vc, pivot_bits, pivot, t);
+        cnt += accumulate_vec<DTYPE>(vd, pivot_bits, pivot, t);
+        if (nhave) { va = na; vb = nb; vc = nc; vd = nd; }
+        have = nhave;
+        batch = nbatch;
+    }
+    // up to three full rows after the last batch
+    for (uint64_t row = nbatches * 4 + wave; row < nrows; row += nwaves)
+        cnt += accumulate_vec<DTYPE>(gv[row * kWave + lane], pivot_bits, pivot, t);
+
+    // what is left: fewer than 64 vectors, then fewer than EPV elements; one wave, careful path
+    if (wave == nwaves - 1) {
+        const uint64_t v = nrows * kWave + lane;
+        if (v < nvec) {
+            const uint4 x = gv[v];
+            const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (DTYPE == LGN_F32) {
+                    accumulate_careful(w[i], pivot, t);
+                } else {
+                    accumulate_careful(w[i] << 16, pivot, t);
+                    accumulate_careful(w[i] & 0xffff0000u, pivot, t);
+                }
+            }
+        }
+        const uint64_t tail = nvec * EPV + lane;
+        if (lane < (uint32_t)EPV && tail < n) accumulate_careful(load_elem<DTYPE>(g, tail), pivot, t);
+    }
+
+    // wave totals relative to the wave's pivot, then (count, mean, M2)
+    const double s1 = wave_sum(t.s1), s2 = wave_sum(t.s2);
+    const double nn = (double)cnt + wave_sum((double)t.slow_cnt);
     BlockAcc b;
-    b.m.n = (double)t.cnt;
-    if (t.cnt) {
-        const double inv = 1.0 / (double)t.cnt;
-        b.m.mean = t.pivot + t.s1 * inv;
-        b.m.m2 = fmax(t.s2 - t.s1 * t.s1 * inv, 0.0);
+    b.m.n = nn;
+    if (nn > 0.0) {
+        b.m.mean = (double)pivot + s1 / nn;
+        b.m.m2 = fmax(s2 - s1 * (s1 / nn), 0.0);
     } else {
         b.m.mean = 0.0;
         b.m.m2 = 0.0;
     }
-    b.nonfinite = (double)t.nonfinite;
-    b.mx = t.mx;
-    b.mn = t.mn;
-    b = block_reduce(b);
+    b.nonfinite = wave_sum((double)t.nonfinite);
+    b.mx = wave_max(t.mx);
+    b.nmn = wave_max(t.nmn);
+    b = block_merge(b);
     if (threadIdx.x == 0) {
         Partial p;
         p.n = b.m.n; p.mean = b.m.mean; p.m2 = b.m.m2;
         p.nonfinite = (uint64_t)b.nonfinite;
-        p.mx = b.mx; p.mn = b.mn;
+        p.mx = b.mx; p.nmn = b.nmn;
         partials[blockIdx.x] = p;
     }
 }
@@ -183,9 +297,10 @@ __global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict
                                                        int count, uint64_t n,
                                                        lgn_stats_t *__restrict__ out)
 {
+    // lane-serial merge of the records in index order, then a fixed butterfly: reproducible
     BlockAcc b;
     b.m.n = 0.0; b.m.mean = 0.0; b.m.m2 = 0.0;
-    b.nonfinite = 0.0; b.mx = 0u; b.mn = 0xffffffffu;
+    b.nonfinite = 0.0; b.mx = 0u; b.nmn = 0u;
     for (int i = threadIdx.x; i < count; i += kBlock) {
         const Partial p = partials[i];
         Moments m;
@@ -193,9 +308,21 @@ __global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict
         b.m = merge(b.m, m);
         b.nonfinite += (double)p.nonfinite;
         b.mx = max(b.mx, p.mx);
-        b.mn = min(b.mn, p.mn);
+        b.nmn = max(b.nmn, p.nmn);
     }
-    b = block_reduce(b);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        Moments o;
+        o.n = __shfl_xor(b.m.n, off);
+        o.mean = __shfl_xor(b.m.mean, off);
+        o.m2 = __shfl_xor(b.m.m2, off);
+        const bool low = (threadIdx.x & off) == 0;  // both partners combine in the same order
+        b.m = low ? merge(b.m, o) : merge(o, b.m);
+        b.nonfinite += __shfl_xor(b.nonfinite, off);
+        b.mx = max(b.mx, (uint32_t)__shfl_xor((int)b.mx, off));
+        b.nmn = max(b.nmn, (uint32_t)__shfl_xor((int)b.nmn, off));
+    }
+    b = block_merge(b);
     if (threadIdx.x != 0) return;
     lgn_stats_t s;
     s.n = n;
@@ -214,13 +341,14 @@ __global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict
         s.status |= LGN_ST_EMPTY;
     } else {
         const double ln2 = 0.693147180559945309417232121458;
-        s.mean_log2 = b.m.mean - 127.0;  // remove the exponent bias
-        s.m2_log2 = b.m.m2;
+        const uint32_t mn = 0u - b.nmn;
+        s.mean_log2 = b.m.mean;
+        s.m2_log2 = b.mx == mn ? 0.0 : b.m.m2;
         s.mu = s.mean_log2 * ln2;
-        s.sigma = sqrt(b.m.m2 / b.m.n) * ln2;
+        s.sigma = sqrt(s.m2_log2 / b.m.n) * ln2;
         s.max_abs = __uint_as_float(b.mx);
-        s.min_abs_nz = __uint_as_float(b.mn);
-        if (b.mx == b.mn) s.status |= LGN_ST_SIGMA0;
+        s.min_abs_nz = __uint_as_float(mn);
+        if (b.mx == mn) s.status |= LGN_ST_SIGMA0;
     }
     *out = s;
 }
@@ -228,7 +356,7 @@ __global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict
 int stats_blocks(uint64_t n, int dtype)
 {
     const uint64_t epv = dtype == LGN_F32 ? 4 : 8;
-    uint64_t blocks = (n / epv + kBlock - 1) / kBlock;
+    uint64_t blocks = (n / epv + 4 * kBlock - 1) / (4 * kBlock);  // four rows per wave and pass
     if (blocks < 1) blocks = 1;
     if (blocks > (uint64_t)kMaxStatsBlocks) blocks = kMaxStatsBlocks;
     return (int)blocks;
@@ -237,9 +365,10 @@ int stats_blocks(uint64_t n, int dtype)
 size_t stats_workspace_bytes() { return sizeof(Partial) * (size_t)kMaxStatsBlocks; }
 
 hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws,
-                        hipStream_t stream)
+                        int max_blocks, hipStream_t stream)
 {
-    const int blocks = stats_blocks(n, dtype);
+    int blocks = stats_blocks(n, dtype);
+    if (blocks > max_blocks) blocks = max_blocks;
     Partial *partials = static_cast<Partial *>(ws);
     if (dtype == LGN_F32)
         stats_stage1<LGN_F32><<<blocks, kBlock, 0, stream>>>(g, n, partials);

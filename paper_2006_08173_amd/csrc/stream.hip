@@ -189,7 +189,8 @@ struct FastConst {
 };
 
 // One element of the fused / quantize-only fast path; returns the code (sign included).
-// `a` is |x| as a bit pattern, `keep` is false where pruning zeroed the element.
+// `a` is |x| as a bit pattern (already raised to alpha where pruning applies), `keep` is false
+// where pruning zeroed the element.
 template <int ROUND>
 __device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool keep, uint32_t w,
                                               const FastConst &c)
@@ -204,18 +205,20 @@ __device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool ke
     return (valid && keep) ? code : 0u;
 }
 
+template <int DTYPE>
+__device__ __forceinline__ const char *tile_in(const StreamArgs &a, uint64_t tile)
+{
+    return reinterpret_cast<const char *>(a.g) + tile * (uint64_t)(kWave * (DTYPE == LGN_F32 ? 16 : 8));
+}
+
+// A full tile whose loads are already in b[].
 // PRUNE: the call prunes; DO_PRUNE: alpha is non-zero, so pruning actually draws random words.
 template <int DTYPE, bool PRUNE, bool DO_PRUNE, bool QUANT, int ROUND, int OUT>
 __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, uint64_t qbase,
                                           int lane, PhiloxKey key, const FastConst &c,
-                                          const QuantConst &q)
+                                          const QuantConst &q, uint32_t b[4])
 {
-    // scalar tile base + 32-bit lane offset
     constexpr int QB = DTYPE == LGN_F32 ? 16 : 8;  // bytes per quad
-    const char *gin = reinterpret_cast<const char *>(a.g) + tile * (uint64_t)(kWave * QB);
-    uint32_t b[4];
-    load_quad<DTYPE>(gin, (uint32_t)lane, b);
-
     const uint32_t q_lo = (uint32_t)qbase + (uint32_t)lane;  // no carry: checked by the caller
     const uint32_t q_hi = (uint32_t)(qbase >> 32);
     const uint64_t p0 = (uint64_t)kPhiloxM0 * q_lo;           // shared by both purposes
@@ -271,6 +274,79 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
     }
 }
 
+// ---- general path: any tile, any offset, any scale ------------------------------------------
+template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
+__device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile, int lane,
+                                             PhiloxKey key, float alpha, const QuantConst &q,
+                                             uint64_t packed_total)
+{
+    const uint64_t n = a.n;
+    const uint32_t alpha_bits = __float_as_uint(alpha);
+    const uint64_t quad = tile * kWave + lane;  // index of this lane's four elements
+    const uint64_t i0 = quad * 4;
+    const bool full = (tile + 1) * 256 <= n;    // wave-uniform
+    uint32_t b[4];
+    if (full) {
+        load_quad<DTYPE>(a.g, quad, b);
+    } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) b[t] = i0 + t < n ? load_elem<DTYPE>(a.g, i0 + t) : 0u;
+    }
+    const uint64_t j0 = a.elem_offset + i0;
+    if (PRUNE && alpha_bits != 0u) {
+        uint32_t w[4];
+        quad_words(j0, 0u, key, w);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) b[t] = prune_bits(b[t], w[t], alpha_bits, alpha);
+    } else if (PRUNE) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) b[t] = (b[t] & 0x7fffffffu) ? b[t] : 0u;
+    }
+    if (!QUANT) {
+        if (full) {
+            store_quad<DTYPE>(a.out, quad, b);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (i0 + t < n) store_elem<DTYPE>(a.out, i0 + t, b[t]);
+        }
+        return;
+    }
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (ROUND == LGN_ROUND_STOCHASTIC) quad_words(j0, 1u, key, w);
+    uint32_t code[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) code[t] = quant_code<ROUND>(b[t], w[t], q);
+    if (OUT == LGN_OUT_VALUE) {
+        uint32_t v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            v[t] = (b[t] & 0x7fffffffu) > 0x7f800000u ? b[t] : code_value_bits(code[t], q);
+        if (full) {
+            store_quad<DTYPE>(a.out, quad, v);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (i0 + t < n) store_elem<DTYPE>(a.out, i0 + t, v[t]);
+        }
+    } else if (OUT == LGN_OUT_CODE8) {
+        if (full) {
+            reinterpret_cast<uint32_t *>(a.out)[quad] =
+                code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (i0 + t < n) reinterpret_cast<uint8_t *>(a.out)[i0 + t] = (uint8_t)code[t];
+        }
+    } else {
+        const int N = q.n_bits;
+        const uint32_t chunk = code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
+        const uint64_t tile_byte = tile * 32ull * (uint64_t)N;
+        pack_store_n(N, chunk, reinterpret_cast<uint8_t *>(a.out) + tile_byte,
+                     packed_total - tile_byte);
+    }
+}
+
 template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
 __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
 {
@@ -279,9 +355,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
     if (PRUNE) alpha = a.p->alpha;
     const uint32_t alpha_bits = __float_as_uint(alpha);
     QuantConst q = {8, 1, 6, 0, 0, 1, 255u};
-    if (QUANT) {
-        load_quant_const(a.f, q);
-    }
+    if (QUANT) load_quant_const(a.f, q);
     const uint64_t n = a.n;
     const uint64_t ntiles = (n + 255) / 256;
     const uint64_t nwaves = (uint64_t)gridDim.x * (kBlock / kWave);
@@ -308,78 +382,33 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
                          (!QUANT || (q.cbias >= 0 && q.cbias <= 254)) &&
                          (!do_prune || (alpha_bits >= 0x12000000u && alpha_bits < 0x7f800000u));
     const uint64_t qoff = a.elem_offset >> 2;
+    // a tile is fast if it is full and its 64 quad indices share the upper counter word
+    auto is_fast = [&](uint64_t t) {
+        return fast_ok && t < ntiles && (t + 1) * 256 <= n &&
+               (uint32_t)(qoff + t * kWave) <= 0xffffffffu - (uint32_t)kWave;
+    };
 
-    for (uint64_t tile = wave; tile < ntiles; tile += nwaves) {
-        const bool full = (tile + 1) * 256 <= n;    // wave-uniform
-        const uint64_t qbase = qoff + tile * kWave;  // global quad index of lane 0
-        if (fast_ok && full && (uint32_t)qbase <= 0xffffffffu - (uint32_t)kWave) {
-            if (do_prune) fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q);
-            else fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q);
-            continue;
-        }
-        const uint64_t quad = tile * kWave + lane;  // index of this lane's four elements
-        const uint64_t i0 = quad * 4;
-        uint32_t b[4];
-        if (full) {
-            load_quad<DTYPE>(a.g, quad, b);
+    // The load of the next fast tile is issued before the current tile is processed, so the
+    // Philox and quantizer arithmetic of one tile overlaps the memory latency of the next.
+    uint64_t tile = wave;
+    uint32_t nb[4] = {0u, 0u, 0u, 0u};
+    bool have = is_fast(tile);
+    if (have) load_quad<DTYPE>(tile_in<DTYPE>(a, tile), (uint32_t)lane, nb);
+    while (tile < ntiles) {
+        const uint64_t next = tile + nwaves;
+        if (have) {
+            uint32_t b[4] = {nb[0], nb[1], nb[2], nb[3]};
+            have = is_fast(next);
+            if (have) load_quad<DTYPE>(tile_in<DTYPE>(a, next), (uint32_t)lane, nb);
+            const uint64_t qbase = qoff + tile * kWave;  // global quad index of lane 0
+            if (do_prune) fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q, b);
+            else fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q, b);
         } else {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) b[t] = i0 + t < n ? load_elem<DTYPE>(a.g, i0 + t) : 0u;
+            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, tile, lane, key, alpha, q, packed_total);
+            have = is_fast(next);
+            if (have) load_quad<DTYPE>(tile_in<DTYPE>(a, next), (uint32_t)lane, nb);
         }
-        const uint64_t j0 = a.elem_offset + i0;
-        if (PRUNE && alpha_bits != 0u) {
-            uint32_t w[4];
-            quad_words(j0, 0u, key, w);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) b[t] = prune_bits(b[t], w[t], alpha_bits, alpha);
-        } else if (PRUNE) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) b[t] = (b[t] & 0x7fffffffu) ? b[t] : 0u;
-        }
-        if (!QUANT) {
-            if (full) {
-                store_quad<DTYPE>(a.out, quad, b);
-            } else {
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (i0 + t < n) store_elem<DTYPE>(a.out, i0 + t, b[t]);
-            }
-            continue;
-        }
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-        if (ROUND == LGN_ROUND_STOCHASTIC) quad_words(j0, 1u, key, w);
-        uint32_t code[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) code[t] = quant_code<ROUND>(b[t], w[t], q);
-        if (OUT == LGN_OUT_VALUE) {
-            uint32_t v[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                v[t] = (b[t] & 0x7fffffffu) > 0x7f800000u ? b[t] : code_value_bits(code[t], q);
-            if (full) {
-                store_quad<DTYPE>(a.out, quad, v);
-            } else {
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (i0 + t < n) store_elem<DTYPE>(a.out, i0 + t, v[t]);
-            }
-        } else if (OUT == LGN_OUT_CODE8) {
-            if (full) {
-                reinterpret_cast<uint32_t *>(a.out)[quad] =
-                    code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
-            } else {
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (i0 + t < n) reinterpret_cast<uint8_t *>(a.out)[i0 + t] = (uint8_t)code[t];
-            }
-        } else {
-            const int N = q.n_bits;
-            const uint32_t chunk =
-                code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
-            const uint64_t tile_byte = tile * 32ull * (uint64_t)N;
-            pack_store_n(N, chunk, reinterpret_cast<uint8_t *>(a.out) + tile_byte,
-                         packed_total - tile_byte);
-        }
+        tile = next;
     }
 }
 

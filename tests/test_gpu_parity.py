@@ -99,12 +99,13 @@ def test_stats_parity_special_values(lgn, dtype):
     assert want.n_nonfinite >= 3
     assert_stats_match(lgn.read_stats(lgn.lgn_stats(to_dev(g))), want)
     # only zeros / only non-finite / all equal / powers of two
-    for arr in (np.zeros(1000, np.float32), np.full(777, np.nan, np.float32),
-                np.full(5000, -3.25e-7, np.float32),
-                (2.0 ** np.arange(-140, 120, dtype=np.float64)).astype(np.float32)):
+    # logarithms of powers of two (normal and subnormal) are exact in the kernel's fixed point
+    for arr, rel in ((np.zeros(1000, np.float32), 1e-6), (np.full(777, np.nan, np.float32), 1e-6),
+                     (np.full(5000, -3.25e-7, np.float32), 1e-6),
+                     ((2.0 ** np.arange(-140, 120, dtype=np.float64)).astype(np.float32), 1e-13)):
         a = arr if dtype == SI.F32 else SI.f32_to_bf16_bits(arr)
         got = lgn.read_stats(lgn.lgn_stats(to_dev(a)))
-        assert_stats_match(got, O.stats(a), rel=1e-9)
+        assert_stats_match(got, O.stats(a), rel=rel)
     # all-equal input: zero spread exactly, not a cancellation residue
     a = np.full(100_000, 1.2345e-5, np.float32)
     got = lgn.read_stats(lgn.lgn_stats(to_dev(a)))
