@@ -123,7 +123,8 @@ typedef struct lgn_fp_params_t {
  *   code = sign << (e+m) | c << m | k,   c in [1, 2^e - 1],  value = (1 + k/2^m) 2^(c - 2^(e-1) + s)
  *   c = 0 encodes zero (whatever k and sign are).  No subnormal, Inf or NaN codes.
  *   |g| >= 2^(2^(e-1) + s) saturates to the largest code; |g| < 2^(1 - 2^(e-1) + s) flushes to
- *   zero, decided before rounding.  Zero and NaN inputs give code 0; with VALUE output NaN stays NaN.
+ *   zero, decided before rounding.  Zero gives code 0; Inf and NaN give the largest code of their
+ *   sign (with VALUE output NaN stays NaN).
  */
 
 /* Bytes of workspace lgn_stats needs for n elements (a few tens of KiB, independent of n
@@ -177,8 +178,9 @@ int lgn_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
 
 /*
  * Stochastic pruning (Section 5): out_i = g_i if |g_i| > alpha; else sign(g_i) alpha if
- * |g_i| >= fl32(alpha * u_i); else 0, with u_i = (word >> 8) / 2^24.  Zeros stay zero; NaN and
- * Inf pass through.  alpha is read from *p on the device (alpha = 0 copies the tensor).
+ * |g_i| >= fl32(alpha * u_i); else 0, with u_i = ((word >> 9) + 1/2) / 2^23 in (0, 1).  Zeros stay
+ * (+)zero; NaN and Inf pass through.  alpha is read from *p on the device (alpha = 0 keeps every
+ * non-zero element).
  *   out   device, n elements of `dtype`; may equal g (in place)
  */
 int lgn_prune(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p, uint64_t seed,

@@ -422,8 +422,8 @@ static uint32_t quantize_one(float x, int e, int m, int s, int rounding, uint32_
     int emax = 1 << (e - 1), etop = emax - 1, emin = 1 - emax;
     uint32_t sign = signbit(x) ? 1u << (e + m) : 0u;
     uint32_t maxmag = (1u << (e + m)) - 1u;
-    if (isnan(x) || x == 0.0f) return 0u;
-    if (isinf(x)) return sign | maxmag;
+    if (x == 0.0f) return 0u;
+    if (isnan(x) || isinf(x)) return sign | maxmag; /* not finite: saturates (NaN stays NaN in VALUE output) */
     int ex;
     double M = 2.0 * frexp(fabs((double)x), &ex); /* |x| = M 2^(ex-1), M in [1,2) */
     int E = (ex - 1) - s;

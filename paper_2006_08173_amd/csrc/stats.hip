@@ -221,28 +221,52 @@ __global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ 
     // the memory channels and cost ~20 % of the read bandwidth.  The next batch is requested
     // before the current one is reduced, so the arithmetic overlaps the memory latency.
     const uint64_t nbatches = nrows / 4;
-    uint64_t batch = wave;
-    bool have = batch < nbatches;
-    uint4 va, vb, vc, vd;
-    if (have) {
-        const uint4 *p = gv + batch * (4 * kWave) + lane;
-        va = p[0]; vb = p[kWave]; vc = p[2 * kWave]; vd = p[3 * kWave];
-    }
-    while (have) {
-        const uint64_t nbatch = batch + nwaves;
-        const bool nhave = nbatch < nbatches;
-        uint4 na, nb, nc, nd;
-        if (nhave) {
-            const uint4 *p = gv + nbatch * (4 * kWave) + lane;
-            na = p[0]; nb = p[kWave]; nc = p[2 * kWave]; nd = p[3 * kWave];
+    if (wave < nbatches) {
+        // Two register sets used alternately.  Inside the loop every load is unconditional, so
+        // the compiler waits for exactly the four older loads while the four younger ones stay in
+        // flight; the last batch of the wave is reduced after the loop.
+        uint4 a0, a1, a2, a3, b0, b1, b2, b3;
+        uint64_t cur = wave;  // batch held in the a-set
+        {
+            const uint4 *p = gv + cur * (4 * kWave) + lane;
+            a0 = p[0]; a1 = p[kWave]; a2 = p[2 * kWave]; a3 = p[3 * kWave];
         }
-        cnt += accumulate_vec<DTYPE>(va, pivot_bits, pivot, t);
-        cnt += accumulate_vec<DTYPE>(vb, pivot_bits, pivot, t);
-        cnt += accumulate_vec<DTYPE>(vc, pivot_bits, pivot, t);
-        cnt += accumulate_vec<DTYPE>(vd, pivot_bits, pivot, t);
-        if (nhave) { va = na; vb = nb; vc = nc; vd = nd; }
-        have = nhave;
-        batch = nbatch;
+        bool in_a = true;  // which set holds the batch that is still to be reduced
+        while (cur + nwaves < nbatches) {
+            {
+                const uint4 *p = gv + (cur + nwaves) * (4 * kWave) + lane;
+                b0 = p[0]; b1 = p[kWave]; b2 = p[2 * kWave]; b3 = p[3 * kWave];
+            }
+            cnt += accumulate_vec<DTYPE>(a0, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(a1, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(a2, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(a3, pivot_bits, pivot, t);
+            cur += nwaves;
+            if (!(cur + nwaves < nbatches)) {
+                in_a = false;
+                break;
+            }
+            {
+                const uint4 *p = gv + (cur + nwaves) * (4 * kWave) + lane;
+                a0 = p[0]; a1 = p[kWave]; a2 = p[2 * kWave]; a3 = p[3 * kWave];
+            }
+            cnt += accumulate_vec<DTYPE>(b0, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(b1, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(b2, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(b3, pivot_bits, pivot, t);
+            cur += nwaves;
+        }
+        if (in_a) {
+            cnt += accumulate_vec<DTYPE>(a0, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(a1, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(a2, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(a3, pivot_bits, pivot, t);
+        } else {
+            cnt += accumulate_vec<DTYPE>(b0, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(b1, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(b2, pivot_bits, pivot, t);
+            cnt += accumulate_vec<DTYPE>(b3, pivot_bits, pivot, t);
+        }
     }
     // up to three full rows after the last batch
     for (uint64_t row = nbatches * 4 + wave; row < nrows; row += nwaves)

@@ -110,8 +110,9 @@ __device__ __forceinline__ uint32_t quant_code(uint32_t bits, uint32_t w, const 
     }
     mag += up ? 1u : 0u;
     mag = min(mag, q.maxmag);                        // carry out of the top binade saturates
-    if (c > q.cmax || a == 0x7f800000u) mag = q.maxmag;
-    if (c < 1 || a == 0u || a > 0x7f800000u) return 0u;  // flush (before rounding), zero, NaN
+    if (a == 0u) return 0u;
+    if (c > q.cmax || a >= 0x7f800000u) mag = q.maxmag;  // above the range, Inf, NaN
+    else if (c < 1) return 0u;                           // flush, decided before rounding
     return ((bits >> 31) << (q.e + q.m)) | mag;
 }
 
@@ -180,29 +181,31 @@ struct FastConst {
     float alpha24;     // accepts): fl32(alpha u) = fma(k, alpha23, alpha24) for u = (k + 1/2) / 2^23
     uint32_t sub;      // cbias << 23: subtracting it re-biases the exponent field
     uint32_t lo_bits;  // smallest magnitude pattern that is not flushed
-    uint32_t span;     // magnitudes in [lo_bits, lo_bits + span) are finite and in range or above
     uint32_t maxmag;
     uint32_t cut;      // 23 - m
-    uint32_t rshift;   // 9 + m
+    uint32_t rmul;     // 2^(9+m)
     uint32_t sshift;   // e + m: position of the sign bit in a code
     uint32_t rnd;      // 2^(cut-1) - 1, the nearest-even increment before the parity bit
 };
 
 // One element of the fused / quantize-only fast path; returns the code (sign included).
 // `a` is |x| as a bit pattern (already raised to alpha where pruning applies), `keep` is false
-// where pruning zeroed the element.
-template <int ROUND>
+// where pruning zeroed the element.  Stochastic rounding is one 64-bit multiply-add: the upper
+// half of y * 2^(9+m) + w is (y + (w >> (9+m))) >> (23-m).  Inf and NaN have huge y and saturate.
+// CHECK_LO = false is used when every magnitude that reaches the quantizer is known to be at or
+// above the flush threshold (fused pass with alpha >= 2^(E_min+s)).
+template <int ROUND, bool CHECK_LO>
 __device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool keep, uint32_t w,
                                               const FastConst &c)
 {
     const uint32_t y = a - c.sub;
     uint32_t mag;
-    if (ROUND == LGN_ROUND_STOCHASTIC) mag = (y + (w >> c.rshift)) >> c.cut;
+    if (ROUND == LGN_ROUND_STOCHASTIC) mag = (uint32_t)(((uint64_t)y * c.rmul + w) >> 32);
     else mag = (y + c.rnd + ((y >> c.cut) & 1u)) >> c.cut;
     mag = min(mag, c.maxmag);
-    const bool valid = (a - c.lo_bits) < c.span;
     const uint32_t code = ((bits >> 31) << c.sshift) | mag;
-    return (valid && keep) ? code : 0u;
+    const bool valid = CHECK_LO ? (a >= c.lo_bits && keep) : keep;
+    return valid ? code : 0u;
 }
 
 template <int DTYPE>
@@ -213,7 +216,7 @@ __device__ __forceinline__ const char *tile_in(const StreamArgs &a, uint64_t til
 
 // A full tile whose loads are already in b[].
 // PRUNE: the call prunes; DO_PRUNE: alpha is non-zero, so pruning actually draws random words.
-template <int DTYPE, bool PRUNE, bool DO_PRUNE, bool QUANT, int ROUND, int OUT>
+template <int DTYPE, bool PRUNE, bool DO_PRUNE, bool QUANT, int ROUND, int OUT, bool CHECK_LO>
 __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, uint64_t qbase,
                                           int lane, PhiloxKey key, const FastConst &c,
                                           const QuantConst &q, uint32_t b[4])
@@ -255,7 +258,8 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
     }
     uint32_t code[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) code[t] = fast_code<ROUND>(b[t], mag_in[t], keep[t], w1[t], c);
+    for (int t = 0; t < 4; ++t)
+        code[t] = fast_code<ROUND, CHECK_LO>(b[t], mag_in[t], keep[t], w1[t], c);
     if (OUT == LGN_OUT_VALUE) {
         uint32_t v[4];
 #pragma unroll
@@ -371,13 +375,14 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
     c.alpha24 = alpha * 0x1p-24f;
     c.sub = (uint32_t)max(q.cbias, 0) << 23;
     c.lo_bits = (uint32_t)min(max(q.cbias + 1, 0), 256) << 23;
-    c.span = c.lo_bits <= 0x7f800000u ? 0x7f800001u - c.lo_bits : 0u;
     c.maxmag = q.maxmag;
     c.cut = 23u - (uint32_t)q.m;
-    c.rshift = 9u + (uint32_t)q.m;
+    c.rmul = 1u << (9u + (uint32_t)q.m);
     c.sshift = (uint32_t)(q.e + q.m);
     c.rnd = (1u << (c.cut - 1u)) - 1u;
     const bool do_prune = PRUNE && alpha_bits != 0u;
+    // pruning raises every surviving magnitude to alpha: no flush test needed if alpha is in range
+    const bool check_lo = !(do_prune && alpha_bits >= c.lo_bits);
     const bool fast_ok = (a.elem_offset & 3ull) == 0ull &&
                          (!QUANT || (q.cbias >= 0 && q.cbias <= 254)) &&
                          (!do_prune || (alpha_bits >= 0x12000000u && alpha_bits < 0x7f800000u));
@@ -401,8 +406,12 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
             have = is_fast(next);
             if (have) load_quad<DTYPE>(tile_in<DTYPE>(a, next), (uint32_t)lane, nb);
             const uint64_t qbase = qoff + tile * kWave;  // global quad index of lane 0
-            if (do_prune) fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q, b);
-            else fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT>(a, tile, qbase, lane, key, c, q, b);
+            if (do_prune && !check_lo)
+                fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, false>(a, tile, qbase, lane, key, c, q, b);
+            else if (do_prune)
+                fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, true>(a, tile, qbase, lane, key, c, q, b);
+            else
+                fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(a, tile, qbase, lane, key, c, q, b);
         } else {
             general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, tile, lane, key, alpha, q, packed_total);
             have = is_fast(next);
