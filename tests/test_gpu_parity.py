@@ -231,7 +231,9 @@ def test_prune_parity_sizes_offsets(lgn, dtype):
     p = dev_prune_params(lgn, alpha)
     for n in SIZES:
         g = mixed_tensor(n, 20 + n % 11, dtype)
-        for off in (0, 4, 1, 2, 3, (1 << 34) - 6, (1 << 40) + 5):
+        # aligned and unaligned offsets, and offsets that cross the 2^34 boundary where the
+        # upper Philox counter word changes
+        for off in (0, 4, 1, 2, 3, (1 << 34) - 6, (1 << 34) - 512, (1 << 40) + 5, 1 << 36):
             want = O.prune(g, alpha, 1234567890123, off)
             got = to_host(lgn.lgn_prune(to_dev(g), p, 1234567890123, off), g)
             assert np.array_equal(bits(got), bits(want)), (n, off)
@@ -316,7 +318,7 @@ def test_fused_parity_and_composition(lgn, dtype, rounding):
             f = dev_fp_params(lgn, e, m, s)
             nb = 1 + e + m
             for kind in (O.OUT_CODE8, O.OUT_PACKED, O.OUT_VALUE):
-                for off in (0, 6):
+                for off in (0, 6, (1 << 34) - 1024):
                     want = O.prune_quantize(g, alpha, e, m, s, rounding, 2024, off, kind)
                     got = to_host(lgn.lgn_prune_quantize_fused(d, p, f, rounding, 2024, off, out_kind=kind, n_bits=nb),
                                   g if kind == O.OUT_VALUE else None)
