@@ -30,7 +30,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM traffic of the dominant kernel per launch measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE, scaled by the same counters on a copy kernel of known size); see profiles/.
 # None until measured for the workload at hand.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/hot_path_c4_hbm_traffic.txt: FETCH_SIZE 401457.6 x 2.000 KiB + WRITE_SIZE 200704.0 x 1.000 KiB
+    ("c4", "code8", "stochastic", "stream_kernel (fused prune+quantize)"): int((401457.6 * 2.0 + 200704.0) * 1024),
+    ("c4", "code8", "stochastic", "stats_stage1"): int((405253.9 * 2.0 + 128.0) * 1024),
+}
 
 
 def parse():
@@ -43,7 +47,9 @@ def parse():
     ap.add_argument("--out-kind", default="code8", choices=["code8", "packed", "value"])
     ap.add_argument("--rounding", default="stochastic", choices=["stochastic", "nearest"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--breakdown", action="store_true", help="print per-kernel times to stderr")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run one plain elementwise copy of the tensor before the timed region "
+                         "(known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -121,6 +127,12 @@ def main():
         if ev:
             ev[3].record()
 
+    if args.copy_probe and cfg["dtype"] == SI.F32:
+        probe = torch.empty_like(d)
+        torch.mul(d, 1.0, out=probe)  # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del probe
+
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -170,7 +182,7 @@ def main():
         import oracle as O
         threads = O.max_threads()
         O.set_threads(threads)
-        m = min(n, 1 << 24)
+        m = min(n, 1 << 28)  # the whole tensor for configuration 4: ~1 s on 16 cores
         sample = SI.make(cfg, n=m)
         t1 = time.perf_counter()
         ost = O.stats(sample)
@@ -190,7 +202,7 @@ def main():
         "metric": "GB/s and % HBM peak for fused lognormal-stats+prune+FP-n quantize",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "u32" if in_bytes == 4 else "u32(bf16 in)",
+        "scaling": "weak", "vs_baseline": None, "dtype": "u32 (bit-level prune/quantize) + f64 (statistics, solver)",
         "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: {n} {cfg['dtype']} elements, zeros {cfg['zero_frac']}, "
                                f"ln|g|~N({cfg['mu']},{cfg['sigma']}^2); stats+threshold(S={sparsity})"
