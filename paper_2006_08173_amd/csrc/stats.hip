@@ -229,13 +229,13 @@ __global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ 
         uint64_t cur = wave;  // batch held in the a-set
         {
             const uint4 *p = gv + cur * (4 * kWave) + lane;
-            a0 = p[0]; a1 = p[kWave]; a2 = p[2 * kWave]; a3 = p[3 * kWave];
+            a0 = load_stream16(p); a1 = load_stream16(p + kWave); a2 = load_stream16(p + 2 * kWave); a3 = load_stream16(p + 3 * kWave);
         }
         bool in_a = true;  // which set holds the batch that is still to be reduced
         while (cur + nwaves < nbatches) {
             {
                 const uint4 *p = gv + (cur + nwaves) * (4 * kWave) + lane;
-                b0 = p[0]; b1 = p[kWave]; b2 = p[2 * kWave]; b3 = p[3 * kWave];
+                b0 = load_stream16(p); b1 = load_stream16(p + kWave); b2 = load_stream16(p + 2 * kWave); b3 = load_stream16(p + 3 * kWave);
             }
             cnt += accumulate_vec<DTYPE>(a0, pivot_bits, pivot, t);
             cnt += accumulate_vec<DTYPE>(a1, pivot_bits, pivot, t);
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ 
             }
             {
                 const uint4 *p = gv + (cur + nwaves) * (4 * kWave) + lane;
-                a0 = p[0]; a1 = p[kWave]; a2 = p[2 * kWave]; a3 = p[3 * kWave];
+                a0 = load_stream16(p); a1 = load_stream16(p + kWave); a2 = load_stream16(p + 2 * kWave); a3 = load_stream16(p + 3 * kWave);
             }
             cnt += accumulate_vec<DTYPE>(b0, pivot_bits, pivot, t);
             cnt += accumulate_vec<DTYPE>(b1, pivot_bits, pivot, t);

@@ -151,7 +151,7 @@ __device__ __forceinline__ void pack_store(uint32_t chunk, uint8_t *tile_out, ui
     if (lane < ND) {
         const uint64_t byte = 4ull * lane;
         if (byte + 4 <= bytes_valid) {
-            reinterpret_cast<uint32_t *>(tile_out)[lane] = dword;
+            __builtin_nontemporal_store(dword, reinterpret_cast<uint32_t *>(tile_out) + lane);
         } else {
             for (uint64_t b = byte; b < bytes_valid; ++b)
                 tile_out[b] = (uint8_t)(dword >> (8 * (b - byte)));
@@ -269,7 +269,8 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
         store_quad<DTYPE>(gout, (uint32_t)lane, v);
     } else if (OUT == LGN_OUT_CODE8) {
         uint32_t *gout = reinterpret_cast<uint32_t *>(a.out) + tile * (uint64_t)kWave;
-        gout[(uint32_t)lane] = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+        __builtin_nontemporal_store(code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
+                                    gout + (uint32_t)lane);
     } else {
         const int N = q.n_bits;
         const uint32_t chunk = code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
@@ -392,32 +393,47 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
         return fast_ok && t < ntiles && (t + 1) * 256 <= n &&
                (uint32_t)(qoff + t * kWave) <= 0xffffffffu - (uint32_t)kWave;
     };
+    auto run_fast = [&](uint64_t t, uint32_t *b) {
+        const uint64_t qbase = qoff + t * kWave;  // global quad index of lane 0
+        if (do_prune && !check_lo)
+            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, false>(a, t, qbase, lane, key, c, q, b);
+        else if (do_prune)
+            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, b);
+        else
+            fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, b);
+    };
 
-    // The load of the next fast tile is issued before the current tile is processed, so the
-    // Philox and quantizer arithmetic of one tile overlaps the memory latency of the next.
-    uint64_t tile = wave;
-    uint32_t nb[4] = {0u, 0u, 0u, 0u};
-    bool have = is_fast(tile);
-    if (have) load_quad<DTYPE>(tile_in<DTYPE>(a, tile), (uint32_t)lane, nb);
-    while (tile < ntiles) {
-        const uint64_t next = tile + nwaves;
+    // A wave walks PAIRS of consecutive tiles (2 KiB of fp32 input): both loads of the next pair are
+    // issued before the current pair is processed, so every wave keeps 2 KiB in flight while its
+    // Philox and quantizer arithmetic runs.  With eight waves per SIMD that is 16 KiB per SIMD,
+    // twice what the measured latency x bandwidth product asks for; one tile per step was not enough.
+    const uint64_t npairs = (ntiles + 1) / 2;
+    uint64_t pair = wave;
+    uint32_t nb[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    bool have = is_fast(2 * pair) && is_fast(2 * pair + 1);
+    if (have) {
+        load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * pair), (uint32_t)lane, nb);
+        load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * pair + 1), (uint32_t)lane, nb + 4);
+    }
+    while (pair < npairs) {
+        const uint64_t next = pair + nwaves;
+        const bool was = have;
+        uint32_t b[8] = {nb[0], nb[1], nb[2], nb[3], nb[4], nb[5], nb[6], nb[7]};
+        have = is_fast(2 * next) && is_fast(2 * next + 1);
         if (have) {
-            uint32_t b[4] = {nb[0], nb[1], nb[2], nb[3]};
-            have = is_fast(next);
-            if (have) load_quad<DTYPE>(tile_in<DTYPE>(a, next), (uint32_t)lane, nb);
-            const uint64_t qbase = qoff + tile * kWave;  // global quad index of lane 0
-            if (do_prune && !check_lo)
-                fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, false>(a, tile, qbase, lane, key, c, q, b);
-            else if (do_prune)
-                fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, true>(a, tile, qbase, lane, key, c, q, b);
-            else
-                fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(a, tile, qbase, lane, key, c, q, b);
-        } else {
-            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, tile, lane, key, alpha, q, packed_total);
-            have = is_fast(next);
-            if (have) load_quad<DTYPE>(tile_in<DTYPE>(a, next), (uint32_t)lane, nb);
+            load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * next), (uint32_t)lane, nb);
+            load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * next + 1), (uint32_t)lane, nb + 4);
         }
-        tile = next;
+        if (was) {
+            run_fast(2 * pair, b);
+            run_fast(2 * pair + 1, b + 4);
+        } else {
+            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair, lane, key, alpha, q, packed_total);
+            if (2 * pair + 1 < ntiles)
+                general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair + 1, lane, key, alpha, q,
+                                                              packed_total);
+        }
+        pair = next;
     }
 }
 
@@ -475,8 +491,8 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
                            : pick_round_out<LGN_BF16, true, false>(rounding, out_kind))
                   : pick_round_out<LGN_BF16, false, true>(rounding, out_kind);
     }
-    const uint64_t ntiles = (args.n + 255) / 256;
-    uint64_t blocks = (ntiles + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const uint64_t npairs = ((args.n + 255) / 256 + 1) / 2;  // a wave step covers two tiles
+    uint64_t blocks = (npairs + (kBlock / kWave) - 1) / (kBlock / kWave);
     if (blocks > (uint64_t)max_blocks) blocks = (uint64_t)max_blocks;
     hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(kBlock), 0, stream, args);
     return hipGetLastError();
