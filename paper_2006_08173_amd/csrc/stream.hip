@@ -352,8 +352,15 @@ __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile,
     }
 }
 
+// Waves per SIMD the register allocator is asked to leave room for.  Eight (64 VGPRs) is what
+// the streaming skeleton likes; the two heaviest variants would spill at that size.
+constexpr int stream_min_waves(bool prune, bool quant, int round, int out)
+{
+    return out == LGN_OUT_PACKED ? 4 : (prune && quant && round == LGN_ROUND_STOCHASTIC) ? 6 : 8;
+}
+
 template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
-__global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
+__global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT)) void stream_kernel(StreamArgs a)
 {
     const PhiloxKey key = {a.k0, a.k1};
     float alpha = 0.0f;
@@ -426,6 +433,9 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(StreamArgs a)
         }
         if (was) {
             run_fast(2 * pair, b);
+            // keep the two tiles' instruction streams apart: interleaving them doubles the live
+            // registers and costs two waves of occupancy
+            __builtin_amdgcn_sched_barrier(0);
             run_fast(2 * pair + 1, b + 4);
         } else {
             general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair, lane, key, alpha, q, packed_total);
