@@ -132,23 +132,38 @@ __device__ __forceinline__ uint32_t code_value_bits(uint32_t code, const QuantCo
     return sh > 24 ? sign : sign | ((0x800000u | mant) >> sh);
 }
 
-template <int N>
-__device__ __forceinline__ void pack_store(uint32_t chunk, uint8_t *tile_out, uint64_t bytes_valid)
+// PACKED output of one 256-element tile.  Lane k < 8N assembles dword k of the tile's 32N-byte run
+// from the chunks that overlap bits [32k, 32k+32): chunk index c0 = 32k / 4N onwards, at most
+// `nchunks` = ceil((4N - 1 + 32) / 4N) of them (wave-uniform; 2 for FP6, 5 for FP2).  c0 and the bit
+// offset `sh` depend only on the lane and on N, so they are computed once per kernel.
+struct PackLane {
+    int c0, sh, cb, nchunks, ndwords;
+};
+
+__device__ __forceinline__ PackLane pack_lane(int n_bits, int lane)
 {
-    constexpr int CB = 4 * N;  // bits per lane chunk
-    constexpr int ND = 8 * N;  // dwords per 256-element tile
-    constexpr int T = (CB - 1 + 32 + CB - 1) / CB;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int bit = 32 * lane;
-    const int c0 = bit / CB, sh = bit - c0 * CB;
+    PackLane p;
+    p.cb = 4 * n_bits;
+    p.c0 = (32 * lane) / p.cb;
+    p.sh = 32 * lane - p.c0 * p.cb;
+    p.nchunks = (p.cb - 1 + 32 + p.cb - 1) / p.cb;
+    p.ndwords = 8 * n_bits;
+    return p;
+}
+
+__device__ __forceinline__ void pack_store_n(const PackLane &p, int lane, uint32_t chunk,
+                                             uint8_t *tile_out, uint64_t bytes_valid)
+{
     uint64_t acc = 0;
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-        const uint32_t v = __shfl(chunk, (c0 + t) & (kWave - 1));
-        if (c0 + t < kWave && t * CB < 64) acc |= (uint64_t)v << (t * CB);
+    for (int t = 0; t < 5; ++t) {
+        if (t < p.nchunks) {  // wave-uniform
+            const uint32_t v = __shfl(chunk, (p.c0 + t) & (kWave - 1));
+            acc |= (uint64_t)v << (t * p.cb);  // (nchunks - 1) * cb < 64 for every N in [2, 8]
+        }
     }
-    const uint32_t dword = (uint32_t)(acc >> sh);
-    if (lane < ND) {
+    const uint32_t dword = (uint32_t)(acc >> p.sh);
+    if (lane < p.ndwords) {
         const uint64_t byte = 4ull * lane;
         if (byte + 4 <= bytes_valid) {
             __builtin_nontemporal_store(dword, reinterpret_cast<uint32_t *>(tile_out) + lane);
@@ -156,20 +171,6 @@ __device__ __forceinline__ void pack_store(uint32_t chunk, uint8_t *tile_out, ui
             for (uint64_t b = byte; b < bytes_valid; ++b)
                 tile_out[b] = (uint8_t)(dword >> (8 * (b - byte)));
         }
-    }
-}
-
-__device__ __forceinline__ void pack_store_n(int n_bits, uint32_t chunk, uint8_t *tile_out,
-                                             uint64_t bytes_valid)
-{
-    switch (n_bits) {  // wave-uniform
-    case 2: pack_store<2>(chunk, tile_out, bytes_valid); break;
-    case 3: pack_store<3>(chunk, tile_out, bytes_valid); break;
-    case 4: pack_store<4>(chunk, tile_out, bytes_valid); break;
-    case 5: pack_store<5>(chunk, tile_out, bytes_valid); break;
-    case 6: pack_store<6>(chunk, tile_out, bytes_valid); break;
-    case 7: pack_store<7>(chunk, tile_out, bytes_valid); break;
-    default: pack_store<8>(chunk, tile_out, bytes_valid); break;
     }
 }
 
@@ -219,7 +220,7 @@ __device__ __forceinline__ const char *tile_in(const StreamArgs &a, uint64_t til
 template <int DTYPE, bool PRUNE, bool DO_PRUNE, bool QUANT, int ROUND, int OUT, bool CHECK_LO>
 __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, uint64_t qbase,
                                           int lane, PhiloxKey key, const FastConst &c,
-                                          const QuantConst &q, uint32_t b[4])
+                                          const QuantConst &q, const PackLane &pk, uint32_t b[4])
 {
     constexpr int QB = DTYPE == LGN_F32 ? 16 : 8;  // bytes per quad
     const uint32_t q_lo = (uint32_t)qbase + (uint32_t)lane;  // no carry: checked by the caller
@@ -274,7 +275,7 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
     } else {
         const int N = q.n_bits;
         const uint32_t chunk = code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
-        pack_store_n(N, chunk, reinterpret_cast<uint8_t *>(a.out) + tile * 32ull * (uint64_t)N,
+        pack_store_n(pk, lane, chunk, reinterpret_cast<uint8_t *>(a.out) + tile * 32ull * (uint64_t)N,
                      ~0ull);
     }
 }
@@ -283,7 +284,7 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
 template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
 __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile, int lane,
                                              PhiloxKey key, float alpha, const QuantConst &q,
-                                             uint64_t packed_total)
+                                             const PackLane &pk, uint64_t packed_total)
 {
     const uint64_t n = a.n;
     const uint32_t alpha_bits = __float_as_uint(alpha);
@@ -347,7 +348,7 @@ __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile,
         const int N = q.n_bits;
         const uint32_t chunk = code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
         const uint64_t tile_byte = tile * 32ull * (uint64_t)N;
-        pack_store_n(N, chunk, reinterpret_cast<uint8_t *>(a.out) + tile_byte,
+        pack_store_n(pk, lane, chunk, reinterpret_cast<uint8_t *>(a.out) + tile_byte,
                      packed_total - tile_byte);
     }
 }
@@ -356,7 +357,8 @@ __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile,
 // the streaming skeleton likes; the two heaviest variants would spill at that size.
 constexpr int stream_min_waves(bool prune, bool quant, int round, int out)
 {
-    return out == LGN_OUT_PACKED ? 4 : (prune && quant && round == LGN_ROUND_STOCHASTIC) ? 6 : 8;
+    const bool heavy = prune && quant && round == LGN_ROUND_STOCHASTIC;
+    return out == LGN_OUT_PACKED ? (heavy ? 5 : 6) : (heavy ? 6 : 8);
 }
 
 template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
@@ -375,6 +377,7 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
     const uint64_t wave = (uint64_t)blockIdx.x * (kBlock / kWave) +
                           (uint64_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint64_t packed_total = (n * (uint64_t)q.n_bits + 7) / 8;
+    const PackLane pk = pack_lane(q.n_bits, lane);
 
     // Fast-path eligibility that does not depend on the tile (all wave-uniform).
     FastConst c;
@@ -403,11 +406,11 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
     auto run_fast = [&](uint64_t t, uint32_t *b) {
         const uint64_t qbase = qoff + t * kWave;  // global quad index of lane 0
         if (do_prune && !check_lo)
-            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, false>(a, t, qbase, lane, key, c, q, b);
+            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, false>(a, t, qbase, lane, key, c, q, pk, b);
         else if (do_prune)
-            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, b);
+            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, pk, b);
         else
-            fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, b);
+            fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, pk, b);
     };
 
     // A wave walks PAIRS of consecutive tiles (2 KiB of fp32 input): both loads of the next pair are
@@ -438,10 +441,10 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
             __builtin_amdgcn_sched_barrier(0);
             run_fast(2 * pair + 1, b + 4);
         } else {
-            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair, lane, key, alpha, q, packed_total);
+            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair, lane, key, alpha, q, pk, packed_total);
             if (2 * pair + 1 < ntiles)
                 general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair + 1, lane, key, alpha, q,
-                                                              packed_total);
+                                                              pk, packed_total);
         }
         pair = next;
     }
