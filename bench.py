@@ -5,6 +5,10 @@ One step = one pass of the whole path over one gradient tensor already resident 
 
     lgn_stats -> lgn_threshold -> lgn_fp_params -> lgn_prune_quantize_fused
 
+By default the first three run as ONE launch (lgn_stats_solve: the last workgroup of the statistics
+pass runs both solvers; results identical to the separate calls), so a step is two launches;
+--launches separate times the calls one by one.
+
 Workload (default): the ResNet-50-style activation gradient of the benchmark configurations,
 256x256x56x56 = 205 520 896 fp32 elements, 40 % exact zeros, ln|g| ~ N(-13, 2^2) (seeded
 synthetic data standing in for ImageNet gradients); target sparsity 0.85, FP6 with the
@@ -42,10 +46,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--n", type=int, default=None, help="override the element count")
     ap.add_argument("--out-kind", default="code8", choices=["code8", "packed", "value"])
     ap.add_argument("--rounding", default="stochastic", choices=["stochastic", "nearest"])
+    ap.add_argument("--launches", default="merged", choices=["merged", "separate"],
+                    help="merged: lgn_stats_solve + lgn_prune_quantize_fused (two launches per step); "
+                         "separate: lgn_stats, lgn_threshold, lgn_fp_params, lgn_prune_quantize_fused")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain elementwise copy of the tensor before the timed region "
@@ -55,6 +62,63 @@ def parse():
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def bench_c3(args, lgn, SI, torch, np):
+    """Twenty tensors with ResNet-18 activation-gradient shapes, twenty whole chains back to back on
+    one stream (no host synchronisation in between): total algorithmic bytes / total time."""
+    tensors = SI.config_c3()
+    rounding = lgn.LGN_ROUND_STOCHASTIC if args.rounding == "stochastic" else lgn.LGN_ROUND_NEAREST_EVEN
+    items = []
+    for cfg in tensors:
+        d = torch.from_numpy(SI.make(cfg)).cuda()
+        items.append(dict(cfg=cfg, d=d, out=torch.empty(cfg["n"], dtype=torch.uint8, device="cuda"),
+                          st=torch.empty(72, dtype=torch.uint8, device="cuda"),
+                          pp=torch.empty(24, dtype=torch.uint8, device="cuda"),
+                          fp=torch.empty(32, dtype=torch.uint8, device="cuda")))
+    ws = lgn.workspace(items[0]["d"].device)
+    total_n = sum(c["n"] for c in tensors)
+
+    merged = args.launches == "merged"
+
+    def one_step():
+        for it in items:
+            c = it["cfg"]
+            if merged:
+                lgn.lgn_stats_solve(it["d"], c["sparsity"], lgn.LGN_F32, c["n_bits"], st=it["st"],
+                                    p=it["pp"], f=it["fp"], ws=ws)
+            else:
+                lgn.lgn_stats(it["d"], out=it["st"], ws=ws)
+                lgn.lgn_threshold(it["st"], c["sparsity"], lgn.LGN_F32, out=it["pp"])
+                lgn.lgn_fp_params(it["st"], c["n_bits"], out=it["fp"])
+            lgn.lgn_prune_quantize_fused(it["d"], it["pp"], it["fp"], rounding, c["rng_seed"], 0,
+                                         out=it["out"], out_kind=lgn.LGN_OUT_CODE8)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    alg = total_n * 9
+    value = alg / (ms * 1e-3) / 1e9
+    log(f"[bench] c3: {len(items)} tensors, {total_n} elements, {ms:.4f} ms per step, {value:.0f} GB/s")
+    print(json.dumps({
+        "metric": "GB/s and % HBM peak for fused lognormal-stats+prune+FP-n quantize", "value": round(value, 1),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 (bit-level prune/quantize) + f64 (statistics, solver)", "data": "synthetic",
+        "config": {"workload": "c3: 20 fp32 tensors with ResNet-18 activation-gradient shapes at batch 256, "
+                               "per-tensor mu, sigma and target sparsity, 20 whole chains back to back "
+                               f"({'2' if merged else '5'} launches each), "
+                               f"{args.rounding} rounding, code8 output",
+                   "elements": total_n, "algorithmic_bytes_per_step": alg,
+                   "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)},
+        "roofline": {"bound": "hbm", "kernel": "whole chain (%d launches)" % (40 if merged else 100), "achieved": round(value, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(value / HBM_PEAK_GBS, 4), "traffic": None},
+        "cpu_baseline": None}), flush=True)
 
 
 def main():
@@ -72,6 +136,8 @@ def main():
     torch.cuda.set_device(0)
     lgn.load()
 
+    if args.workload == "c3":
+        return bench_c3(args, lgn, SI, torch, np)
     cfg = {"c1": SI.config_c1, "c2": SI.config_c2, "c4": SI.config_c4, "c5": SI.config_c5}[args.workload]()
     if args.n:
         cfg["n"] = args.n
@@ -113,14 +179,22 @@ def main():
     fp = torch.empty(32, dtype=torch.uint8, device="cuda")
     ws = lgn.workspace(d.device)
 
+    alpha_dt = lgn.LGN_F32 if in_bytes == 4 else lgn.LGN_BF16
+    merged = args.launches == "merged"
+
     def one_step(ev=None):
         if ev:
             ev[0].record()
-        lgn.lgn_stats(d, out=st, ws=ws)
-        if ev:
-            ev[1].record()
-        lgn.lgn_threshold(st, sparsity, lgn.LGN_F32 if in_bytes == 4 else lgn.LGN_BF16, out=pp)
-        lgn.lgn_fp_params(st, n_bits, out=fp)
+        if merged:
+            lgn.lgn_stats_solve(d, sparsity, alpha_dt, n_bits, st=st, p=pp, f=fp, ws=ws)
+            if ev:
+                ev[1].record()
+        else:
+            lgn.lgn_stats(d, out=st, ws=ws)
+            if ev:
+                ev[1].record()
+            lgn.lgn_threshold(st, sparsity, alpha_dt, out=pp)
+            lgn.lgn_fp_params(st, n_bits, out=fp)
         if ev:
             ev[2].record()
         lgn.lgn_prune_quantize_fused(d, pp, fp, rounding, seed, 0, out=out, out_kind=out_kind)
@@ -167,7 +241,8 @@ def main():
         dom = dict(kernel="stream_kernel (fused prune+quantize)", achieved=fused_gbs,
                    bytes=fused_bytes, ms=t_fused)
     else:
-        dom = dict(kernel="stats_stage1", achieved=stats_gbs, bytes=stats_bytes, ms=t_stats)
+        dom = dict(kernel="stats_solve_kernel" if merged else "stats_stage1", achieved=stats_gbs,
+                   bytes=stats_bytes, ms=t_stats)
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, args.out_kind, args.rounding, dom["kernel"]))
     roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": round(dom["achieved"], 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom["achieved"] / HBM_PEAK_GBS, 4),
@@ -207,7 +282,8 @@ def main():
         "config": {"workload": f"{cfg['name']}: {n} {cfg['dtype']} elements, zeros {cfg['zero_frac']}, "
                                f"ln|g|~N({cfg['mu']},{cfg['sigma']}^2); stats+threshold(S={sparsity})"
                                f"+FP{n_bits} format+fused prune/quantize, {args.rounding} rounding, "
-                               f"{args.out_kind} output",
+                               f"{args.out_kind} output, "
+                               + ("2 launches (stats+solvers merged, fused)" if merged else "5 launches"),
                    "elements": n, "elements_per_s": round(n / (ms_per_step * 1e-3)),
                    "algorithmic_bytes_per_step": int(alg_bytes_step),
                    "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)},

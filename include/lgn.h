@@ -127,9 +127,14 @@ typedef struct lgn_fp_params_t {
  *   sign (with VALUE output NaN stays NaN).
  */
 
-/* Bytes of workspace lgn_stats needs for n elements (a few tens of KiB, independent of n
- * beyond a cap).  Host function, no device work. */
+/* Bytes of workspace lgn_stats and lgn_stats_solve need for n elements (a few tens of KiB,
+ * independent of n).  Host function, no device work. */
 size_t lgn_workspace_bytes(uint64_t n, int dtype);
+
+/* Prepares a workspace for lgn_stats_solve: clears the 64-byte ticket area at its end with a
+ * small fill kernel on `stream`.  Needed once per workspace (every lgn_stats_solve leaves the
+ * ticket cleared again); lgn_stats does not need it. */
+int lgn_workspace_init(void *ws, size_t ws_bytes, void *stream);
 
 /* Bytes of a PACKED output: ceil(n * n_bits / 8). Host function. */
 size_t lgn_packed_bytes(uint64_t n, int n_bits);
@@ -140,14 +145,34 @@ size_t lgn_packed_bytes(uint64_t n, int n_bits);
  *   g        device, n elements of `dtype`, read once
  *   out      device, one lgn_stats_t, written
  *   ws       device workspace of at least lgn_workspace_bytes(n, dtype) bytes, 8-byte aligned;
- *            contents on entry are irrelevant, contents on exit are unspecified
- * Two launches: per-block partial moments, then a one-block combine.  Logarithms are taken in
- * base 2 as (exponent field) + log2(mantissa) in fp32, accumulated in fp64 as deviations from a
- * per-thread pivot and merged pairwise, so the result does not suffer from cancellation.
+ *            the per-block records at its start are overwritten, the ticket area at its end is
+ *            not touched
+ * Two launches: per-block partial moments, then a one-block combine.  log2|g| is taken in fp32
+ * (one hardware instruction, relative error about 1e-7) and accumulated in fp64 as deviations
+ * from a per-wave pivot; partial results are merged pairwise as (count, mean, M2), so the result
+ * does not suffer from cancellation.
  * Errors: INVALID_ARG (null/misaligned), UNSUPPORTED (dtype), WORKSPACE, DEVICE.
  */
 int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, size_t ws_bytes,
               void *stream);
+
+/*
+ * lgn_stats, lgn_threshold and lgn_fp_params in ONE launch (same passages as those three): the
+ * workgroup that finishes last combines the per-block records and runs both solvers, so the two
+ * parameter structs are ready when the statistics pass ends.  Results are identical to the three
+ * separate calls.
+ *   target_sparsity  in [0, 1), or negative to skip the threshold (p_out may then be null)
+ *   n_bits           in [2, 8], or 0 to skip the format (f_out may then be null)
+ *   other arguments  as in lgn_stats / lgn_threshold / lgn_fp_params
+ *   ws               as for lgn_stats, and prepared once with lgn_workspace_init: the kernel
+ *                    counts finished workgroups in the ticket area, which must be zero on entry
+ *                    and is zero again on exit.  Calls that overlap in time need separate
+ *                    workspaces.
+ */
+int lgn_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity, int alpha_dtype,
+                    int n_bits, int e_bits, int scale_mode, double scale_arg, int sigma_units,
+                    lgn_stats_t *st_out, lgn_prune_params_t *p_out, lgn_fp_params_t *f_out,
+                    void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Threshold alpha such that stochastic pruning leaves a fraction `target_sparsity` of the WHOLE

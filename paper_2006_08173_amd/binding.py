@@ -58,7 +58,7 @@ _lib = None
 
 EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshold",
            "lgn_fp_params", "lgn_prune", "lgn_fp_quantize", "lgn_prune_quantize_fused",
-           "lgn_dequantize", "lgn_last_error", "lgn_version")
+           "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_last_error", "lgn_version")
 
 
 def library_path() -> str:
@@ -85,9 +85,11 @@ def load():
     L.lgn_fp_quantize.argtypes = [vp, u64, i32, vp, i32, u64, u64, vp, i32, vp]
     L.lgn_prune_quantize_fused.argtypes = [vp, u64, i32, vp, vp, i32, u64, u64, vp, i32, vp]
     L.lgn_dequantize.argtypes = [vp, u64, i32, vp, i32, vp, vp]
+    L.lgn_workspace_init.argtypes = [vp, sz, vp]
+    L.lgn_stats_solve.argtypes = [vp, u64, i32, dbl, i32, i32, i32, i32, dbl, i32, vp, vp, vp, vp, sz, vp]
     L.lgn_last_error.restype = C.c_char_p
     L.lgn_version.restype = i32
-    for name in EXPORTS[2:9]:
+    for name in EXPORTS[2:11]:
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -128,11 +130,13 @@ _ws_cache = {}
 
 
 def workspace(device) -> torch.Tensor:
-    """Per-device scratch tensor for lgn_stats (allocated once by torch)."""
+    """Per-device scratch tensor for lgn_stats / lgn_stats_solve (allocated once by torch and
+    prepared once with lgn_workspace_init)."""
     key = torch.device(device).index if torch.device(device).index is not None else torch.cuda.current_device()
     ws = _ws_cache.get(key)
     if ws is None:
         ws = torch.empty(lgn_workspace_bytes(0, LGN_F32), dtype=torch.uint8, device=f"cuda:{key}")
+        lgn_workspace_init(ws)
         _ws_cache[key] = ws
     return ws
 
@@ -159,6 +163,36 @@ def lgn_stats(g: torch.Tensor, out: torch.Tensor = None, ws: torch.Tensor = None
     _check(load().lgn_stats(g.data_ptr(), g.numel(), _dtype_code(g, dtype), out.data_ptr(),
                             ws.data_ptr(), ws.numel(), _stream()))
     return out
+
+
+def lgn_workspace_init(ws: torch.Tensor) -> None:
+    with torch.cuda.device(ws.device):
+        _check(load().lgn_workspace_init(ws.data_ptr(), ws.numel(), _stream()))
+
+
+def lgn_stats_solve(g: torch.Tensor, target_sparsity: float = -1.0, alpha_dtype: int = LGN_F32,
+                    n_bits: int = 0, e_bits: int = -1, scale_mode: int = LGN_SCALE_QUANTILE,
+                    scale_arg: float = 0.997, sigma_units: int = LGN_SIGMA_PAPER_LITERAL,
+                    st: torch.Tensor = None, p: torch.Tensor = None, f: torch.Tensor = None,
+                    ws: torch.Tensor = None, dtype=None):
+    """One launch for lgn_stats + lgn_threshold + lgn_fp_params; returns (st, p, f) buffers
+    (p is None without a target sparsity, f is None without n_bits)."""
+    g = _flat(g)
+    if st is None:
+        st = _struct_buf(C.sizeof(LgnStats), g.device)
+    if p is None and target_sparsity >= 0.0:
+        p = _struct_buf(C.sizeof(LgnPruneParams), g.device)
+    if f is None and n_bits:
+        f = _struct_buf(C.sizeof(LgnFpParams), g.device)
+    if ws is None:
+        ws = workspace(g.device)
+    _check(load().lgn_stats_solve(g.data_ptr(), g.numel(), _dtype_code(g, dtype), float(target_sparsity),
+                                  int(alpha_dtype), int(n_bits), int(e_bits), int(scale_mode),
+                                  float(scale_arg), int(sigma_units), st.data_ptr(),
+                                  p.data_ptr() if p is not None else None,
+                                  f.data_ptr() if f is not None else None,
+                                  ws.data_ptr(), ws.numel(), _stream()))
+    return st, p, f
 
 
 def lgn_threshold(st: torch.Tensor, target_sparsity: float, alpha_dtype: int = LGN_F32,

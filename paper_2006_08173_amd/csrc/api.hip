@@ -18,6 +18,12 @@ struct StreamArgs {
 hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws,
                         int max_blocks, hipStream_t stream);
 size_t stats_workspace_bytes();
+hipError_t launch_workspace_init(void *ws, hipStream_t stream);
+hipError_t launch_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity,
+                              int alpha_dtype, int n_bits, int e_bits, int scale_mode,
+                              double scale_arg, int sigma_units, lgn_stats_t *st,
+                              lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
+                              hipStream_t stream);
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
                             lgn_prune_params_t *out, hipStream_t stream);
 hipError_t launch_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
@@ -92,6 +98,44 @@ int stats_blocks_cap()
     return cached;
 }
 
+int check_stats_args(const void *g, uint64_t n, int dtype, const lgn_stats_t *out, const void *ws,
+                     size_t ws_bytes)
+{
+    if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (!out) return fail(LGN_ERR_INVALID_ARG, "null stats pointer");
+    if (!aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "stats struct not 8-byte aligned");
+    if (n && !g) return fail(LGN_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned(g, 16)) return fail(LGN_ERR_INVALID_ARG, "input tensor not 16-byte aligned");
+    if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
+    if (!ws || ws_bytes < lgn::stats_workspace_bytes())
+        return fail(LGN_ERR_WORKSPACE, "workspace missing or smaller than %zu bytes",
+                    lgn::stats_workspace_bytes());
+    if (!aligned(ws, 8)) return fail(LGN_ERR_WORKSPACE, "workspace not 8-byte aligned");
+    return LGN_OK;
+}
+
+int check_threshold_args(double target_sparsity, int alpha_dtype)
+{
+    if (!dtype_ok(alpha_dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown alpha dtype %d", alpha_dtype);
+    if (!(target_sparsity >= 0.0 && target_sparsity < 1.0))
+        return fail(LGN_ERR_INVALID_ARG, "target sparsity %g outside [0, 1)", target_sparsity);
+    return LGN_OK;
+}
+
+int check_fp_args(int n_bits, int e_bits, int scale_mode, double scale_arg, int sigma_units)
+{
+    if (n_bits < 2 || n_bits > 8) return fail(LGN_ERR_INVALID_ARG, "n_bits %d outside [2, 8]", n_bits);
+    if (e_bits != -1 && (e_bits < 1 || e_bits > n_bits - 1))
+        return fail(LGN_ERR_INVALID_ARG, "e_bits %d outside [1, %d]", e_bits, n_bits - 1);
+    if (scale_mode != LGN_SCALE_QUANTILE && scale_mode != LGN_SCALE_MAX && scale_mode != LGN_SCALE_CENTER)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown scale mode %d", scale_mode);
+    if (scale_mode == LGN_SCALE_QUANTILE && !(scale_arg > 0.0 && scale_arg < 1.0))
+        return fail(LGN_ERR_INVALID_ARG, "quantile %g outside (0, 1)", scale_arg);
+    if (sigma_units != LGN_SIGMA_PAPER_LITERAL && sigma_units != LGN_SIGMA_BASE2)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown sigma units %d", sigma_units);
+    return LGN_OK;
+}
+
 int check_stream_common(const void *g, uint64_t n, int dtype, const void *out, int out_kind)
 {
     if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
@@ -118,22 +162,47 @@ const char *lgn_last_error(void) { return g_err; }
 
 int lgn_version(void) { return LGN_VERSION; }
 
+int lgn_workspace_init(void *ws, size_t ws_bytes, void *stream)
+{
+    if (!ws || ws_bytes < lgn::stats_workspace_bytes())
+        return fail(LGN_ERR_WORKSPACE, "workspace missing or smaller than %zu bytes",
+                    lgn::stats_workspace_bytes());
+    if (!aligned(ws, 8)) return fail(LGN_ERR_WORKSPACE, "workspace not 8-byte aligned");
+    const hipError_t e = lgn::launch_workspace_init(ws, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_workspace_init", e);
+}
+
 int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, size_t ws_bytes,
               void *stream)
 {
-    if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
-    if (!out) return fail(LGN_ERR_INVALID_ARG, "null stats pointer");
-    if (!aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "stats struct not 8-byte aligned");
-    if (n && !g) return fail(LGN_ERR_INVALID_ARG, "null tensor pointer");
-    if (!aligned(g, 16)) return fail(LGN_ERR_INVALID_ARG, "input tensor not 16-byte aligned");
-    if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
-    if (!ws || ws_bytes < lgn_workspace_bytes(n, dtype))
-        return fail(LGN_ERR_WORKSPACE, "workspace missing or smaller than %zu bytes",
-                    lgn_workspace_bytes(n, dtype));
-    if (!aligned(ws, 8)) return fail(LGN_ERR_WORKSPACE, "workspace not 8-byte aligned");
+    if (int rc = check_stats_args(g, n, dtype, out, ws, ws_bytes)) return rc;
     const hipError_t e = lgn::launch_stats(g, n, dtype, out, ws, stats_blocks_cap(),
                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats", e);
+}
+
+int lgn_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity, int alpha_dtype,
+                    int n_bits, int e_bits, int scale_mode, double scale_arg, int sigma_units,
+                    lgn_stats_t *st_out, lgn_prune_params_t *p_out, lgn_fp_params_t *f_out,
+                    void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_stats_args(g, n, dtype, st_out, ws, ws_bytes)) return rc;
+    const bool want_p = target_sparsity >= 0.0 || target_sparsity != target_sparsity;
+    if (want_p) {
+        if (int rc = check_threshold_args(target_sparsity, alpha_dtype)) return rc;
+        if (!p_out || !aligned(p_out, 8))
+            return fail(LGN_ERR_INVALID_ARG, "prune params struct null or not 8-byte aligned");
+    }
+    if (n_bits != 0) {
+        if (int rc = check_fp_args(n_bits, e_bits, scale_mode, scale_arg, sigma_units)) return rc;
+        if (!f_out || !aligned(f_out, 8))
+            return fail(LGN_ERR_INVALID_ARG, "fp params struct null or not 8-byte aligned");
+    }
+    const hipError_t e = lgn::launch_stats_solve(
+        g, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
+        scale_arg, sigma_units, st_out, want_p ? p_out : nullptr, n_bits ? f_out : nullptr, ws,
+        stats_blocks_cap(), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_solve", e);
 }
 
 int lgn_threshold(const lgn_stats_t *st, double target_sparsity, int alpha_dtype,
@@ -141,9 +210,7 @@ int lgn_threshold(const lgn_stats_t *st, double target_sparsity, int alpha_dtype
 {
     if (!st || !out) return fail(LGN_ERR_INVALID_ARG, "null struct pointer");
     if (!aligned(st, 8) || !aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "struct not 8-byte aligned");
-    if (!dtype_ok(alpha_dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown alpha dtype %d", alpha_dtype);
-    if (!(target_sparsity >= 0.0 && target_sparsity < 1.0))
-        return fail(LGN_ERR_INVALID_ARG, "target sparsity %g outside [0, 1)", target_sparsity);
+    if (int rc = check_threshold_args(target_sparsity, alpha_dtype)) return rc;
     const hipError_t e = lgn::launch_threshold(st, target_sparsity, alpha_dtype, out,
                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_threshold", e);
@@ -154,15 +221,7 @@ int lgn_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
 {
     if (!st || !out) return fail(LGN_ERR_INVALID_ARG, "null struct pointer");
     if (!aligned(st, 8) || !aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "struct not 8-byte aligned");
-    if (n_bits < 2 || n_bits > 8) return fail(LGN_ERR_INVALID_ARG, "n_bits %d outside [2, 8]", n_bits);
-    if (e_bits != -1 && (e_bits < 1 || e_bits > n_bits - 1))
-        return fail(LGN_ERR_INVALID_ARG, "e_bits %d outside [1, %d]", e_bits, n_bits - 1);
-    if (scale_mode != LGN_SCALE_QUANTILE && scale_mode != LGN_SCALE_MAX && scale_mode != LGN_SCALE_CENTER)
-        return fail(LGN_ERR_UNSUPPORTED, "unknown scale mode %d", scale_mode);
-    if (scale_mode == LGN_SCALE_QUANTILE && !(scale_arg > 0.0 && scale_arg < 1.0))
-        return fail(LGN_ERR_INVALID_ARG, "quantile %g outside (0, 1)", scale_arg);
-    if (sigma_units != LGN_SIGMA_PAPER_LITERAL && sigma_units != LGN_SIGMA_BASE2)
-        return fail(LGN_ERR_UNSUPPORTED, "unknown sigma units %d", sigma_units);
+    if (int rc = check_fp_args(n_bits, e_bits, scale_mode, scale_arg, sigma_units)) return rc;
     const hipError_t e = lgn::launch_fp_params(st, n_bits, e_bits, scale_mode, scale_arg,
                                                sigma_units, out, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_fp_params", e);

@@ -17,6 +17,7 @@
 // subnormals with integer operations.  Zeros contribute a zero deviation and are counted out
 // with a ballot / popcount on the scalar unit.
 #include "lgn_device.hpp"
+#include "solver_device.hpp"
 
 namespace lgn {
 
@@ -177,9 +178,28 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;  // the xor butterfly adds the same pairs in every lane: all lanes agree
 }
 
-template <int DTYPE>
-__global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ g, uint64_t n,
-                                                       Partial *__restrict__ partials)
+// Stores of a per-block record.  The plain form is for a consumer in a LATER launch.  The
+// write-through form is for a consumer in the SAME launch on another XCD: each word goes out as a
+// device-scope atomic store (written through this XCD's L2), so waiting for the stores to complete
+// makes the record visible device-wide without writing back the whole L2, which a device-scope
+// release fence would do (measured: +40 us on a 140 us pass when every workgroup issues one).
+__device__ __forceinline__ void store_partial(Partial *dst, const Partial &p, bool write_through)
+{
+    if (!write_through) {
+        *dst = p;
+        return;
+    }
+    static_assert(sizeof(Partial) == 40, "five 8-byte words");
+    unsigned long long w[5];
+    __builtin_memcpy(w, &p, sizeof p);
+    unsigned long long *d = reinterpret_cast<unsigned long long *>(dst);
+#pragma unroll
+    for (int i = 0; i < 5; ++i) __hip_atomic_store(d + i, w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int DTYPE, bool WRITE_THROUGH>
+__device__ __forceinline__ void stage1_body(const void *__restrict__ g, uint64_t n,
+                                            Partial *partials)
 {
     constexpr int EPV = DTYPE == LGN_F32 ? 4 : 8;  // elements per 16-byte vector
     constexpr int kWavesPerBlock = kBlock / kWave;
@@ -313,13 +333,20 @@ __global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ 
         p.n = b.m.n; p.mean = b.m.mean; p.m2 = b.m.m2;
         p.nonfinite = (uint64_t)b.nonfinite;
         p.mx = b.mx; p.nmn = b.nmn;
-        partials[blockIdx.x] = p;
+        store_partial(partials + blockIdx.x, p, WRITE_THROUGH);
     }
 }
 
-__global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict__ partials,
-                                                       int count, uint64_t n,
-                                                       lgn_stats_t *__restrict__ out)
+template <int DTYPE>
+__global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ g, uint64_t n,
+                                                       Partial *__restrict__ partials)
+{
+    stage1_body<DTYPE, false>(g, n, partials);
+}
+
+// Merges `count` per-block records; thread 0 writes the result to *out and, if given, to *lds_out.
+__device__ __forceinline__ void stage2_body(const Partial *partials, int count, uint64_t n,
+                                            lgn_stats_t *out, lgn_stats_t *lds_out)
 {
     // lane-serial merge of the records in index order, then a fixed butterfly: reproducible
     BlockAcc b;
@@ -375,6 +402,62 @@ __global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict
         if (b.mx == mn) s.status |= LGN_ST_SIGMA0;
     }
     *out = s;
+    if (lds_out) *lds_out = s;
+}
+
+__global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict__ partials,
+                                                       int count, uint64_t n,
+                                                       lgn_stats_t *__restrict__ out)
+{
+    stage2_body(partials, count, n, out, nullptr);
+}
+
+// ---- one launch for statistics + both parameter solves -------------------------------------
+// Every workgroup publishes its record, then takes a ticket; the workgroup that draws the last
+// ticket merges all records (stage 2) and runs the two solvers in two of its waves.  The ticket
+// lives at the end of the workspace, must be zero on entry and is reset to zero on exit.
+struct SolveRequest {
+    double target_sparsity;  // < 0: no threshold asked for
+    int alpha_dtype;
+    int n_bits;              // 0: no format asked for
+    int e_bits, scale_mode, sigma_units;
+    double scale_arg;
+};
+
+template <int DTYPE>
+__global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restrict__ g, uint64_t n,
+                                                             Partial *partials, unsigned int *ticket,
+                                                             SolveRequest rq, lgn_stats_t *st_out,
+                                                             lgn_prune_params_t *p_out,
+                                                             lgn_fp_params_t *f_out)
+{
+    stage1_body<DTYPE, true>(g, n, partials);
+    __shared__ bool is_last;
+    __shared__ lgn_stats_t st_lds;
+    if (threadIdx.x == 0) {
+        // Thread 0 wrote the record with write-through stores; once they have completed
+        // (s_waitcnt 0 = every counter at zero) the record is in memory, and only then is the
+        // ticket taken.  The signal fences keep the compiler from moving memory operations
+        // across the wait.
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        __builtin_amdgcn_s_waitcnt(0);
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        is_last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                  gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    // one workgroup only: drop what this XCD's caches hold, then read every record
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    stage2_body(partials, (int)gridDim.x, n, st_out, &st_lds);
+    __syncthreads();
+    const int wave = threadIdx.x / kWave;
+    if (wave == 0 && p_out && rq.target_sparsity >= 0.0) {
+        if ((threadIdx.x & (kWave - 1)) == 0) threshold_body(&st_lds, rq.target_sparsity, rq.alpha_dtype, p_out);
+    } else if (wave == 1 && f_out && rq.n_bits != 0) {
+        fp_params_body(&st_lds, rq.n_bits, rq.e_bits, rq.scale_mode, rq.scale_arg, rq.sigma_units, f_out);
+    }
+    if (threadIdx.x == 0) *ticket = 0u;  // ready for the next call on this workspace
 }
 
 int stats_blocks(uint64_t n, int dtype)
@@ -386,7 +469,21 @@ int stats_blocks(uint64_t n, int dtype)
     return (int)blocks;
 }
 
-size_t stats_workspace_bytes() { return sizeof(Partial) * (size_t)kMaxStatsBlocks; }
+constexpr size_t kTicketOffset = sizeof(Partial) * (size_t)kMaxStatsBlocks;  // 8-byte aligned
+
+size_t stats_workspace_bytes() { return kTicketOffset + 64; }
+
+__global__ void ticket_clear_kernel(unsigned int *ticket)
+{
+    if (threadIdx.x < 16) ticket[threadIdx.x] = 0u;
+}
+
+hipError_t launch_workspace_init(void *ws, hipStream_t stream)
+{
+    ticket_clear_kernel<<<1, kWave, 0, stream>>>(
+        reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset));
+    return hipGetLastError();
+}
 
 hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws,
                         int max_blocks, hipStream_t stream)
@@ -401,6 +498,25 @@ hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     stats_stage2<<<1, kBlock, 0, stream>>>(partials, blocks, n, out);
+    return hipGetLastError();
+}
+
+
+hipError_t launch_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity,
+                              int alpha_dtype, int n_bits, int e_bits, int scale_mode,
+                              double scale_arg, int sigma_units, lgn_stats_t *st,
+                              lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
+                              hipStream_t stream)
+{
+    int blocks = stats_blocks(n, dtype);
+    if (blocks > max_blocks) blocks = max_blocks;
+    Partial *partials = static_cast<Partial *>(ws);
+    unsigned int *ticket = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset);
+    const SolveRequest rq = {target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode, sigma_units, scale_arg};
+    if (dtype == LGN_F32)
+        stats_solve_kernel<LGN_F32><<<blocks, kBlock, 0, stream>>>(g, n, partials, ticket, rq, st, p, f);
+    else
+        stats_solve_kernel<LGN_BF16><<<blocks, kBlock, 0, stream>>>(g, n, partials, ticket, rq, st, p, f);
     return hipGetLastError();
 }
 

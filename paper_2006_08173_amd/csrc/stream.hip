@@ -181,8 +181,10 @@ struct FastConst {
     float alpha23;     // alpha * 2^-23 and alpha * 2^-24 (exact for the alphas the fast path
     float alpha24;     // accepts): fl32(alpha u) = fma(k, alpha23, alpha24) for u = (k + 1/2) / 2^23
     uint32_t sub;      // cbias << 23: subtracting it re-biases the exponent field
+    uint32_t sub_hi;   // -(cbias << m) mod 2^32: the same subtraction applied to a magnitude code
     uint32_t lo_bits;  // smallest magnitude pattern that is not flushed
-    uint32_t maxmag;
+    uint32_t sat_bits; // smallest magnitude pattern that gives the largest code without rounding
+    uint32_t floor_bits;  // lower clamp of the magnitude: min(alpha, sat_bits) when pruning, else 0
     uint32_t cut;      // 23 - m
     uint32_t rmul;     // 2^(9+m)
     uint32_t sshift;   // e + m: position of the sign bit in a code
@@ -190,23 +192,48 @@ struct FastConst {
 };
 
 // One element of the fused / quantize-only fast path; returns the code (sign included).
-// `a` is |x| as a bit pattern (already raised to alpha where pruning applies), `keep` is false
-// where pruning zeroed the element.  Stochastic rounding is one 64-bit multiply-add: the upper
-// half of y * 2^(9+m) + w is (y + (w >> (9+m))) >> (23-m).  Inf and NaN have huge y and saturate.
+// `a` is |x| as a bit pattern, clamped to [floor_bits, sat_bits] by the caller: the lower clamp
+// raises what pruning keeps to alpha, the upper clamp is the saturation rule (a magnitude clamped
+// to sat_bits has no remainder, so rounding cannot carry past the largest code; Inf and NaN
+// patterns lie above sat_bits).  `keep` is false where pruning zeroed the element.  Stochastic
+// rounding is one 64-bit multiply-add: the upper half of y * 2^(9+m) + w is
+// (y + (w >> (9+m))) >> (23-m).
 // CHECK_LO = false is used when every magnitude that reaches the quantizer is known to be at or
 // above the flush threshold (fused pass with alpha >= 2^(E_min+s)).
 template <int ROUND, bool CHECK_LO>
 __device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool keep, uint32_t w,
                                               const FastConst &c)
 {
-    const uint32_t y = a - c.sub;
     uint32_t mag;
-    if (ROUND == LGN_ROUND_STOCHASTIC) mag = (uint32_t)(((uint64_t)y * c.rmul + w) >> 32);
-    else mag = (y + c.rnd + ((y >> c.cut) & 1u)) >> c.cut;
-    mag = min(mag, c.maxmag);
+    if (ROUND == LGN_ROUND_STOCHASTIC) {
+        // (a - sub) * 2^(9+m) + w, with the re-biasing folded into the upper word of the addend
+        // (sub * 2^(9+m) is a multiple of 2^32)
+        mag = (uint32_t)(((uint64_t)a * c.rmul + (((uint64_t)c.sub_hi << 32) | w)) >> 32);
+    } else {
+        const uint32_t y = a - c.sub;
+        mag = (y + c.rnd + ((y >> c.cut) & 1u)) >> c.cut;
+    }
     const uint32_t code = ((bits >> 31) << c.sshift) | mag;
     const bool valid = CHECK_LO ? (a >= c.lo_bits && keep) : keep;
     return valid ? code : 0u;
+}
+
+// clamp(x, lo, hi) for lo <= hi: the median of the three, one instruction.  The compiler forms
+// v_med3_u32 only for constant bounds, hence the asm; one bound sits in a vector register because
+// an instruction of this family reads at most one scalar register.
+__device__ __forceinline__ uint32_t clamp_u32(uint32_t x, uint32_t lo, uint32_t hi)
+{
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "s"(hi));
+    return r;
+}
+
+// Four byte-sized codes into one dword with three byte permutes (selector 0x0c yields zero).
+__device__ __forceinline__ uint32_t merge_bytes(const uint32_t code[4])
+{
+    const uint32_t lo = __builtin_amdgcn_perm(code[1], code[0], 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(code[3], code[2], 0x04000c0cu);
+    return lo | hi;
 }
 
 template <int DTYPE>
@@ -242,15 +269,15 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
             const float kf = (float)(w0[t] >> 9);
             const uint32_t thr = __float_as_uint(__builtin_fmaf(kf, c.alpha23, c.alpha24));
             keep[t] = !(ab < thr);
-            if (QUANT) {
-                mag_in[t] = max(ab, c.alpha_bits);  // below alpha: the survivor is +-alpha
-            } else {
+            if (!QUANT) {
                 const uint32_t small = keep[t] ? (c.alpha_bits | (b[t] & 0x80000000u)) : 0u;
                 b[t] = ab > c.alpha_bits ? b[t] : small;
             }
         } else if (PRUNE && !QUANT) {
             b[t] = ab ? b[t] : 0u;  // alpha = 0: only -0 changes
         }
+        // below alpha the survivor is +-alpha; above the range the code saturates
+        if (QUANT) mag_in[t] = clamp_u32(ab, c.floor_bits, c.sat_bits);
     }
     if (!QUANT) {
         char *gout = reinterpret_cast<char *>(a.out) + tile * (uint64_t)(kWave * QB);
@@ -270,8 +297,7 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
         store_quad<DTYPE>(gout, (uint32_t)lane, v);
     } else if (OUT == LGN_OUT_CODE8) {
         uint32_t *gout = reinterpret_cast<uint32_t *>(a.out) + tile * (uint64_t)kWave;
-        __builtin_nontemporal_store(code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
-                                    gout + (uint32_t)lane);
+        __builtin_nontemporal_store(merge_bytes(code), gout + (uint32_t)lane);
     } else {
         const int N = q.n_bits;
         const uint32_t chunk = code[0] | (code[1] << N) | (code[2] << (2 * N)) | (code[3] << (3 * N));
@@ -358,81 +384,58 @@ __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile,
 constexpr int stream_min_waves(bool prune, bool quant, int round, int out)
 {
     const bool heavy = prune && quant && round == LGN_ROUND_STOCHASTIC;
-    return out == LGN_OUT_PACKED ? (heavy ? 5 : 6) : (heavy ? 6 : 8);
+    return out == LGN_OUT_PACKED ? 5 : (heavy ? 6 : 7);
 }
 
-template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
-__global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT)) void stream_kernel(StreamArgs a)
-{
-    const PhiloxKey key = {a.k0, a.k1};
-    float alpha = 0.0f;
-    if (PRUNE) alpha = a.p->alpha;
-    const uint32_t alpha_bits = __float_as_uint(alpha);
-    QuantConst q = {8, 1, 6, 0, 0, 1, 255u};
-    if (QUANT) load_quant_const(a.f, q);
-    const uint64_t n = a.n;
-    const uint64_t ntiles = (n + 255) / 256;
-    const uint64_t nwaves = (uint64_t)gridDim.x * (kBlock / kWave);
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t wave = (uint64_t)blockIdx.x * (kBlock / kWave) +
-                          (uint64_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
-    const uint64_t packed_total = (n * (uint64_t)q.n_bits + 7) / 8;
-    const PackLane pk = pack_lane(q.n_bits, lane);
-
-    // Fast-path eligibility that does not depend on the tile (all wave-uniform).
+// Everything a wave needs that does not depend on the tile.
+struct WalkState {
+    StreamArgs a;
+    PhiloxKey key;
+    float alpha;
+    QuantConst q;
+    PackLane pk;
     FastConst c;
-    c.alpha_bits = alpha_bits;
-    c.alpha23 = alpha * 0x1p-23f;
-    c.alpha24 = alpha * 0x1p-24f;
-    c.sub = (uint32_t)max(q.cbias, 0) << 23;
-    c.lo_bits = (uint32_t)min(max(q.cbias + 1, 0), 256) << 23;
-    c.maxmag = q.maxmag;
-    c.cut = 23u - (uint32_t)q.m;
-    c.rmul = 1u << (9u + (uint32_t)q.m);
-    c.sshift = (uint32_t)(q.e + q.m);
-    c.rnd = (1u << (c.cut - 1u)) - 1u;
-    const bool do_prune = PRUNE && alpha_bits != 0u;
-    // pruning raises every surviving magnitude to alpha: no flush test needed if alpha is in range
-    const bool check_lo = !(do_prune && alpha_bits >= c.lo_bits);
-    const bool fast_ok = (a.elem_offset & 3ull) == 0ull &&
-                         (!QUANT || (q.cbias >= 0 && q.cbias <= 254)) &&
-                         (!do_prune || (alpha_bits >= 0x12000000u && alpha_bits < 0x7f800000u));
-    const uint64_t qoff = a.elem_offset >> 2;
+    uint64_t ntiles, nwaves, wave, packed_total, qoff;
+    int lane;
+    bool fast_ok;
+};
+
+// The tile loop of one wave.  A wave walks PAIRS of consecutive tiles (2 KiB of fp32 input): both
+// loads of the next pair are issued before the current pair is processed, so every wave keeps
+// 2 KiB in flight while its Philox and quantizer arithmetic runs.  With eight waves per SIMD that
+// is 16 KiB per SIMD, twice what the measured latency x bandwidth product asks for; one tile per
+// step was not enough.  DO_PRUNE and CHECK_LO select the fast-tile variant once per kernel, so
+// the loop itself carries no variant dispatch.
+template <int DTYPE, bool PRUNE, bool DO_PRUNE, bool QUANT, int ROUND, int OUT, bool CHECK_LO>
+__device__ __forceinline__ void walk_pairs(const WalkState &s)
+{
+    const uint64_t n = s.a.n;
     // a tile is fast if it is full and its 64 quad indices share the upper counter word
     auto is_fast = [&](uint64_t t) {
-        return fast_ok && t < ntiles && (t + 1) * 256 <= n &&
-               (uint32_t)(qoff + t * kWave) <= 0xffffffffu - (uint32_t)kWave;
+        return s.fast_ok && t < s.ntiles && (t + 1) * 256 <= n &&
+               (uint32_t)(s.qoff + t * kWave) <= 0xffffffffu - (uint32_t)kWave;
     };
     auto run_fast = [&](uint64_t t, uint32_t *b) {
-        const uint64_t qbase = qoff + t * kWave;  // global quad index of lane 0
-        if (do_prune && !check_lo)
-            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, false>(a, t, qbase, lane, key, c, q, pk, b);
-        else if (do_prune)
-            fast_tile<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, pk, b);
-        else
-            fast_tile<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(a, t, qbase, lane, key, c, q, pk, b);
+        const uint64_t qbase = s.qoff + t * kWave;  // global quad index of lane 0
+        fast_tile<DTYPE, PRUNE, DO_PRUNE, QUANT, ROUND, OUT, CHECK_LO>(s.a, t, qbase, s.lane, s.key,
+                                                                       s.c, s.q, s.pk, b);
     };
-
-    // A wave walks PAIRS of consecutive tiles (2 KiB of fp32 input): both loads of the next pair are
-    // issued before the current pair is processed, so every wave keeps 2 KiB in flight while its
-    // Philox and quantizer arithmetic runs.  With eight waves per SIMD that is 16 KiB per SIMD,
-    // twice what the measured latency x bandwidth product asks for; one tile per step was not enough.
-    const uint64_t npairs = (ntiles + 1) / 2;
-    uint64_t pair = wave;
+    const uint64_t npairs = (s.ntiles + 1) / 2;
+    uint64_t pair = s.wave;
     uint32_t nb[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     bool have = is_fast(2 * pair) && is_fast(2 * pair + 1);
     if (have) {
-        load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * pair), (uint32_t)lane, nb);
-        load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * pair + 1), (uint32_t)lane, nb + 4);
+        load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * pair), (uint32_t)s.lane, nb);
+        load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * pair + 1), (uint32_t)s.lane, nb + 4);
     }
     while (pair < npairs) {
-        const uint64_t next = pair + nwaves;
+        const uint64_t next = pair + s.nwaves;
         const bool was = have;
         uint32_t b[8] = {nb[0], nb[1], nb[2], nb[3], nb[4], nb[5], nb[6], nb[7]};
         have = is_fast(2 * next) && is_fast(2 * next + 1);
         if (have) {
-            load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * next), (uint32_t)lane, nb);
-            load_quad<DTYPE>(tile_in<DTYPE>(a, 2 * next + 1), (uint32_t)lane, nb + 4);
+            load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * next), (uint32_t)s.lane, nb);
+            load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * next + 1), (uint32_t)s.lane, nb + 4);
         }
         if (was) {
             run_fast(2 * pair, b);
@@ -441,13 +444,67 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
             __builtin_amdgcn_sched_barrier(0);
             run_fast(2 * pair + 1, b + 4);
         } else {
-            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair, lane, key, alpha, q, pk, packed_total);
-            if (2 * pair + 1 < ntiles)
-                general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, 2 * pair + 1, lane, key, alpha, q,
-                                                              pk, packed_total);
+            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(s.a, 2 * pair, s.lane, s.key, s.alpha, s.q,
+                                                          s.pk, s.packed_total);
+            if (2 * pair + 1 < s.ntiles)
+                general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(s.a, 2 * pair + 1, s.lane, s.key,
+                                                              s.alpha, s.q, s.pk, s.packed_total);
         }
         pair = next;
     }
+}
+
+template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
+__global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT)) void stream_kernel(StreamArgs a)
+{
+    WalkState s;
+    s.a = a;
+    s.key = {a.k0, a.k1};
+    s.alpha = 0.0f;
+    if (PRUNE) s.alpha = a.p->alpha;
+    const uint32_t alpha_bits = __float_as_uint(s.alpha);
+    s.q = {8, 1, 6, 0, 0, 1, 255u};
+    if (QUANT) load_quant_const(a.f, s.q);
+    const QuantConst &q = s.q;
+    s.ntiles = (a.n + 255) / 256;
+    s.nwaves = (uint64_t)gridDim.x * (kBlock / kWave);
+    s.lane = threadIdx.x & (kWave - 1);
+    s.wave = (uint64_t)blockIdx.x * (kBlock / kWave) +
+             (uint64_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    s.packed_total = (a.n * (uint64_t)q.n_bits + 7) / 8;
+    s.pk = pack_lane(q.n_bits, s.lane);
+
+    // Fast-path eligibility that does not depend on the tile (all wave-uniform).
+    const bool do_prune = PRUNE && alpha_bits != 0u;
+    FastConst &c = s.c;
+    c.alpha_bits = alpha_bits;
+    c.alpha23 = s.alpha * 0x1p-23f;
+    c.alpha24 = s.alpha * 0x1p-24f;
+    c.sub = (uint32_t)max(q.cbias, 0) << 23;
+    c.lo_bits = (uint32_t)min(max(q.cbias + 1, 0), 256) << 23;
+    c.cut = 23u - (uint32_t)q.m;
+    c.sub_hi = 0u - (c.sub >> c.cut);
+    c.sat_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)(c.sub + (q.maxmag << c.cut)));
+    c.floor_bits = do_prune ? min(alpha_bits, c.sat_bits) : 0u;
+    c.rmul = 1u << (9u + (uint32_t)q.m);
+    // Hide from the optimiser that rmul is a power of two: y * rmul + w is then one
+    // v_mad_u64_u32 instead of a 64-bit shift, a zero extension and a 64-bit add.
+    asm volatile("" : "+s"(c.rmul));
+    c.sshift = (uint32_t)(q.e + q.m);
+    c.rnd = (1u << (c.cut - 1u)) - 1u;
+    // pruning raises every surviving magnitude to alpha: no flush test needed if alpha is in range
+    const bool check_lo = !(do_prune && alpha_bits >= c.lo_bits);
+    s.fast_ok = (a.elem_offset & 3ull) == 0ull &&
+                (!QUANT || (q.cbias >= 0 && q.cbias <= 254)) &&
+                (!do_prune || (alpha_bits >= 0x12000000u && alpha_bits < 0x7f800000u));
+    s.qoff = a.elem_offset >> 2;
+
+    if (PRUNE && do_prune && !check_lo)
+        walk_pairs<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, false>(s);
+    else if (PRUNE && do_prune)
+        walk_pairs<DTYPE, PRUNE, PRUNE, QUANT, ROUND, OUT, true>(s);
+    else
+        walk_pairs<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(s);
 }
 
 // ---- dequantize (not on the hot path): one element per thread ------------------------------

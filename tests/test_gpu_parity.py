@@ -376,3 +376,55 @@ def test_chain_on_device_matches_oracle_chain(lgn):
     # and the paper's claims hold on the device output: achieved = required sparsity
     achieved = np.mean((got & 0x1F) == 0)
     assert abs(achieved - cfg["sparsity"]) < 6 * math.sqrt(0.85 * 0.15 / g.size) + 3 / math.sqrt(ost.nnz)
+
+
+# ------------------------------------------------------------ one launch: statistics + solvers
+@pytest.mark.parametrize("dtype", [SI.F32, SI.BF16])
+def test_stats_solve_equals_three_calls(lgn, dtype):
+    """The single-launch entry point gives the bytes the three separate calls give, for sizes from
+    empty to many workgroups, called back to back on one workspace (the ticket re-arms itself)."""
+    alpha_dt = lgn.LGN_F32 if dtype == SI.F32 else lgn.LGN_BF16
+    for n in (0, 1, 5, 1023, 4099, 262_147, 3_000_001, 70_001, 17):
+        g = mixed_tensor(n, 300 + n % 89, dtype) if n > 64 else \
+            SI.lognormal_tensor(n, seed=5, mu=-11.0, sigma=2.0, zero_frac=0.2, dtype=dtype)
+        d = to_dev(g)
+        st = lgn.lgn_stats(d)
+        p = lgn.lgn_threshold(st, 0.9, alpha_dt)
+        f = lgn.lgn_fp_params(st, 5, scale_mode=lgn.LGN_SCALE_MAX)
+        st1, p1, f1 = lgn.lgn_stats_solve(d, 0.9, alpha_dt, 5, scale_mode=lgn.LGN_SCALE_MAX)
+        assert bytes(lgn.read_stats(st1)) == bytes(lgn.read_stats(st)), n
+        assert bytes(lgn.read_prune_params(p1)) == bytes(lgn.read_prune_params(p)), n
+        assert bytes(lgn.read_fp_params(f1)) == bytes(lgn.read_fp_params(f)), n
+        assert_stats_match(lgn.read_stats(st1), O.stats(g))
+    # either solve can be left out
+    st2, p2, f2 = lgn.lgn_stats_solve(d, n_bits=6)
+    assert p2 is None and bytes(lgn.read_fp_params(f2)) == bytes(lgn.read_fp_params(lgn.lgn_fp_params(st2, 6)))
+    st3, p3, f3 = lgn.lgn_stats_solve(d, 0.5)
+    assert f3 is None and bytes(lgn.read_prune_params(p3)) == bytes(lgn.read_prune_params(lgn.lgn_threshold(st3, 0.5)))
+    # a workspace of its own, prepared by the caller
+    ws = torch.full((lgn.lgn_workspace_bytes(0, lgn.LGN_F32),), 0xAB, dtype=torch.uint8, device="cuda")
+    lgn.lgn_workspace_init(ws)
+    for _ in range(3):
+        st4, _, _ = lgn.lgn_stats_solve(d, 0.5, ws=ws)
+        assert bytes(lgn.read_stats(st4)) == bytes(lgn.read_stats(st3))
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_stats_solve(d, 1.5)
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_stats_solve(d, 0.5, n_bits=11)
+
+
+def test_stats_solve_chain_c1(lgn):
+    """Two launches for the whole path: statistics + solvers, then the fused pass."""
+    cfg = SI.config_c1()
+    g = SI.make(cfg)
+    d = to_dev(g)
+    st, p, f = lgn.lgn_stats_solve(d, cfg["sparsity"], lgn.LGN_F32, cfg["n_bits"])
+    codes = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, cfg["rng_seed"], 0, out_kind=O.OUT_CODE8)
+    hs, hp, hf = lgn.read_stats(st), lgn.read_prune_params(p), lgn.read_fp_params(f)
+    same_in = O.make_stats(hs.n, hs.nnz, hs.mu, hs.sigma, hs.max_abs, hs.min_abs_nz, hs.n_nonfinite, hs.status)
+    op, of = O.threshold(same_in, cfg["sparsity"]), O.fp_params(same_in, cfg["n_bits"])
+    assert np.float32(hp.alpha) == np.float32(op.alpha)
+    assert (hf.e_bits, hf.m_bits, hf.scale_exp) == (of.e_bits, of.m_bits, of.scale_exp)
+    want = O.prune_quantize(g, hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp, O.ROUND_STOCHASTIC,
+                            cfg["rng_seed"], 0, O.OUT_CODE8)
+    assert np.array_equal(to_host(codes), want)
