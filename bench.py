@@ -44,8 +44,10 @@ MEASURED_TRAFFIC_BYTES = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # a step takes a third of a millisecond and the device needs some tens of steps to settle into
+    # its steady state (the first ~20 steps after an idle period run 15 % slower), hence the counts
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--n", type=int, default=None, help="override the element count")
     ap.add_argument("--out-kind", default="code8", choices=["code8", "packed", "value"])
@@ -53,6 +55,9 @@ def parse():
     ap.add_argument("--launches", default="merged", choices=["merged", "separate"],
                     help="merged: lgn_stats_solve + lgn_prune_quantize_fused (two launches per step); "
                          "separate: lgn_stats, lgn_threshold, lgn_fp_params, lgn_prune_quantize_fused")
+    ap.add_argument("--event-every", type=int, default=10,
+                    help="record the per-kernel HIP events on every N-th timed step (each record "
+                         "costs a few microseconds of stream time; 1 = every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain elementwise copy of the tensor before the timed region "
@@ -188,7 +193,7 @@ def main():
         if merged:
             lgn.lgn_stats_solve(d, sparsity, alpha_dt, n_bits, st=st, p=pp, f=fp, ws=ws)
             if ev:
-                ev[1].record()
+                ev[1] = ev[2]  # no separate solver launches: one record serves both marks
         else:
             lgn.lgn_stats(d, out=st, ws=ws)
             if ev:
@@ -211,7 +216,9 @@ def main():
         one_step()
     torch.cuda.synchronize()
 
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    every = max(1, args.event_every)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] if k % every == 0 else None
+              for k in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for k in range(args.steps):
@@ -220,9 +227,10 @@ def main():
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / args.steps
 
-    t_stats = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    t_solve = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    t_fused = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+    events = [e for e in events if e is not None]
+    t_stats = sum(e[0].elapsed_time(e[1]) for e in events) / len(events)
+    t_solve = sum(e[1].elapsed_time(e[2]) for e in events) / len(events)
+    t_fused = sum(e[2].elapsed_time(e[3]) for e in events) / len(events)
 
     alg_bytes_step = n * (2 * in_bytes + out_bytes_per_elem)
     value = alg_bytes_step / (ms_per_step * 1e-3) / 1e9

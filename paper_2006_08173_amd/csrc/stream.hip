@@ -204,16 +204,21 @@ template <int ROUND, bool CHECK_LO>
 __device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool keep, uint32_t w,
                                               const FastConst &c)
 {
-    uint32_t mag;
+    uint32_t code;
     if (ROUND == LGN_ROUND_STOCHASTIC) {
-        // (a - sub) * 2^(9+m) + w, with the re-biasing folded into the upper word of the addend
-        // (sub * 2^(9+m) is a multiple of 2^32)
-        mag = (uint32_t)(((uint64_t)a * c.rmul + (((uint64_t)c.sub_hi << 32) | w)) >> 32);
+        // upper word of  a * 2^(9+m) + w  plus, in the upper word of the addend, the sign bit at
+        // its place in the code minus the re-biasing (cbias << m): sub * 2^(9+m) is a multiple of
+        // 2^32, and the re-biased magnitude code stays below the sign bit, so nothing carries.
+        // Written as asm so that the sum stays one v_mad_u64_u32 with a ready-made addend.
+        const uint64_t addend = ((uint64_t)(((bits >> 31) << c.sshift) + c.sub_hi) << 32) | w;
+        uint64_t r;
+        asm("v_mad_u64_u32 %0, vcc, %1, %2, %3" : "=v"(r) : "v"(a), "s"(c.rmul), "v"(addend) : "vcc");
+        code = (uint32_t)(r >> 32);
     } else {
         const uint32_t y = a - c.sub;
-        mag = (y + c.rnd + ((y >> c.cut) & 1u)) >> c.cut;
+        const uint32_t mag = (y + c.rnd + ((y >> c.cut) & 1u)) >> c.cut;
+        code = ((bits >> 31) << c.sshift) | mag;
     }
-    const uint32_t code = ((bits >> 31) << c.sshift) | mag;
     const bool valid = CHECK_LO ? (a >= c.lo_bits && keep) : keep;
     return valid ? code : 0u;
 }
@@ -487,9 +492,10 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
     c.sat_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)(c.sub + (q.maxmag << c.cut)));
     c.floor_bits = do_prune ? min(alpha_bits, c.sat_bits) : 0u;
     c.rmul = 1u << (9u + (uint32_t)q.m);
-    // Hide from the optimiser that rmul is a power of two: y * rmul + w is then one
-    // v_mad_u64_u32 instead of a 64-bit shift, a zero extension and a 64-bit add.
-    asm volatile("" : "+s"(c.rmul));
+    c.rmul = (uint32_t)__builtin_amdgcn_readfirstlane((int)c.rmul);  // scalar operand of the asm
+    // kept in a vector register: (sign << sshift) + sub_hi is then one shift-and-add (an
+    // instruction reads at most one scalar register, and the shift count is the other one)
+    asm volatile("" : "+v"(c.sub_hi));
     c.sshift = (uint32_t)(q.e + q.m);
     c.rnd = (1u << (c.cut - 1u)) - 1u;
     // pruning raises every surviving magnitude to alpha: no flush test needed if alpha is in range
