@@ -77,25 +77,29 @@ int stream_blocks()
     return cached;
 }
 
-// Workgroups of the statistics pass (read-only streaming likes fewer, longer-lived waves).
-int stats_blocks_cap()
+// Workgroups of the statistics pass.  Read-only streaming likes few, long-lived waves: for fp32
+// two workgroups per CU (each wave keeps 8 KiB in flight) measured best, 6.3 TB/s against 5.9 at
+// four; bf16 has twice the arithmetic per byte and wants four.  Fewer workgroups also mean fewer
+// per-block records for the combine step.
+int stats_blocks_cap(int dtype)
 {
-    static int cached = 0;
-    if (cached) return cached;
-    int per_cu = 4;  // read-only streaming: four workgroups per CU measured best (2..8 within 3 %)
-    if (const char *e = getenv("LGN_STATS_BLOCKS_PER_CU")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= 8) per_cu = v;
-    }
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+    static int cus = 0;
+    static int env_per_cu = -1;
+    if (!cus) {
+        int dev = 0, v = 0;
+        cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
             cus = v;
+        env_per_cu = 0;
+        if (const char *e = getenv("LGN_STATS_BLOCKS_PER_CU")) {
+            const int w = atoi(e);
+            if (w >= 1 && w <= 8) env_per_cu = w;
+        }
     }
-    cached = cus * per_cu;
-    if (cached > 2048) cached = 2048;
-    return cached;
+    const int per_cu = env_per_cu ? env_per_cu : (dtype == LGN_F32 ? 2 : 4);
+    const int blocks = cus * per_cu;
+    return blocks > 2048 ? 2048 : blocks;
 }
 
 int check_stats_args(const void *g, uint64_t n, int dtype, const lgn_stats_t *out, const void *ws,
@@ -176,7 +180,7 @@ int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, 
               void *stream)
 {
     if (int rc = check_stats_args(g, n, dtype, out, ws, ws_bytes)) return rc;
-    const hipError_t e = lgn::launch_stats(g, n, dtype, out, ws, stats_blocks_cap(),
+    const hipError_t e = lgn::launch_stats(g, n, dtype, out, ws, stats_blocks_cap(dtype),
                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats", e);
 }
@@ -201,7 +205,7 @@ int lgn_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity
     const hipError_t e = lgn::launch_stats_solve(
         g, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
         scale_arg, sigma_units, st_out, want_p ? p_out : nullptr, n_bits ? f_out : nullptr, ws,
-        stats_blocks_cap(), static_cast<hipStream_t>(stream));
+        stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_solve", e);
 }
 

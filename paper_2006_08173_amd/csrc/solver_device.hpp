@@ -5,8 +5,9 @@
 //   threshold (Section 5.1-5.2 and Appendix "From sparsity to the threshold"):
 //       S(alpha) = Phi(L/sigma) - exp(sigma^2/2 - L) Phi((L - sigma^2)/sigma),  L = ln(alpha) - mu,
 //     which is the printed closed form with erf(a) - 1 written as -erfc(a).  S is increasing in
-//     v = ln(alpha) and dS/dv equals the second term, so Newton's step costs nothing extra.  The
-//     iteration is safeguarded by a bracket and falls back to bisection when a step leaves it.
+//     v = ln(alpha); dS/dv equals the second term B and d2S/dv2 = -B + phi(L/sigma)/sigma, so a
+//     third-order (Halley) step costs one more exponential.  The iteration is safeguarded by a
+//     bracket and falls back to bisection when a step leaves it.
 //   format (Section 4.2-4.3): expected relative error of FP(1,e,m) for every e in [1, N-1], one
 //     lane per candidate, then an arg-min across lanes (ties to the smaller e).
 //   scale (Section 4.4, Alg. 1, Appendix "Neural gradients lognormal distributions are truncated").
@@ -43,6 +44,18 @@ __device__ double normal_quantile(double q)
     return upper ? z : -z;
 }
 
+// Rational first guess of the standard normal quantile alone (|error| < 4.5e-4).
+__device__ __forceinline__ double normal_quantile_guess(double q)
+{
+    const bool upper = q > 0.5;
+    const double p = upper ? 1.0 - q : q;
+    if (!(p > 0.0)) return upper ? 40.0 : -40.0;
+    const double t = sqrt(-2.0 * log(p));
+    const double z = t - (2.515517 + 0.802853 * t + 0.010328 * t * t) /
+                             (1.0 + 1.432788 * t + 0.189269 * t * t + 0.001308 * t * t * t);
+    return upper ? z : -z;
+}
+
 // S(v) and its derivative B(v) = dS/dv.
 __device__ __forceinline__ void sparsity_terms(double mu, double sigma, double v, double &S, double &B)
 {
@@ -51,6 +64,14 @@ __device__ __forceinline__ void sparsity_terms(double mu, double sigma, double v
     const double tail = erfc((sigma * sigma - L) / (kSqrt2 * sigma));
     B = tail > 0.0 ? 0.5 * exp(0.5 * sigma * sigma - L + log(tail)) : 0.0;
     S = A - B;
+}
+
+// Second derivative of S given B: the derivative of the second term of S is -B + phi(L/sigma)/sigma
+// (the exponents of its two factors add up to -L^2 / (2 sigma^2)).
+__device__ __forceinline__ double sparsity_curvature(double mu, double sigma, double v, double B)
+{
+    const double a = (v - mu) / sigma;
+    return exp(-0.5 * a * a) * (0.398942280401432677939946059934 / sigma) - B;
 }
 
 __device__ __forceinline__ float round_to_bf16(float f)
@@ -92,8 +113,9 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
         r.status |= LGN_ST_SIGMA0;
     } else {
         // Bracket: stochastic pruning zeroes less than a hard threshold at the same alpha, so the
-        // lognormal quantile of s_eff is a lower bound of the root.
-        double lo = mu + sigma * normal_quantile(s_eff), hi = lo, S, B;
+        // lognormal quantile of s_eff is a lower bound of the root; the unpolished guess of the
+        // normal quantile, lowered by more than its error, is enough for that.
+        double lo = mu + sigma * (normal_quantile_guess(s_eff) - 1e-3), hi = lo, S, B;
         double step = sigma;
         bool ok = false;
         for (int i = 0; i < 64; ++i) {
@@ -108,11 +130,20 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
         bool converged = false;
         for (int it = 0; it < 200 && ok; ++it) {
             sparsity_terms(mu, sigma, v, S, B);
-            if (S < s_eff) lo = v; else hi = v;
-            double nv = B > 0.0 ? v + (s_eff - S) / B : 0.5 * (lo + hi);
-            if (!(nv > lo && nv < hi)) nv = 0.5 * (lo + hi);
-            const double tol = 1e-15 * fmax(1.0, fabs(nv));
-            const bool done = fabs(nv - v) <= tol || hi - lo <= tol;
+            const double f = S - s_eff;
+            if (f < 0.0) lo = v; else hi = v;
+            double nv = 0.5 * (lo + hi);
+            bool third_order = false;
+            if (B > 0.0) {
+                const double den = 2.0 * B * B - f * sparsity_curvature(mu, sigma, v, B);
+                const double h = v - 2.0 * f * B / den;
+                if (h > lo && h < hi) { nv = h; third_order = true; }
+            }
+            // a third-order step of size d leaves an error of order d^3: below 3e-6 that is under
+            // one unit in the last place of v, so no further evaluation is needed
+            const double d = fabs(nv - v), scale = fmax(1.0, fabs(nv));
+            const bool done = (third_order && d <= 3e-6 * scale) || d <= 1e-15 * scale ||
+                              hi - lo <= 1e-15 * scale;
             v = nv;
             if (done) { converged = true; break; }
         }

@@ -389,7 +389,7 @@ __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile,
 constexpr int stream_min_waves(bool prune, bool quant, int round, int out)
 {
     const bool heavy = prune && quant && round == LGN_ROUND_STOCHASTIC;
-    return out == LGN_OUT_PACKED ? 5 : (heavy ? 6 : 7);
+    return out == LGN_OUT_PACKED ? (heavy ? 4 : 5) : (heavy ? 6 : 7);
 }
 
 // Everything a wave needs that does not depend on the tile.
@@ -496,6 +496,7 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
     // kept in a vector register: (sign << sshift) + sub_hi is then one shift-and-add (an
     // instruction reads at most one scalar register, and the shift count is the other one)
     asm volatile("" : "+v"(c.sub_hi));
+    asm volatile("" : "+v"(c.floor_bits));  // vector operand of the clamp, kept live across tiles
     c.sshift = (uint32_t)(q.e + q.m);
     c.rnd = (1u << (c.cut - 1u)) - 1u;
     // pruning raises every surviving magnitude to alpha: no flush test needed if alpha is in range
