@@ -35,9 +35,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # WRITE_SIZE, scaled by the same counters on a copy kernel of known size); see profiles/.
 # None until measured for the workload at hand.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/hot_path_c4_hbm_traffic.txt: FETCH_SIZE 401457.6 x 2.000 KiB + WRITE_SIZE 200704.0 x 1.000 KiB
-    ("c4", "code8", "stochastic", "stream_kernel (fused prune+quantize)"): int((401457.6 * 2.0 + 200704.0) * 1024),
-    ("c4", "code8", "stochastic", "stats_stage1"): int((405253.9 * 2.0 + 128.0) * 1024),
+    # profiles/hot_path_c4_hbm_traffic.txt: FETCH_SIZE x 2.000 KiB + WRITE_SIZE x 1.000 KiB per launch
+    ("c4", "code8", "stochastic", "stream_kernel (fused prune+quantize)"): int((401466.6 * 2.0 + 200704.0) * 1024),
+    ("c4", "code8", "stochastic", "stats_solve_kernel"): int((402515.5 * 2.0 + 96.2) * 1024),
 }
 
 
