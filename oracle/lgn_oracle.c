@@ -24,11 +24,17 @@
  *     zero; saturation goes to the largest finite code; underflow flushes to zero and is decided
  *     on the exponent before rounding.
  *
+ *   - the prefix code of the appendix "Encoding" is laid out as a bit stream in which stream bit
+ *     k is bit (k & 7) of byte k >> 3, codewords are written first symbol first, the value that
+ *     follows "11" is the element's own bit pattern (32, 16 or N bits) least significant bit
+ *     first, and every chunk of 4096 elements starts on a 32-bit boundary listed in a table.
+ *
  * Pins (tests/test_oracle_*.py): Philox known-answer vectors; Table 2 of the paper for the
  * format choice; quadrature of the sparsity definition (the expectation over the uniform
  * variable of the lognormal CDF) and Monte-Carlo pruning for the threshold; exhaustive
  * enumeration of all FP-n codes for the quantizer; exact results on powers of two for the
- * statistics.  Parity unpinned (pure conventions): the 0.997 default quantile of the scale rule,
+ * statistics; the code table of the appendix, an independent string decoder and the paper's
+ * bits-per-value claim for the prefix code.  Parity unpinned (pure conventions): the 0.997 default quantile of the scale rule,
  * the tie rule of nearest rounding, the 23-bit midpoint grid of u.
  */
 #include <float.h>
@@ -548,3 +554,115 @@ uint32_t orc_quantize_one(float x, int e, int m, int s, int rounding, uint32_t w
     return quantize_one(x, e, m, s, rounding, w);
 }
 float orc_prune_one(float x, float alpha, uint32_t w) { return prune_one(x, alpha, w); }
+
+/* ------------------------------------------------------------------------------------------
+ * Prefix code of the pruned tensor (appendix "Encoding", table "Simple proposed encoding for the
+ * values after stochastic pruning"):
+ *     0 -> "0",   +alpha -> "100",   -alpha -> "101",   any other value -> "11" then the value.
+ * An element is given as its raw pattern of `width` bits (fp32: 32, bf16: 16, FP-n code: N);
+ * the top bit of the pattern is the sign, `special` is the magnitude pattern of alpha.  Only the
+ * all-zero pattern takes the one-bit codeword, so the code is lossless for any input.
+ * Container (this build's choice, the paper gives the codewords only): chunks of 4096 elements,
+ * each starting on a 32-bit boundary; table[c] = index of the first 32-bit word of chunk c,
+ * table[nchunks] = total number of words, table[nchunks + 1] = 0 (status, no overflow here).
+ * ------------------------------------------------------------------------------------------ */
+#define ORC_PREFIX_CHUNK 4096u
+
+static uint32_t raw_pattern(const void *in, uint64_t i, int width)
+{
+    if (width == 32) return ((const uint32_t *)in)[i];
+    if (width == 16) return ((const uint16_t *)in)[i];
+    return ((const uint8_t *)in)[i];
+}
+
+static unsigned symbol_bits(uint32_t v, int width, uint32_t special)
+{
+    const uint32_t mag = v & ((1u << (width - 1)) - 1u);
+    if (v == 0u) return 1u;
+    if (special != 0u && mag == special) return 3u;
+    return 2u + (unsigned)width;
+}
+
+static void put_bit(uint8_t *out, uint64_t k, unsigned bit)
+{
+    if (bit) out[k >> 3] |= (uint8_t)(1u << (k & 7u));
+}
+
+uint64_t orc_prefix_chunks(uint64_t n) { return (n + ORC_PREFIX_CHUNK - 1u) / ORC_PREFIX_CHUNK; }
+
+/* Worst case: every element takes the long codeword. */
+uint64_t orc_prefix_bound_bytes(uint64_t n, int width)
+{
+    const uint64_t words_per_chunk = ((uint64_t)ORC_PREFIX_CHUNK * (2u + (unsigned)width) + 31u) / 32u;
+    return orc_prefix_chunks(n) * words_per_chunk * 4u;
+}
+
+/* Fills table (nchunks + 2 entries) and, if out is not NULL, the zero-initialised stream.
+ * Returns the number of bytes of the stream. */
+uint64_t orc_prefix_encode(const void *in, uint64_t n, int width, uint32_t special, uint8_t *out,
+                           uint64_t *table)
+{
+    const uint64_t nchunks = orc_prefix_chunks(n);
+    int64_t c;
+#pragma omp parallel for num_threads(g_threads)
+    for (c = 0; c < (int64_t)nchunks; ++c) {
+        uint64_t bits = 0, i = (uint64_t)c * ORC_PREFIX_CHUNK;
+        const uint64_t end = i + ORC_PREFIX_CHUNK < n ? i + ORC_PREFIX_CHUNK : n;
+        for (; i < end; ++i) bits += symbol_bits(raw_pattern(in, i, width), width, special);
+        table[c + 1] = (bits + 31u) / 32u; /* words of this chunk, turned into offsets below */
+    }
+    table[0] = 0;
+    for (c = 0; c < (int64_t)nchunks; ++c) table[c + 1] += table[c];
+    table[nchunks + 1] = 0;
+    if (!out) return table[nchunks] * 4u;
+#pragma omp parallel for num_threads(g_threads)
+    for (c = 0; c < (int64_t)nchunks; ++c) {
+        uint64_t k = table[c] * 32u, i = (uint64_t)c * ORC_PREFIX_CHUNK;
+        const uint64_t end = i + ORC_PREFIX_CHUNK < n ? i + ORC_PREFIX_CHUNK : n;
+        for (; i < end; ++i) {
+            const uint32_t v = raw_pattern(in, i, width);
+            const unsigned len = symbol_bits(v, width, special);
+            if (len == 1u) {
+                put_bit(out, k++, 0u);
+            } else if (len == 3u) {
+                put_bit(out, k++, 1u);
+                put_bit(out, k++, 0u);
+                put_bit(out, k++, (v >> (width - 1)) & 1u);
+            } else {
+                int b;
+                put_bit(out, k++, 1u);
+                put_bit(out, k++, 1u);
+                for (b = 0; b < width; ++b) put_bit(out, k++, (v >> b) & 1u);
+            }
+        }
+    }
+    return table[nchunks] * 4u;
+}
+
+static unsigned get_bit(const uint8_t *in, uint64_t k) { return (in[k >> 3] >> (k & 7u)) & 1u; }
+
+void orc_prefix_decode(const uint8_t *stream, const uint64_t *table, uint64_t n, int width,
+                       uint32_t special, void *out)
+{
+    const uint64_t nchunks = orc_prefix_chunks(n);
+    int64_t c;
+#pragma omp parallel for num_threads(g_threads)
+    for (c = 0; c < (int64_t)nchunks; ++c) {
+        uint64_t k = table[c] * 32u, i = (uint64_t)c * ORC_PREFIX_CHUNK;
+        const uint64_t end = i + ORC_PREFIX_CHUNK < n ? i + ORC_PREFIX_CHUNK : n;
+        for (; i < end; ++i) {
+            uint32_t v = 0;
+            if (get_bit(stream, k++)) {
+                if (get_bit(stream, k++)) {
+                    int b;
+                    for (b = 0; b < width; ++b) v |= (uint32_t)get_bit(stream, k++) << b;
+                } else {
+                    v = special | ((uint32_t)get_bit(stream, k++) << (width - 1));
+                }
+            }
+            if (width == 32) ((uint32_t *)out)[i] = v;
+            else if (width == 16) ((uint16_t *)out)[i] = (uint16_t)v;
+            else ((uint8_t *)out)[i] = (uint8_t)v;
+        }
+    }
+}

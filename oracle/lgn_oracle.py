@@ -90,6 +90,13 @@ def lib():
         L.orc_quantize_one.restype = u32
         L.orc_prune_one.argtypes = [f32, f32, u32]
         L.orc_prune_one.restype = f32
+        L.orc_prefix_chunks.argtypes = [u64]
+        L.orc_prefix_chunks.restype = u64
+        L.orc_prefix_bound_bytes.argtypes = [u64, i32]
+        L.orc_prefix_bound_bytes.restype = u64
+        L.orc_prefix_encode.argtypes = [vp, u64, i32, u32, vp, vp]
+        L.orc_prefix_encode.restype = u64
+        L.orc_prefix_decode.argtypes = [vp, vp, u64, i32, u32, vp]
         _lib = L
     return _lib
 
@@ -238,3 +245,61 @@ def quantize_one(x, e, m, s, rounding=ROUND_NEAREST_EVEN, w=0) -> int:
 
 def prune_one(x, alpha, w) -> float:
     return float(lib().orc_prune_one(np.float32(x), np.float32(alpha), int(w) & 0xFFFFFFFF))
+
+
+# ---- prefix code of the pruned tensor (appendix "Encoding") ----------------------------------
+PREFIX_CHUNK = 4096
+
+
+def _raw_view(a: np.ndarray, width: int) -> np.ndarray:
+    a = np.ascontiguousarray(a).reshape(-1)
+    if width == 32:
+        return a.view(np.uint32)
+    if width == 16:
+        return a.view(np.uint16)
+    return a.view(np.uint8)
+
+
+def prefix_width(a: np.ndarray, n_bits: int = None) -> int:
+    """Bits of an element's pattern: 32 (fp32), 16 (bf16 bit patterns) or N (FP-n codes)."""
+    if a.dtype == np.float32:
+        return 32
+    if a.dtype == np.uint16:
+        return 16
+    assert a.dtype == np.uint8 and n_bits is not None
+    return int(n_bits)
+
+
+def prefix_special_of_alpha(alpha: float, width: int) -> int:
+    """Magnitude pattern of alpha as an fp32 (width 32) or bf16 (width 16) value."""
+    b = int(np.float32(alpha).view(np.uint32)) & 0x7FFFFFFF
+    return b if width == 32 else b >> 16
+
+
+def prefix_special_of_code(alpha: float, e: int, m: int, s: int) -> int:
+    """Magnitude code that alpha quantizes to with nearest rounding."""
+    return quantize_one(abs(float(alpha)), e, m, s, ROUND_NEAREST_EVEN) & ((1 << (e + m)) - 1)
+
+
+def prefix_bound_bytes(n: int, width: int) -> int:
+    return int(lib().orc_prefix_bound_bytes(int(n), int(width)))
+
+
+def prefix_encode(a: np.ndarray, special: int, n_bits: int = None):
+    """Returns (stream bytes, table) for the prefix code; see orc_prefix_encode."""
+    width = prefix_width(a, n_bits)
+    raw = _raw_view(a, width)
+    nchunks = int(lib().orc_prefix_chunks(raw.size))
+    table = np.zeros(nchunks + 2, dtype=np.uint64)
+    nbytes = int(lib().orc_prefix_encode(_ptr(raw), raw.size, width, int(special), None, _ptr(table)))
+    stream = np.zeros(nbytes, dtype=np.uint8)
+    lib().orc_prefix_encode(_ptr(raw), raw.size, width, int(special), _ptr(stream), _ptr(table))
+    return stream, table
+
+
+def prefix_decode(stream: np.ndarray, table: np.ndarray, n: int, width: int, special: int) -> np.ndarray:
+    stream = np.ascontiguousarray(stream, dtype=np.uint8)
+    table = np.ascontiguousarray(table, dtype=np.uint64)
+    out = np.empty(n, dtype={32: np.uint32, 16: np.uint16}.get(width, np.uint8))
+    lib().orc_prefix_decode(_ptr(stream), _ptr(table), int(n), int(width), int(special), _ptr(out))
+    return out
