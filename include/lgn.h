@@ -230,6 +230,42 @@ int lgn_prune_quantize_fused(const void *g, uint64_t n, int dtype, const lgn_pru
 int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f, int dtype,
                    void *out, void *stream);
 
+/*
+ * Prefix code of a pruned tensor (appendix "Encoding", table of codewords): 0 -> "0",
+ * +alpha -> "100", -alpha -> "101", any other value -> "11" followed by the value itself.
+ *   in        device, n elements: LGN_OUT_VALUE = values of `dtype` as lgn_prune writes them (the
+ *             value after "11" is the 32- or 16-bit pattern), LGN_OUT_CODE8 = one FP-n code per
+ *             byte as lgn_fp_quantize / lgn_prune_quantize_fused write them (the value is the
+ *             N-bit code, N read from *f); 16-byte aligned
+ *   p         device; alpha marks the special class.  VALUE: an element is +-alpha if its
+ *             magnitude pattern equals alpha's (rounded to `dtype`).  CODE8: if its magnitude code
+ *             equals the code alpha takes with nearest rounding in the format *f.  May be null
+ *             (then, and for alpha = 0, there is no special class).
+ *   f         device, needed for CODE8 (ignored for VALUE)
+ *   out       device, the bit stream: stream bit k is bit (k & 7) of byte k >> 3; codewords first
+ *             symbol first, the value after "11" least significant bit first.  Only the all-zero
+ *             pattern takes the codeword "0", so decoding returns the input exactly.
+ *   table     device, lgn_prefix_table_bytes(n) bytes = ceil(n / 4096) + 2 entries of 64 bits:
+ *             elements are coded in chunks of LGN_PREFIX_CHUNK, every chunk starts on a 32-bit
+ *             boundary (padding bits are zero); table[c] = index of the first 32-bit word of chunk
+ *             c, table[nchunks] = number of words of the whole stream, table[nchunks + 1] = 0, or
+ *             1 if out_capacity was too small (the chunks that did not fit are then not written).
+ *   out_capacity  bytes available at out; lgn_prefix_bound_bytes(n, width) always suffices
+ *             (width = 32, 16 or N)
+ * Three launches (words per chunk, in-place scan of the table, emit); `in` is read twice.
+ */
+#define LGN_PREFIX_CHUNK 4096
+size_t lgn_prefix_table_bytes(uint64_t n);
+size_t lgn_prefix_bound_bytes(uint64_t n, int width);
+int lgn_prefix_encode(const void *in, uint64_t n, int in_kind, int dtype, const lgn_prune_params_t *p,
+                      const lgn_fp_params_t *f, void *out, size_t out_capacity, uint64_t *table,
+                      void *stream);
+
+/* Inverse of lgn_prefix_encode: writes n elements (values of `dtype`, or one code per byte) to
+ * out.  in_kind, dtype, *p and *f must be those of the encoding call.  One thread per chunk. */
+int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_kind, int dtype,
+                      const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out, void *stream);
+
 const char *lgn_last_error(void);
 int lgn_version(void);
 

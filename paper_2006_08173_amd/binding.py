@@ -24,6 +24,7 @@ LGN_SCALE_QUANTILE, LGN_SCALE_MAX, LGN_SCALE_CENTER = 0, 1, 2
 LGN_SIGMA_PAPER_LITERAL, LGN_SIGMA_BASE2 = 0, 1
 LGN_ST_EMPTY, LGN_ST_SIGMA0, LGN_ST_NOTHING_TO_PRUNE, LGN_ST_NOT_CONVERGED = 1, 2, 4, 8
 LGN_ST_ALPHA_BELOW_FP_RANGE, LGN_ST_HAS_NONFINITE = 16, 32
+LGN_PREFIX_CHUNK = 4096
 
 
 class LgnStats(C.Structure):
@@ -58,7 +59,9 @@ _lib = None
 
 EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshold",
            "lgn_fp_params", "lgn_prune", "lgn_fp_quantize", "lgn_prune_quantize_fused",
-           "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_last_error", "lgn_version")
+           "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_prefix_encode",
+           "lgn_prefix_decode", "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes",
+           "lgn_last_error", "lgn_version")
 
 
 def library_path() -> str:
@@ -89,7 +92,13 @@ def load():
     L.lgn_stats_solve.argtypes = [vp, u64, i32, dbl, i32, i32, i32, i32, dbl, i32, vp, vp, vp, vp, sz, vp]
     L.lgn_last_error.restype = C.c_char_p
     L.lgn_version.restype = i32
-    for name in EXPORTS[2:11]:
+    L.lgn_prefix_encode.argtypes = [vp, u64, i32, i32, vp, vp, vp, sz, vp, vp]
+    L.lgn_prefix_decode.argtypes = [vp, vp, u64, i32, i32, vp, vp, vp, vp]
+    L.lgn_prefix_table_bytes.argtypes = [u64]
+    L.lgn_prefix_table_bytes.restype = sz
+    L.lgn_prefix_bound_bytes.argtypes = [u64, i32]
+    L.lgn_prefix_bound_bytes.restype = sz
+    for name in EXPORTS[2:13]:
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -269,6 +278,46 @@ def lgn_dequantize(codes: torch.Tensor, n: int, in_kind: int, f: torch.Tensor,
                           device=codes.device)
     _check(load().lgn_dequantize(codes.data_ptr(), int(n), int(in_kind), f.data_ptr(), int(dtype),
                                  out.data_ptr(), _stream()))
+    return out
+
+
+def lgn_prefix_table_bytes(n: int) -> int:
+    return int(load().lgn_prefix_table_bytes(int(n)))
+
+
+def lgn_prefix_bound_bytes(n: int, width: int) -> int:
+    return int(load().lgn_prefix_bound_bytes(int(n), int(width)))
+
+
+def lgn_prefix_encode(x: torch.Tensor, in_kind: int, p: torch.Tensor = None, f: torch.Tensor = None,
+                      out: torch.Tensor = None, table: torch.Tensor = None, width: int = None, dtype=None):
+    """Returns (stream buffer, table).  The buffer is sized for the worst case unless `out` is given;
+    the stream itself is the first table[nchunks] * 4 bytes of it."""
+    x = _flat(x)
+    n = x.numel()
+    dt = LGN_F32 if in_kind == LGN_OUT_CODE8 else _dtype_code(x, dtype)
+    if out is None:
+        if width is None:
+            width = 8 if in_kind == LGN_OUT_CODE8 else (32 if dt == LGN_F32 else 16)
+        out = torch.empty(max(lgn_prefix_bound_bytes(n, width), 4), dtype=torch.uint8, device=x.device)
+    if table is None:
+        table = torch.empty(lgn_prefix_table_bytes(n) // 8, dtype=torch.int64, device=x.device)
+    _check(load().lgn_prefix_encode(x.data_ptr(), n, int(in_kind), dt,
+                                    p.data_ptr() if p is not None else None,
+                                    f.data_ptr() if f is not None else None,
+                                    out.data_ptr(), out.numel(), table.data_ptr(), _stream()))
+    return out, table
+
+
+def lgn_prefix_decode(stream_buf: torch.Tensor, table: torch.Tensor, n: int, in_kind: int,
+                      p: torch.Tensor = None, f: torch.Tensor = None, dtype: int = LGN_F32,
+                      out: torch.Tensor = None) -> torch.Tensor:
+    if out is None:
+        tdt = torch.uint8 if in_kind == LGN_OUT_CODE8 else (torch.float32 if dtype == LGN_F32 else torch.bfloat16)
+        out = torch.empty(int(n), dtype=tdt, device=stream_buf.device)
+    _check(load().lgn_prefix_decode(stream_buf.data_ptr(), table.data_ptr(), int(n), int(in_kind),
+                                    int(dtype), p.data_ptr() if p is not None else None,
+                                    f.data_ptr() if f is not None else None, out.data_ptr(), _stream()))
     return out
 
 

@@ -33,6 +33,12 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
                          const StreamArgs &args, int max_blocks, hipStream_t stream);
 hipError_t launch_dequant(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f,
                           int dtype, void *out, hipStream_t stream);
+hipError_t launch_prefix_encode(int width_class, const void *in, uint64_t n, const lgn_prune_params_t *p,
+                                const lgn_fp_params_t *f, void *out, uint64_t capacity_words,
+                                uint64_t *table, hipStream_t stream);
+hipError_t launch_prefix_decode(int width_class, const void *in, const uint64_t *table, uint64_t n,
+                                const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out,
+                                hipStream_t stream);
 }  // namespace lgn
 
 namespace {
@@ -280,6 +286,57 @@ int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_para
     const hipError_t e = lgn::launch_dequant(codes, n, in_kind, f, dtype, out,
                                              static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_dequantize", e);
+}
+
+size_t lgn_prefix_table_bytes(uint64_t n)
+{
+    return (size_t)(((n + LGN_PREFIX_CHUNK - 1) / LGN_PREFIX_CHUNK + 2) * 8);
+}
+
+size_t lgn_prefix_bound_bytes(uint64_t n, int width)
+{
+    if (width < 2 || width > 32) return 0;
+    const uint64_t words_per_chunk = ((uint64_t)LGN_PREFIX_CHUNK * (2 + (uint64_t)width) + 31) / 32;
+    return (size_t)((n + LGN_PREFIX_CHUNK - 1) / LGN_PREFIX_CHUNK * words_per_chunk * 4);
+}
+
+static int prefix_width_class(int in_kind, int dtype, const lgn_fp_params_t *f)
+{
+    if (in_kind == LGN_OUT_CODE8) {
+        if (!f) return fail(LGN_ERR_INVALID_ARG, "codes need the fp params they were made with") - 100;
+        return 0;
+    }
+    if (in_kind != LGN_OUT_VALUE) return fail(LGN_ERR_UNSUPPORTED, "prefix code takes VALUE or CODE8 input") - 100;
+    if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype) - 100;
+    return dtype == LGN_F32 ? 2 : 1;
+}
+
+int lgn_prefix_encode(const void *in, uint64_t n, int in_kind, int dtype, const lgn_prune_params_t *p,
+                      const lgn_fp_params_t *f, void *out, size_t out_capacity, uint64_t *table,
+                      void *stream)
+{
+    const int wc = prefix_width_class(in_kind, dtype, f);
+    if (wc < 0) return wc + 100;
+    if (!table || !aligned(table, 8)) return fail(LGN_ERR_INVALID_ARG, "table null or not 8-byte aligned");
+    if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
+    if (n && (!in || !aligned(in, 16))) return fail(LGN_ERR_INVALID_ARG, "input null or not 16-byte aligned");
+    if (out_capacity && (!out || !aligned(out, 4))) return fail(LGN_ERR_INVALID_ARG, "stream buffer null or not 4-byte aligned");
+    const hipError_t e = lgn::launch_prefix_encode(wc, in, n, p, f, out, out_capacity / 4, table,
+                                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_prefix_encode", e);
+}
+
+int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_kind, int dtype,
+                      const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out, void *stream)
+{
+    const int wc = prefix_width_class(in_kind, dtype, f);
+    if (wc < 0) return wc + 100;
+    if (!table || !aligned(table, 8)) return fail(LGN_ERR_INVALID_ARG, "table null or not 8-byte aligned");
+    if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
+    if (n && (!in || !out || !aligned(in, 4))) return fail(LGN_ERR_INVALID_ARG, "null or misaligned buffer");
+    const hipError_t e = lgn::launch_prefix_decode(wc, in, table, n, p, f, out,
+                                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_prefix_decode", e);
 }
 
 }  // extern "C"
