@@ -245,16 +245,18 @@ int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_para
  *   out       device, the bit stream: stream bit k is bit (k & 7) of byte k >> 3; codewords first
  *             symbol first, the value after "11" least significant bit first.  Only the all-zero
  *             pattern takes the codeword "0", so decoding returns the input exactly.
- *   table     device, lgn_prefix_table_bytes(n) bytes = ceil(n / 4096) + 2 entries of 64 bits:
+ *   table     device, lgn_prefix_table_bytes(n) bytes: ceil(n / 4096) + 2 entries of 64 bits
+ *             (followed by LGN_PREFIX_MAX_BLOCKS entries of scratch for the encoder):
  *             elements are coded in chunks of LGN_PREFIX_CHUNK, every chunk starts on a 32-bit
  *             boundary (padding bits are zero); table[c] = index of the first 32-bit word of chunk
  *             c, table[nchunks] = number of words of the whole stream, table[nchunks + 1] = 0, or
  *             1 if out_capacity was too small (the chunks that did not fit are then not written).
  *   out_capacity  bytes available at out; lgn_prefix_bound_bytes(n, width) always suffices
  *             (width = 32, 16 or N)
- * Three launches (words per chunk, in-place scan of the table, emit); `in` is read twice.
+ * Three launches (words per chunk, scan of per-workgroup sums, emit); `in` is read twice.
  */
 #define LGN_PREFIX_CHUNK 4096
+#define LGN_PREFIX_MAX_BLOCKS 2048 /* entries of scratch the encoder keeps behind the table */
 size_t lgn_prefix_table_bytes(uint64_t n);
 size_t lgn_prefix_bound_bytes(uint64_t n, int width);
 int lgn_prefix_encode(const void *in, uint64_t n, int in_kind, int dtype, const lgn_prune_params_t *p,

@@ -290,7 +290,7 @@ int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_para
 
 size_t lgn_prefix_table_bytes(uint64_t n)
 {
-    return (size_t)(((n + LGN_PREFIX_CHUNK - 1) / LGN_PREFIX_CHUNK + 2) * 8);
+    return (size_t)(((n + LGN_PREFIX_CHUNK - 1) / LGN_PREFIX_CHUNK + 2 + LGN_PREFIX_MAX_BLOCKS) * 8);
 }
 
 size_t lgn_prefix_bound_bytes(uint64_t n, int width)
@@ -333,7 +333,8 @@ int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_
     if (wc < 0) return wc + 100;
     if (!table || !aligned(table, 8)) return fail(LGN_ERR_INVALID_ARG, "table null or not 8-byte aligned");
     if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
-    if (n && (!in || !out || !aligned(in, 4))) return fail(LGN_ERR_INVALID_ARG, "null or misaligned buffer");
+    if (n && (!in || !out || !aligned(in, 4) || !aligned(out, 16)))
+        return fail(LGN_ERR_INVALID_ARG, "null or misaligned buffer (stream 4, output 16 bytes)");
     const hipError_t e = lgn::launch_prefix_decode(wc, in, table, n, p, f, out,
                                                    static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_prefix_decode", e);

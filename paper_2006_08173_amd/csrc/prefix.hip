@@ -10,10 +10,13 @@
 // Container: chunks of 4096 elements, each starting on a 32-bit boundary listed in a table
 // (table[c] = first word of chunk c, table[nchunks] = total words, table[nchunks+1] = status).
 // Variable-length output needs the chunk sizes before anything can be placed, hence three
-// launches: count (words per chunk), scan (one workgroup, in place), emit.  One workgroup owns a
-// chunk; thread t owns its elements 16t .. 16t+15, a block-wide exclusive scan of the threads'
-// bit counts gives each thread its offset, the chunk is assembled in LDS (first and last word of
-// a thread with LDS atomic OR, interior words with plain stores) and copied out coalesced.
+// launches.  Count: words per chunk, one wave per chunk, and their sum per workgroup.  Scan: one
+// small workgroup turns the per-workgroup sums into first-word offsets.  Emit: a workgroup walks
+// its contiguous run of chunks with a running offset; thread t owns elements 16t .. 16t+15 of the
+// chunk, a block-wide exclusive scan of the threads' bit counts gives each thread its position,
+// and the chunk is assembled in a zero-initialised LDS image with atomic ORs -- only non-zero
+// elements write anything, the codeword "0" is the zero bit that is already there -- then copied
+// out coalesced while the image is cleared for the next chunk.
 #include "fpcode_device.hpp"
 
 namespace lgn {
@@ -120,155 +123,191 @@ __device__ __forceinline__ int load_thread_elems(const void *in, uint64_t first,
     return count;
 }
 
-// Exclusive scan of one value per thread over the workgroup; also returns the total.
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t &total)
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T x)
 {
-    __shared__ uint32_t wave_sum[kBlock / kWave];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    uint32_t incl = x;
+    const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off);
-        if (lane >= off) incl += up;
+        const T up = __shfl_up(x, off);
+        if (lane >= off) x += up;
     }
-    __syncthreads();  // previous use of wave_sum is over
-    if (lane == kWave - 1) wave_sum[wave] = incl;
-    __syncthreads();
-    uint32_t base = 0, sum = 0;
-#pragma unroll
-    for (int w = 0; w < kBlock / kWave; ++w) {
-        if (w < wave) base += wave_sum[w];
-        sum += wave_sum[w];
-    }
-    total = sum;
-    return base + incl - x;
+    return x;
 }
 
-// ---- launch 1: words per chunk -> table[c + 1] ----------------------------------------------
-template <int WC>
-__global__ __launch_bounds__(kBlock) void prefix_count_kernel(PrefixArgs a)
+// Chunks are dealt to workgroups in contiguous runs, so that a workgroup knows the offsets of its
+// own chunks from a running sum and only one number per workgroup has to be scanned globally.
+struct ChunkRun {
+    uint64_t first, last;  // chunks [first, last) of this workgroup
+};
+
+__device__ __forceinline__ ChunkRun chunk_run(uint64_t nchunks)
 {
+    const uint64_t per = (nchunks + gridDim.x - 1) / gridDim.x;
+    ChunkRun r;
+    r.first = min((uint64_t)blockIdx.x * per, nchunks);
+    r.last = min(r.first + per, nchunks);
+    return r;
+}
+
+// ---- launch 1: words per chunk -> table[c + 1], words per workgroup -> scratch[block] --------
+// Wave-synchronous: a wave sums the codeword lengths of whole chunks (order does not matter for
+// a sum, so the loads are lane-contiguous 16-byte vectors); no barrier until the final total.
+template <int WC>
+__global__ __launch_bounds__(kBlock) void prefix_count_kernel(PrefixArgs a, uint64_t *scratch)
+{
+    using T = typename Elem<WC>::T;
+    constexpr int EPV = 16 / (int)sizeof(T);             // elements per 16-byte vector
+    constexpr int kVecsPerLane = kChunk / (EPV * kWave);  // 4 (codes), 8 (bf16), 16 (fp32)
+    __shared__ uint64_t wave_words[kBlock / kWave];
     int width;
     uint32_t special;
     prefix_consts<WC>(a, width, special);
     const uint64_t nchunks = (a.n + kChunk - 1) / kChunk;
-    for (uint64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        uint32_t v[kPerThread];
-        const int count = load_thread_elems<WC>(a.in, c * kChunk + (uint64_t)threadIdx.x * kPerThread, a.n, v);
+    const ChunkRun run = chunk_run(nchunks);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const T *src = reinterpret_cast<const T *>(a.in);
+    uint64_t words = 0;  // wave-uniform
+    for (uint64_t c = run.first + wave; c < run.last; c += kBlock / kWave) {
+        const uint64_t e0 = c * kChunk;
         uint32_t bits = 0;
+        if (e0 + kChunk <= a.n) {
+            const uint4 *vp = reinterpret_cast<const uint4 *>(src + e0) + lane;
 #pragma unroll
-        for (int j = 0; j < kPerThread; ++j)
-            if (j < count) bits += (uint32_t)symbol_len(v[j], width, special);
-        uint32_t total;
-        block_exclusive_scan(bits, total);
-        if (threadIdx.x == 0) a.table[c + 1] = (total + 31u) / 32u;
+            for (int k = 0; k < kVecsPerLane; ++k) {
+                const uint4 x = vp[k * kWave];
+                const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (WC == 2) {
+                        bits += (uint32_t)symbol_len(w[j], width, special);
+                    } else if (WC == 1) {
+                        bits += (uint32_t)symbol_len(w[j] & 0xffffu, width, special);
+                        bits += (uint32_t)symbol_len(w[j] >> 16, width, special);
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            bits += (uint32_t)symbol_len((w[j] >> (8 * t)) & 0xffu, width, special);
+                    }
+                }
+            }
+        } else {  // the ragged last chunk, element by element
+            for (uint64_t i = e0 + lane; i < a.n; i += kWave)
+                bits += (uint32_t)symbol_len(src[i], width, special);
+        }
+        const uint32_t total = __shfl(wave_inclusive_scan(bits), kWave - 1);
+        const uint32_t w32 = (total + 31u) / 32u;
+        if (lane == 0) a.table[c + 1] = w32;
+        words += w32;
+    }
+    if (lane == 0) wave_words[wave] = words;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t sum = 0;
+        for (int w = 0; w < kBlock / kWave; ++w) sum += wave_words[w];
+        scratch[blockIdx.x] = sum;
     }
 }
 
-// ---- launch 2: in-place exclusive scan of the table (one workgroup) --------------------------
+// ---- launch 2: exclusive scan of the per-workgroup totals (one workgroup) --------------------
 constexpr int kScanThreads = 1024;
+constexpr int kMaxPrefixBlocks = LGN_PREFIX_MAX_BLOCKS;  // two totals per scanning thread
 
-__global__ __launch_bounds__(kScanThreads) void prefix_scan_kernel(uint64_t *table, uint64_t nchunks)
+__global__ __launch_bounds__(kScanThreads) void prefix_scan_kernel(uint64_t *table, uint64_t nchunks,
+                                                                   uint64_t *scratch, int nblocks)
 {
-    __shared__ uint64_t part[kScanThreads];
-    const uint64_t per = (nchunks + kScanThreads - 1) / kScanThreads;
-    const uint64_t lo = min((uint64_t)threadIdx.x * per, nchunks), hi = min(lo + per, nchunks);
-    uint64_t sum = 0;
-    for (uint64_t c = lo; c < hi; ++c) sum += table[c + 1];
-    part[threadIdx.x] = sum;
+    __shared__ uint64_t wave_sum[kScanThreads / kWave];
+    const int i0 = 2 * threadIdx.x, i1 = i0 + 1;
+    const uint64_t x0 = i0 < nblocks ? scratch[i0] : 0, x1 = i1 < nblocks ? scratch[i1] : 0;
+    const uint64_t incl = wave_inclusive_scan(x0 + x1);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == kWave - 1) wave_sum[wave] = incl;
     __syncthreads();
+    uint64_t base = 0;
+    for (int w = 0; w < wave; ++w) base += wave_sum[w];
+    const uint64_t excl = base + incl - (x0 + x1);
+    if (i0 < nblocks) scratch[i0] = excl;        // first word of the workgroup's first chunk
+    if (i1 < nblocks) scratch[i1] = excl + x0;
     if (threadIdx.x == 0) {
-        uint64_t run = 0;
-        for (int t = 0; t < kScanThreads; ++t) {
-            const uint64_t x = part[t];
-            part[t] = run;
-            run += x;
-        }
         table[0] = 0;
         table[nchunks + 1] = 0;  // status: cleared here, set by the emit pass on overflow
-    }
-    __syncthreads();
-    uint64_t run = part[threadIdx.x];
-    for (uint64_t c = lo; c < hi; ++c) {
-        run += table[c + 1];
-        table[c + 1] = run;  // entry c + 1 = first word of chunk c + 1 = end of chunk c
     }
 }
 
 // ---- launch 3: assemble each chunk in LDS and copy it out ------------------------------------
-struct BitWriter {
-    uint32_t *lds;
-    uint64_t acc;     // bits not yet written; the low `fill` bits are in place
-    uint32_t fill;    // < 32 between puts
-    uint32_t word;    // index of the word the low bits of acc belong to
-    bool first;       // the next flushed word may be shared with the previous thread
-
-    __device__ __forceinline__ void put(uint32_t bits, int len)  // len <= 32
-    {
-        acc |= (uint64_t)bits << fill;
-        fill += (uint32_t)len;
-        if (fill >= 32u) {
-            const uint32_t w = (uint32_t)acc;
-            if (first) atomicOr(lds + word, w);
-            else lds[word] = w;
-            first = false;
-            acc >>= 32;
-            fill -= 32u;
-            ++word;
-        }
-    }
-    __device__ __forceinline__ void finish()
-    {
-        if (fill) atomicOr(lds + word, (uint32_t)acc);  // shared with the next thread
-    }
-};
+// ORs `len` <= 32 bits into the zero-initialised LDS image of the chunk at bit position `pos`.
+__device__ __forceinline__ void lds_put(uint32_t *buf, uint32_t pos, uint32_t bits)
+{
+    const uint64_t x = (uint64_t)bits << (pos & 31u);
+    const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+    atomicOr(buf + (pos >> 5), lo);
+    if (hi) atomicOr(buf + (pos >> 5) + 1, hi);
+}
 
 template <int WC>
-__global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a)
+__global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const uint64_t *scratch)
 {
-    __shared__ uint32_t buf[kChunkWordsMax];
+    __shared__ uint32_t buf[kChunkWordsMax + 1];  // + 1: the word after the last bit may be ORed with 0
+    __shared__ uint32_t wave_sum[kBlock / kWave];
     int width;
     uint32_t special;
     prefix_consts<WC>(a, width, special);
+    const uint32_t payload_mask = width == 32 ? 0xffffffffu : (1u << width) - 1u;
     const uint64_t nchunks = (a.n + kChunk - 1) / kChunk;
+    const ChunkRun run = chunk_run(nchunks);
     uint32_t *out = reinterpret_cast<uint32_t *>(a.out);
-    for (uint64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        const uint64_t w0 = a.table[c];
-        // what the count pass found for this chunk; never more than the LDS buffer holds
-        const uint32_t nwords = (uint32_t)min(a.table[c + 1] - w0, (uint64_t)kChunkWordsMax);
-        for (uint32_t i = threadIdx.x; i < nwords; i += kBlock) buf[i] = 0u;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (uint32_t i = threadIdx.x; i < (uint32_t)kChunkWordsMax + 1u; i += kBlock) buf[i] = 0u;
+    uint64_t w0 = scratch[blockIdx.x];  // first word of the current chunk
+    bool overflow = false;
+    __syncthreads();
+    for (uint64_t c = run.first; c < run.last; ++c) {
         uint32_t v[kPerThread];
         const int count = load_thread_elems<WC>(a.in, c * kChunk + (uint64_t)threadIdx.x * kPerThread, a.n, v);
         uint32_t bits = 0;
 #pragma unroll
         for (int j = 0; j < kPerThread; ++j)
             if (j < count) bits += (uint32_t)symbol_len(v[j], width, special);
-        uint32_t total;
-        const uint32_t off = block_exclusive_scan(bits, total);  // its barriers also cover the zeroing
-        BitWriter bw = {buf, 0ull, off & 31u, off >> 5, true};
+        const uint32_t incl = wave_inclusive_scan(bits);
+        if (lane == kWave - 1) wave_sum[wave] = incl;
+        __syncthreads();
+        uint32_t pos = incl - bits, total = 0;
+#pragma unroll
+        for (int w = 0; w < kBlock / kWave; ++w) {
+            if (w < wave) pos += wave_sum[w];
+            total += wave_sum[w];
+        }
+        // zero symbols are the zero bits the image already holds: only the others are written
 #pragma unroll
         for (int j = 0; j < kPerThread; ++j) {
             if (j < count) {
                 const int len = symbol_len(v[j], width, special);
-                if (len == 1) {
-                    bw.put(0u, 1);
-                } else if (len == 3) {
-                    bw.put(1u | (((v[j] >> (width - 1)) & 1u) << 2), 3);
-                } else {
-                    bw.put(3u, 2);
-                    bw.put(width == 32 ? v[j] : (v[j] & ((1u << width) - 1u)), width);
+                if (len == 3) {
+                    lds_put(buf, pos, 1u | (((v[j] >> (width - 1)) & 1u) << 2));
+                } else if (len != 1) {
+                    if (WC == 2) {
+                        lds_put(buf, pos, 3u);
+                        lds_put(buf, pos + 2u, v[j]);
+                    } else {
+                        lds_put(buf, pos, 3u | ((v[j] & payload_mask) << 2));  // at most 18 bits
+                    }
                 }
+                pos += (uint32_t)len;
             }
         }
-        bw.finish();
         __syncthreads();
-        if (w0 + nwords <= a.capacity_words) {
-            for (uint32_t i = threadIdx.x; i < nwords; i += kBlock) out[w0 + i] = buf[i];
-        } else if (threadIdx.x == 0) {
-            a.table[nchunks + 1] = 1;  // stream buffer too small: this chunk is not written
+        const uint32_t nwords = (total + 31u) / 32u;  // = what the count pass stored in table[c + 1]
+        const bool fits = w0 + nwords <= a.capacity_words;
+        for (uint32_t i = threadIdx.x; i < nwords; i += kBlock) {
+            if (fits) out[w0 + i] = buf[i];
+            buf[i] = 0u;
         }
-        __syncthreads();  // buf is reused by the next chunk
+        overflow |= !fits;
+        w0 += nwords;
+        if (threadIdx.x == 0) a.table[c + 1] = w0;  // end of chunk c = first word of chunk c + 1
+        __syncthreads();  // the image and wave_sum are reused by the next chunk
     }
+    if (overflow && threadIdx.x == 0) a.table[nchunks + 1] = 1;  // stream buffer too small
 }
 
 // ---- decode: one thread per chunk (sequential by nature; not on the hot path) ----------------
@@ -276,6 +315,7 @@ template <int WC>
 __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
 {
     using T = typename Elem<WC>::T;
+    constexpr int EPV = 16 / (int)sizeof(T);
     int width;
     uint32_t special;
     prefix_consts<WC>(a, width, special);
@@ -289,34 +329,44 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
     uint64_t w = a.table[c];
     uint64_t acc = 0;   // bits fetched and not yet consumed, low bits first
     uint32_t have = 0;
-    auto need = [&](uint32_t k) {  // make at least k <= 32 bits available (zeros past the chunk)
+    auto take = [&](uint32_t k) {  // k <= 32 bits; zeros past the end of the chunk
         if (have < k) {
             const uint32_t x = w < wend ? in[w] : 0u;
             ++w;
             acc |= (uint64_t)x << have;
             have += 32u;
         }
-    };
-    auto take = [&](uint32_t k) {
-        need(k);
         const uint32_t r = k == 32u ? (uint32_t)acc : ((uint32_t)acc & ((1u << k) - 1u));
         acc >>= k;
         have -= k;
         return r;
     };
-    for (uint64_t i = first; i < last; ++i) {
+    auto symbol = [&]() {
         uint32_t v = 0u;
         if (take(1)) {
             if (take(1)) v = take((uint32_t)width);
             else v = special | (take(1) << (width - 1));
         }
-        out[i] = (T)v;
+        return v;
+    };
+    uint64_t i = first;
+    for (; i + EPV <= last; i += EPV) {  // sixteen bytes of output at a time
+        uint32_t q[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) {
+            const uint32_t v = symbol();
+            if (WC == 2) q[j] = v;
+            else if (WC == 1) q[j / 2] |= v << (16 * (j % 2));
+            else q[j / 4] |= v << (8 * (j % 4));
+        }
+        *reinterpret_cast<uint4 *>(out + i) = make_uint4(q[0], q[1], q[2], q[3]);
     }
+    for (; i < last; ++i) out[i] = (T)symbol();
 }
 
 static int prefix_grid(uint64_t nchunks)
 {
-    const uint64_t cap = 256 * 8;
+    const uint64_t cap = kMaxPrefixBlocks;
     return (int)(nchunks < 1 ? 1 : (nchunks < cap ? nchunks : cap));
 }
 
@@ -324,15 +374,17 @@ template <int WC>
 static hipError_t encode_launches(const PrefixArgs &a, hipStream_t stream)
 {
     const uint64_t nchunks = (a.n + kChunk - 1) / kChunk;
+    uint64_t *scratch = a.table + nchunks + 2;  // per-workgroup totals, then first words
+    const int blocks = prefix_grid(nchunks);
     if (nchunks) {
-        prefix_count_kernel<WC><<<prefix_grid(nchunks), kBlock, 0, stream>>>(a);
+        prefix_count_kernel<WC><<<blocks, kBlock, 0, stream>>>(a, scratch);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    prefix_scan_kernel<<<1, kScanThreads, 0, stream>>>(a.table, nchunks);
+    prefix_scan_kernel<<<1, kScanThreads, 0, stream>>>(a.table, nchunks, scratch, nchunks ? blocks : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !nchunks) return e;
-    prefix_emit_kernel<WC><<<prefix_grid(nchunks), kBlock, 0, stream>>>(a);
+    prefix_emit_kernel<WC><<<blocks, kBlock, 0, stream>>>(a, scratch);
     return hipGetLastError();
 }
 

@@ -189,3 +189,34 @@ def test_more_than_2_to_32_elements(lgn):
         assert np.array_equal(pruned[lo:hi].cpu().numpy().view(np.uint16), wantp), (lo, hi)
     # different positions of the same repeated data draw different random words
     assert not torch.equal(codes[:block_n], codes[block_n:2 * block_n])
+
+
+def test_prefix_code_at_full_size(lgn):
+    """Configuration 4: prune to 0.85, code the fp32 values; then the fused FP6 codes.  The whole
+    stream and table are compared with the oracle; the device decoder returns the input."""
+    cfg = SI.config_c4()
+    g, d = upload(cfg)
+    st, p, f = lgn.lgn_stats_solve(d, cfg["sparsity"], lgn.LGN_F32, 6)
+    hp, hf = lgn.read_prune_params(p), lgn.read_fp_params(f)
+    y = lgn.lgn_prune(d, p, cfg["rng_seed"], 0)
+    buf, table = lgn.lgn_prefix_encode(y, lgn.LGN_OUT_VALUE, p)
+    t = table.cpu().numpy().view(np.uint64)[: (g.size + 4095) // 4096 + 2]
+    hy = y.cpu().numpy()
+    want, wt = O.prefix_encode(hy, O.prefix_special_of_alpha(hp.alpha, 32))
+    assert np.array_equal(t, wt)
+    assert np.array_equal(buf[: int(t[-2]) * 4].cpu().numpy(), want)
+    back = lgn.lgn_prefix_decode(buf, table, g.size, lgn.LGN_OUT_VALUE, p)
+    assert torch.equal(back.view(torch.int32), y.view(torch.int32))
+    # 40 % of the elements were zero before pruning, so fewer are +-alpha than in the paper's example
+    assert want.size * 8 / g.size < 4.5
+    del buf, back, y, hy, want
+    codes = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, cfg["rng_seed"], 0, out_kind=O.OUT_CODE8)
+    buf, table = lgn.lgn_prefix_encode(codes, lgn.LGN_OUT_CODE8, p, f, width=6)
+    t = table.cpu().numpy().view(np.uint64)[: (g.size + 4095) // 4096 + 2]
+    hc = codes.cpu().numpy()
+    special = O.prefix_special_of_code(hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp)
+    want, wt = O.prefix_encode(hc, special, 6)
+    assert np.array_equal(t, wt)
+    assert np.array_equal(buf[: int(t[-2]) * 4].cpu().numpy(), want)
+    assert torch.equal(lgn.lgn_prefix_decode(buf, table, g.size, lgn.LGN_OUT_CODE8, p, f), codes)
+    assert want.size * 8 / g.size < 2.2                   # against 6 bits per value packed

@@ -26,8 +26,14 @@ def to_dev(a: np.ndarray):
     return torch.from_numpy(a).cuda()
 
 
-def host_stream(buf, table):
-    t = table.cpu().numpy().view(np.uint64)
+def host_table(table, n):
+    """The table proper: one entry per chunk, the total and the status (scratch follows it)."""
+    nchunks = (n + 4095) // 4096
+    return table.cpu().numpy().view(np.uint64)[: nchunks + 2]
+
+
+def host_stream(buf, table, n):
+    t = host_table(table, n)
     return buf.cpu().numpy()[: int(t[-2]) * 4], t
 
 
@@ -58,7 +64,7 @@ def test_value_streams_match_oracle(lgn, dtype):
         a = pruned_like(n, 40 + n % 7, dtype, alpha)
         d = to_dev(a)
         buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_VALUE, p)
-        got, t = host_stream(buf, table)
+        got, t = host_stream(buf, table, n)
         want, wt = O.prefix_encode(a, special)
         assert np.array_equal(t, wt), n
         assert np.array_equal(got, want), n
@@ -85,7 +91,7 @@ def test_code_streams_match_oracle(lgn, n_bits, e):
         codes[r > 0.5] = 0
         d = to_dev(codes)
         buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_CODE8, p, f)
-        got, t = host_stream(buf, table)
+        got, t = host_stream(buf, table, n)
         want, wt = O.prefix_encode(codes, special, n_bits)
         assert np.array_equal(t, wt), n
         assert np.array_equal(got, want), n
@@ -97,14 +103,14 @@ def test_no_special_class_and_small_capacity(lgn):
     a = pruned_like(5 * 4096, 3, SI.F32)
     d = to_dev(a)
     buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_VALUE, None)        # no alpha: two classes only
-    got, t = host_stream(buf, table)
+    got, t = host_stream(buf, table, a.size)
     want, wt = O.prefix_encode(a, 0)
     assert np.array_equal(t, wt) and np.array_equal(got, want)
     # a buffer that holds the first three chunks only: they are written, the status entry is set
     cap = int(wt[3]) * 4
     small = torch.full((cap + 64,), 0xEE, dtype=torch.uint8, device="cuda")
     _, table2 = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_VALUE, None, out=small[:cap])
-    t2 = table2.cpu().numpy().view(np.uint64)
+    t2 = host_table(table2, a.size)
     assert t2[-1] == 1 and np.array_equal(t2[:-1], wt[:-1])
     hs = small.cpu().numpy()
     assert np.array_equal(hs[:cap], want[:cap]) and np.all(hs[cap:] == 0xEE)
@@ -125,7 +131,7 @@ def test_chain_prune_quantize_encode_config1(lgn):
     hp, hf = lgn.read_prune_params(p), lgn.read_fp_params(f)
     special = O.prefix_special_of_code(hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp)
     hc = codes.cpu().numpy()
-    got, t = host_stream(buf, table)
+    got, t = host_stream(buf, table, g.size)
     want, wt = O.prefix_encode(hc, special, cfg["n_bits"])
     assert np.array_equal(t, wt) and np.array_equal(got, want)
     assert np.array_equal(O.prefix_decode(got, t, g.size, cfg["n_bits"], special), hc)
@@ -143,7 +149,7 @@ def test_bits_per_value_claim_on_device(lgn):
         st, p, _ = lgn.lgn_stats_solve(d, sparsity)
         y = lgn.lgn_prune(d, p, 5, 0)
         buf, table = lgn.lgn_prefix_encode(y, lgn.LGN_OUT_VALUE, p)
-        words = int(table.cpu().numpy().view(np.uint64)[-2])
+        words = int(host_table(table, n)[-2])
         assert abs(words * 32 / n - claim) < 0.35
         back = lgn.lgn_prefix_decode(buf, table, n, lgn.LGN_OUT_VALUE, p)
         assert torch.equal(back.view(torch.int32), y.view(torch.int32))
