@@ -281,18 +281,17 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
 #pragma unroll
         for (int j = 0; j < kPerThread; ++j) {
             if (j < count) {
-                const int len = symbol_len(v[j], width, special);
-                if (len == 3) {
-                    lds_put(buf, pos, 1u | (((v[j] >> (width - 1)) & 1u) << 2));
-                } else if (len != 1) {
-                    if (WC == 2) {
-                        lds_put(buf, pos, 3u);
-                        lds_put(buf, pos + 2u, v[j]);
-                    } else {
-                        lds_put(buf, pos, 3u | ((v[j] & payload_mask) << 2));  // at most 18 bits
-                    }
+                const uint32_t x = v[j];
+                const bool is_special = special != 0u && (x & ((1u << (width - 1)) - 1u)) == special;
+                const uint32_t head = is_special ? (1u | (((x >> (width - 1)) & 1u) << 2)) : 3u;
+                if (WC == 2) {
+                    if (x != 0u) lds_put(buf, pos, head);
+                    if (x != 0u && !is_special) lds_put(buf, pos + 2u, x);
+                } else {
+                    // at most 2 + 16 bits
+                    if (x != 0u) lds_put(buf, pos, is_special ? head : (3u | ((x & payload_mask) << 2)));
                 }
-                pos += (uint32_t)len;
+                pos += x == 0u ? 1u : (is_special ? 3u : 2u + (uint32_t)width);
             }
         }
         __syncthreads();
