@@ -127,7 +127,19 @@ static void store_elem(void *out, uint64_t i, int dtype, float v)
  * mu = mean of ln|g|, sigma = population standard deviation of ln|g|, both over the entries
  * that are finite and non-zero.  Two passes: mean first, then squared deviations.
  * ========================================================================================== */
-void orc_stats(const void *g, uint64_t n, int dtype, orc_stats_t *out)
+/* Is element i part of the fit?  Without a mask every element is.  With one (appendix "Algorithm
+ * for bi-Modal lognormal pruning", step 3: only the values whose corresponding entries in the
+ * other gradient tensor are non-zero), element i counts iff the mask's entry i is non-zero; the
+ * mask is either a tensor of the same type as g (kind 1) or one byte per element (kind 2). */
+static int in_fit(const void *mask, int mask_kind, uint64_t i, int dtype)
+{
+    if (mask_kind == 1) return load_elem(mask, i, dtype) != 0.0f; /* NaN != 0: counts */
+    if (mask_kind == 2) return ((const uint8_t *)mask)[i] != 0;
+    return 1;
+}
+
+static void stats_impl(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                       orc_stats_t *out)
 {
     uint64_t nnz = 0, nonfinite = 0;
     long double sum = 0.0L;
@@ -136,6 +148,7 @@ void orc_stats(const void *g, uint64_t n, int dtype, orc_stats_t *out)
 #pragma omp parallel for num_threads(g_threads) reduction(+ : nnz, nonfinite, sum) \
     reduction(max : mx) reduction(min : mn)
     for (i = 0; i < N; ++i) {
+        if (!in_fit(mask, mask_kind, (uint64_t)i, dtype)) continue;
         float x = load_elem(g, (uint64_t)i, dtype);
         if (!isfinite(x)) { ++nonfinite; continue; }
         if (x == 0.0f) continue;
@@ -162,6 +175,7 @@ void orc_stats(const void *g, uint64_t n, int dtype, orc_stats_t *out)
     long double ss = 0.0L;
 #pragma omp parallel for num_threads(g_threads) reduction(+ : ss)
     for (i = 0; i < N; ++i) {
+        if (!in_fit(mask, mask_kind, (uint64_t)i, dtype)) continue;
         float x = load_elem(g, (uint64_t)i, dtype);
         if (!isfinite(x) || x == 0.0f) continue;
         long double d = (long double)log((double)fabsf(x)) - (long double)mu;
@@ -172,6 +186,21 @@ void orc_stats(const void *g, uint64_t n, int dtype, orc_stats_t *out)
     out->max_abs = mx;
     out->min_abs_nz = mn;
     if (mx == mn) out->status |= ORC_ST_SIGMA0;
+}
+
+void orc_stats(const void *g, uint64_t n, int dtype, orc_stats_t *out)
+{
+    stats_impl(g, NULL, 0, n, dtype, out);
+}
+
+/* Statistics of the right mode of a bi-modal gradient (appendix "Algorithm for bi-Modal lognormal
+ * pruning", steps 1 and 3).  n stays the size of the whole tensor and nnz counts the entries of
+ * the fit, so the zero credit of orc_threshold, S' = (S n - (n - nnz)) / nnz, is step 2's
+ * S' = (S - l) / (1 - l) with l the fraction left out of the fit. */
+void orc_stats_masked(const void *g, const void *mask, uint64_t n, int dtype, int mask_kind,
+                      orc_stats_t *out)
+{
+    stats_impl(g, mask, mask_kind, n, dtype, out);
 }
 
 /* ==========================================================================================

@@ -63,6 +63,7 @@ def lib():
         L.orc_get_threads.restype = i32
         L.orc_max_threads.restype = i32
         L.orc_stats.argtypes = [vp, u64, i32, C.POINTER(Stats)]
+        L.orc_stats_masked.argtypes = [vp, vp, u64, i32, i32, C.POINTER(Stats)]
         L.orc_sparsity_of_alpha.argtypes = [dbl, dbl, dbl]
         L.orc_sparsity_of_alpha.restype = dbl
         L.orc_sparsity_of_log_alpha.argtypes = [dbl, dbl, dbl]
@@ -125,6 +126,22 @@ def stats(g: np.ndarray) -> Stats:
     g = np.ascontiguousarray(g).reshape(-1)
     st = Stats()
     lib().orc_stats(_ptr(g), g.size, _dtype_of(g), C.byref(st))
+    return st
+
+
+MASK_NONE, MASK_SAME_DTYPE, MASK_U8 = 0, 1, 2
+
+
+def stats_masked(g: np.ndarray, mask: np.ndarray) -> Stats:
+    """Statistics over the entries of g whose mask entry is non-zero (the right mode of a bi-modal
+    gradient); the mask has g's dtype or is one byte per element."""
+    g = np.ascontiguousarray(g).reshape(-1)
+    mask = np.ascontiguousarray(mask).reshape(-1)
+    assert mask.size == g.size
+    kind = MASK_U8 if mask.dtype == np.uint8 else MASK_SAME_DTYPE
+    assert kind == MASK_U8 or mask.dtype == g.dtype
+    st = Stats()
+    lib().orc_stats_masked(_ptr(g), _ptr(mask), g.size, _dtype_of(g), kind, C.byref(st))
     return st
 
 

@@ -115,6 +115,20 @@ def lognormal_tensor(n, *, seed, mu, sigma, zero_frac=0.0, dtype=F32, start=0,
     return out
 
 
+def bimodal_pair(n, *, seed, left_frac, mu_right, sigma_right, mu_left, sigma_left, dtype=F32):
+    """A pre-batch-norm style gradient and the post-batch-norm gradient that splits it in two modes.
+
+    Returns (x, m).  m is a ReLU-masked lognormal tensor: a fraction `left_frac` of exact zeros.  x is
+    dense: lognormal(mu_left, sigma_left) where m is zero (the left mode, orders of magnitude
+    smaller) and lognormal(mu_right, sigma_right) elsewhere, symmetric signs.
+    """
+    m = lognormal_tensor(n, seed=seed, mu=mu_right, sigma=sigma_right, zero_frac=left_frac, dtype=dtype)
+    right = lognormal_tensor(n, seed=seed + 101, mu=mu_right, sigma=sigma_right, dtype=dtype)
+    left = lognormal_tensor(n, seed=seed + 202, mu=mu_left, sigma=sigma_left, dtype=dtype)
+    x = np.where(m == 0, left, right)
+    return x, m
+
+
 # ---------------------------------------------------------------------------------------------
 # The benchmark configurations (sizes, distributions and work) of BASELINE.json `configs`.
 # `seed` is the data seed; `rng_seed` keys the random words the pruning / rounding steps draw.
