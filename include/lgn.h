@@ -157,22 +157,43 @@ int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, 
               void *stream);
 
 /*
+ * Statistics of the right mode of a bi-modal gradient (appendix "Algorithm for bi-Modal lognormal
+ * pruning", steps 1 and 3): as lgn_stats, but only the entries of g whose entry in `mask` is
+ * non-zero enter the fit (the mask is the gradient on the other side of the batch-norm, whose
+ * zeros mark the left mode).
+ *   mask       device, n entries, 16-byte aligned, read once
+ *   mask_kind  LGN_MASK_SAME_DTYPE: a tensor of g's dtype, an entry counts unless it is +0 or -0;
+ *              LGN_MASK_U8: one byte per element, counts unless 0; LGN_MASK_NONE: mask ignored
+ * out->n is the size of the whole tensor and out->nnz the number of entries in the fit, so the zero
+ * credit of lgn_threshold, S' = (S n - (n - nnz)) / nnz, is step 2's S' = (S - l) / (1 - l); the
+ * threshold is then applied to the whole tensor with lgn_prune (step 4).  max_abs, min_abs_nz and
+ * n_nonfinite refer to the entries in the fit.
+ */
+#define LGN_MASK_NONE 0
+#define LGN_MASK_SAME_DTYPE 1
+#define LGN_MASK_U8 2
+int lgn_stats_masked(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                     lgn_stats_t *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * lgn_stats, lgn_threshold and lgn_fp_params in ONE launch (same passages as those three): the
  * workgroup that finishes last combines the per-block records and runs both solvers, so the two
  * parameter structs are ready when the statistics pass ends.  Results are identical to the three
  * separate calls.
  *   target_sparsity  in [0, 1), or negative to skip the threshold (p_out may then be null)
  *   n_bits           in [2, 8], or 0 to skip the format (f_out may then be null)
+ *   mask, mask_kind  as in lgn_stats_masked (null and LGN_MASK_NONE for a plain tensor)
  *   other arguments  as in lgn_stats / lgn_threshold / lgn_fp_params
  *   ws               as for lgn_stats, and prepared once with lgn_workspace_init: the kernel
  *                    counts finished workgroups in the ticket area, which must be zero on entry
  *                    and is zero again on exit.  Calls that overlap in time need separate
  *                    workspaces.
  */
-int lgn_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity, int alpha_dtype,
-                    int n_bits, int e_bits, int scale_mode, double scale_arg, int sigma_units,
-                    lgn_stats_t *st_out, lgn_prune_params_t *p_out, lgn_fp_params_t *f_out,
-                    void *ws, size_t ws_bytes, void *stream);
+int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                    double target_sparsity, int alpha_dtype, int n_bits, int e_bits, int scale_mode,
+                    double scale_arg, int sigma_units, lgn_stats_t *st_out,
+                    lgn_prune_params_t *p_out, lgn_fp_params_t *f_out, void *ws, size_t ws_bytes,
+                    void *stream);
 
 /*
  * Threshold alpha such that stochastic pruning leaves a fraction `target_sparsity` of the WHOLE

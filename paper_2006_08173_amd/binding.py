@@ -25,6 +25,7 @@ LGN_SIGMA_PAPER_LITERAL, LGN_SIGMA_BASE2 = 0, 1
 LGN_ST_EMPTY, LGN_ST_SIGMA0, LGN_ST_NOTHING_TO_PRUNE, LGN_ST_NOT_CONVERGED = 1, 2, 4, 8
 LGN_ST_ALPHA_BELOW_FP_RANGE, LGN_ST_HAS_NONFINITE = 16, 32
 LGN_PREFIX_CHUNK = 4096
+LGN_MASK_NONE, LGN_MASK_SAME_DTYPE, LGN_MASK_U8 = 0, 1, 2
 
 
 class LgnStats(C.Structure):
@@ -59,7 +60,7 @@ _lib = None
 
 EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshold",
            "lgn_fp_params", "lgn_prune", "lgn_fp_quantize", "lgn_prune_quantize_fused",
-           "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_prefix_encode",
+           "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_stats_masked", "lgn_prefix_encode",
            "lgn_prefix_decode", "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes",
            "lgn_last_error", "lgn_version")
 
@@ -89,7 +90,8 @@ def load():
     L.lgn_prune_quantize_fused.argtypes = [vp, u64, i32, vp, vp, i32, u64, u64, vp, i32, vp]
     L.lgn_dequantize.argtypes = [vp, u64, i32, vp, i32, vp, vp]
     L.lgn_workspace_init.argtypes = [vp, sz, vp]
-    L.lgn_stats_solve.argtypes = [vp, u64, i32, dbl, i32, i32, i32, i32, dbl, i32, vp, vp, vp, vp, sz, vp]
+    L.lgn_stats_solve.argtypes = [vp, vp, i32, u64, i32, dbl, i32, i32, i32, i32, dbl, i32, vp, vp, vp, vp, sz, vp]
+    L.lgn_stats_masked.argtypes = [vp, vp, i32, u64, i32, vp, vp, sz, vp]
     L.lgn_last_error.restype = C.c_char_p
     L.lgn_version.restype = i32
     L.lgn_prefix_encode.argtypes = [vp, u64, i32, i32, vp, vp, vp, sz, vp, vp]
@@ -98,7 +100,7 @@ def load():
     L.lgn_prefix_table_bytes.restype = sz
     L.lgn_prefix_bound_bytes.argtypes = [u64, i32]
     L.lgn_prefix_bound_bytes.restype = sz
-    for name in EXPORTS[2:13]:
+    for name in EXPORTS[2:14]:
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -179,11 +181,38 @@ def lgn_workspace_init(ws: torch.Tensor) -> None:
         _check(load().lgn_workspace_init(ws.data_ptr(), ws.numel(), _stream()))
 
 
+def _mask_args(g: torch.Tensor, mask):
+    """(pointer, kind) of an optional mask: a uint8 tensor or a tensor of g's element size."""
+    if mask is None:
+        return None, LGN_MASK_NONE
+    mask = _flat(mask)
+    if mask.numel() != g.numel():
+        raise ValueError("mask and tensor differ in size")
+    if mask.dtype == torch.uint8:
+        return mask.data_ptr(), LGN_MASK_U8
+    if mask.element_size() != g.element_size():
+        raise TypeError("a mask is one byte per element or a tensor of the same type")
+    return mask.data_ptr(), LGN_MASK_SAME_DTYPE
+
+
+def lgn_stats_masked(g: torch.Tensor, mask: torch.Tensor, out: torch.Tensor = None,
+                     ws: torch.Tensor = None, dtype=None) -> torch.Tensor:
+    g = _flat(g)
+    if out is None:
+        out = _struct_buf(C.sizeof(LgnStats), g.device)
+    if ws is None:
+        ws = workspace(g.device)
+    mp, mk = _mask_args(g, mask)
+    _check(load().lgn_stats_masked(g.data_ptr(), mp, mk, g.numel(), _dtype_code(g, dtype), out.data_ptr(),
+                                   ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
 def lgn_stats_solve(g: torch.Tensor, target_sparsity: float = -1.0, alpha_dtype: int = LGN_F32,
                     n_bits: int = 0, e_bits: int = -1, scale_mode: int = LGN_SCALE_QUANTILE,
                     scale_arg: float = 0.997, sigma_units: int = LGN_SIGMA_PAPER_LITERAL,
                     st: torch.Tensor = None, p: torch.Tensor = None, f: torch.Tensor = None,
-                    ws: torch.Tensor = None, dtype=None):
+                    ws: torch.Tensor = None, dtype=None, mask: torch.Tensor = None):
     """One launch for lgn_stats + lgn_threshold + lgn_fp_params; returns (st, p, f) buffers
     (p is None without a target sparsity, f is None without n_bits)."""
     g = _flat(g)
@@ -195,7 +224,8 @@ def lgn_stats_solve(g: torch.Tensor, target_sparsity: float = -1.0, alpha_dtype:
         f = _struct_buf(C.sizeof(LgnFpParams), g.device)
     if ws is None:
         ws = workspace(g.device)
-    _check(load().lgn_stats_solve(g.data_ptr(), g.numel(), _dtype_code(g, dtype), float(target_sparsity),
+    mp, mk = _mask_args(g, mask)
+    _check(load().lgn_stats_solve(g.data_ptr(), mp, mk, g.numel(), _dtype_code(g, dtype), float(target_sparsity),
                                   int(alpha_dtype), int(n_bits), int(e_bits), int(scale_mode),
                                   float(scale_arg), int(sigma_units), st.data_ptr(),
                                   p.data_ptr() if p is not None else None,

@@ -15,13 +15,13 @@ struct StreamArgs {
     const lgn_fp_params_t *f;
     uint32_t k0, k1;
 };
-hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws,
-                        int max_blocks, hipStream_t stream);
+hipError_t launch_stats(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                        lgn_stats_t *out, void *ws, int max_blocks, hipStream_t stream);
 size_t stats_workspace_bytes();
 hipError_t launch_workspace_init(void *ws, hipStream_t stream);
-hipError_t launch_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity,
-                              int alpha_dtype, int n_bits, int e_bits, int scale_mode,
-                              double scale_arg, int sigma_units, lgn_stats_t *st,
+hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                              double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
+                              int scale_mode, double scale_arg, int sigma_units, lgn_stats_t *st,
                               lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
                               hipStream_t stream);
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
@@ -124,6 +124,15 @@ int check_stats_args(const void *g, uint64_t n, int dtype, const lgn_stats_t *ou
     return LGN_OK;
 }
 
+int check_mask_args(const void *mask, int mask_kind, uint64_t n)
+{
+    if (mask_kind != LGN_MASK_NONE && mask_kind != LGN_MASK_SAME_DTYPE && mask_kind != LGN_MASK_U8)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown mask kind %d", mask_kind);
+    if (mask_kind != LGN_MASK_NONE && n && (!mask || !aligned(mask, 16)))
+        return fail(LGN_ERR_INVALID_ARG, "mask null or not 16-byte aligned");
+    return LGN_OK;
+}
+
 int check_threshold_args(double target_sparsity, int alpha_dtype)
 {
     if (!dtype_ok(alpha_dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown alpha dtype %d", alpha_dtype);
@@ -186,17 +195,29 @@ int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, 
               void *stream)
 {
     if (int rc = check_stats_args(g, n, dtype, out, ws, ws_bytes)) return rc;
-    const hipError_t e = lgn::launch_stats(g, n, dtype, out, ws, stats_blocks_cap(dtype),
-                                           static_cast<hipStream_t>(stream));
+    const hipError_t e = lgn::launch_stats(g, nullptr, LGN_MASK_NONE, n, dtype, out, ws,
+                                           stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats", e);
 }
 
-int lgn_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity, int alpha_dtype,
-                    int n_bits, int e_bits, int scale_mode, double scale_arg, int sigma_units,
-                    lgn_stats_t *st_out, lgn_prune_params_t *p_out, lgn_fp_params_t *f_out,
-                    void *ws, size_t ws_bytes, void *stream)
+int lgn_stats_masked(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                     lgn_stats_t *out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_stats_args(g, n, dtype, out, ws, ws_bytes)) return rc;
+    if (int rc = check_mask_args(mask, mask_kind, n)) return rc;
+    const hipError_t e = lgn::launch_stats(g, mask, mask_kind, n, dtype, out, ws,
+                                           stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_masked", e);
+}
+
+int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                    double target_sparsity, int alpha_dtype, int n_bits, int e_bits, int scale_mode,
+                    double scale_arg, int sigma_units, lgn_stats_t *st_out,
+                    lgn_prune_params_t *p_out, lgn_fp_params_t *f_out, void *ws, size_t ws_bytes,
+                    void *stream)
 {
     if (int rc = check_stats_args(g, n, dtype, st_out, ws, ws_bytes)) return rc;
+    if (int rc = check_mask_args(mask, mask_kind, n)) return rc;
     const bool want_p = target_sparsity >= 0.0 || target_sparsity != target_sparsity;
     if (want_p) {
         if (int rc = check_threshold_args(target_sparsity, alpha_dtype)) return rc;
@@ -209,7 +230,7 @@ int lgn_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity
             return fail(LGN_ERR_INVALID_ARG, "fp params struct null or not 8-byte aligned");
     }
     const hipError_t e = lgn::launch_stats_solve(
-        g, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
+        g, mask, mask_kind, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
         scale_arg, sigma_units, st_out, want_p ? p_out : nullptr, n_bits ? f_out : nullptr, ws,
         stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_solve", e);

@@ -197,12 +197,108 @@ __device__ __forceinline__ void store_partial(Partial *dst, const Partial &p, bo
     for (int i = 0; i < 5; ++i) __hip_atomic_store(d + i, w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int DTYPE, bool WRITE_THROUGH>
-__device__ __forceinline__ void stage1_body(const void *__restrict__ g, uint64_t n,
-                                            Partial *partials)
+// ---- optional mask: statistics of the right mode of a bi-modal gradient ---------------------
+// (appendix "Algorithm for bi-Modal lognormal pruning", step 3: only the values whose
+// corresponding entries in the other gradient tensor are non-zero).  MASK = 0: none; 1: a tensor
+// of the same type as g (entry counts iff its pattern is not +-0); 2: one byte per element.
+// A masked-out element is turned into a zero pattern, which the accumulation leaves out anyway.
+template <int DTYPE, int MASK>
+struct MaskVec {  // the mask entries that go with one 16-byte vector of g
+};
+template <int DTYPE>
+struct MaskVec<DTYPE, 1> {
+    uint4 v;
+};
+template <>
+struct MaskVec<LGN_F32, 2> {
+    uint32_t v;  // four bytes
+};
+template <>
+struct MaskVec<LGN_BF16, 2> {
+    uint2 v;  // eight bytes
+};
+
+template <int DTYPE, int MASK>
+__device__ __forceinline__ MaskVec<DTYPE, MASK> load_mask_vec(const void *mask, uint64_t vec)
+{
+    MaskVec<DTYPE, MASK> m;
+    if constexpr (MASK == 1) {
+        m.v = load_stream16(reinterpret_cast<const uint4 *>(mask) + vec);
+    } else if constexpr (MASK == 2 && DTYPE == LGN_F32) {
+        m.v = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(mask) + vec);
+    } else if constexpr (MASK == 2) {
+        const u32x2_t x = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(mask) + vec);
+        m.v = make_uint2(x.x, x.y);
+    }
+    return m;
+}
+
+// keeps the 16-bit halves of w whose mask halves (sign bit aside) / mask bytes are non-zero
+__device__ __forceinline__ uint32_t keep_halves(uint32_t w, bool lo, bool hi)
+{
+    return w & ((lo ? 0x0000ffffu : 0u) | (hi ? 0xffff0000u : 0u));
+}
+
+template <int DTYPE, int MASK>
+__device__ __forceinline__ uint4 apply_mask(uint4 g, const MaskVec<DTYPE, MASK> &m)
+{
+    if constexpr (MASK == 1 && DTYPE == LGN_F32) {
+        g.x = (m.v.x & 0x7fffffffu) ? g.x : 0u;
+        g.y = (m.v.y & 0x7fffffffu) ? g.y : 0u;
+        g.z = (m.v.z & 0x7fffffffu) ? g.z : 0u;
+        g.w = (m.v.w & 0x7fffffffu) ? g.w : 0u;
+    } else if constexpr (MASK == 1) {
+        g.x = keep_halves(g.x, m.v.x & 0x7fffu, m.v.x & 0x7fff0000u);
+        g.y = keep_halves(g.y, m.v.y & 0x7fffu, m.v.y & 0x7fff0000u);
+        g.z = keep_halves(g.z, m.v.z & 0x7fffu, m.v.z & 0x7fff0000u);
+        g.w = keep_halves(g.w, m.v.w & 0x7fffu, m.v.w & 0x7fff0000u);
+    } else if constexpr (MASK == 2 && DTYPE == LGN_F32) {
+        g.x = (m.v & 0x000000ffu) ? g.x : 0u;
+        g.y = (m.v & 0x0000ff00u) ? g.y : 0u;
+        g.z = (m.v & 0x00ff0000u) ? g.z : 0u;
+        g.w = (m.v & 0xff000000u) ? g.w : 0u;
+    } else if constexpr (MASK == 2) {
+        g.x = keep_halves(g.x, m.v.x & 0x000000ffu, m.v.x & 0x0000ff00u);
+        g.y = keep_halves(g.y, m.v.x & 0x00ff0000u, m.v.x & 0xff000000u);
+        g.z = keep_halves(g.z, m.v.y & 0x000000ffu, m.v.y & 0x0000ff00u);
+        g.w = keep_halves(g.w, m.v.y & 0x00ff0000u, m.v.y & 0xff000000u);
+    }
+    return g;
+}
+
+// mask entry of one element (tail of the tensor)
+template <int DTYPE, int MASK>
+__device__ __forceinline__ bool mask_elem(const void *mask, uint64_t i)
+{
+    if constexpr (MASK == 1) return (load_elem<DTYPE>(mask, i) & 0x7fffffffu) != 0u;
+    else if constexpr (MASK == 2) return reinterpret_cast<const uint8_t *>(mask)[i] != 0;
+    else return true;
+}
+
+// One 16-byte vector of g with its mask entries, as loaded (the mask is applied when the row is
+// reduced, so that both loads can stay in flight).
+template <int DTYPE, int MASK>
+struct Row {
+    uint4 g;
+    MaskVec<DTYPE, MASK> m;
+};
+
+template <int DTYPE, int MASK>
+__device__ __forceinline__ Row<DTYPE, MASK> load_row(const uint4 *gv, const void *mask, uint64_t vec)
+{
+    Row<DTYPE, MASK> r;
+    r.g = load_stream16(gv + vec);
+    r.m = load_mask_vec<DTYPE, MASK>(mask, vec);
+    return r;
+}
+
+template <int DTYPE, bool WRITE_THROUGH, int MASK>
+__device__ __forceinline__ void stage1_body(const void *__restrict__ g, const void *__restrict__ mask,
+                                            uint64_t n, Partial *partials)
 {
     constexpr int EPV = DTYPE == LGN_F32 ? 4 : 8;  // elements per 16-byte vector
     constexpr int kWavesPerBlock = kBlock / kWave;
+    using R = Row<DTYPE, MASK>;
     const uint64_t nvec = n / EPV;
     const uint64_t nrows = nvec / kWave;  // full rows of 64 vectors (1 KiB)
     const uint64_t nwaves = (uint64_t)gridDim.x * kWavesPerBlock;
@@ -220,7 +316,8 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, uint64_t
     // log2 as the hardware instruction returns it.
     uint32_t pivot_bits = 0x3f800000u;
     if (wave < nrows) {
-        const uint4 v = gv[wave * kWave + lane];
+        const R r = load_row<DTYPE, MASK>(gv, mask, wave * kWave + lane);
+        const uint4 v = apply_mask<DTYPE, MASK>(r.g, r.m);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
         uint32_t cand = 0u;
 #pragma unroll
@@ -235,6 +332,9 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, uint64_t
         pivot_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)pivot_bits);
     }
     const float pivot = __builtin_amdgcn_logf(__uint_as_float(pivot_bits));
+    auto reduce = [&](const R &r) {
+        cnt += accumulate_vec<DTYPE>(apply_mask<DTYPE, MASK>(r.g, r.m), pivot_bits, pivot, t);
+    };
 
     // Full rows, wave-uniform control flow.  A batch is four CONSECUTIVE rows (4 KiB contiguous
     // per wave): strides of a power-of-two number of rows between the loads of one wave alias in
@@ -243,60 +343,52 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, uint64_t
     const uint64_t nbatches = nrows / 4;
     if (wave < nbatches) {
         // Two register sets used alternately.  Inside the loop every load is unconditional, so
-        // the compiler waits for exactly the four older loads while the four younger ones stay in
+        // the compiler waits for exactly the older loads while the younger ones stay in
         // flight; the last batch of the wave is reduced after the loop.
-        uint4 a0, a1, a2, a3, b0, b1, b2, b3;
+        R a0, a1, a2, a3, b0, b1, b2, b3;
         uint64_t cur = wave;  // batch held in the a-set
         {
-            const uint4 *p = gv + cur * (4 * kWave) + lane;
-            a0 = load_stream16(p); a1 = load_stream16(p + kWave); a2 = load_stream16(p + 2 * kWave); a3 = load_stream16(p + 3 * kWave);
+            const uint64_t v = cur * (4 * kWave) + lane;
+            a0 = load_row<DTYPE, MASK>(gv, mask, v); a1 = load_row<DTYPE, MASK>(gv, mask, v + kWave);
+            a2 = load_row<DTYPE, MASK>(gv, mask, v + 2 * kWave); a3 = load_row<DTYPE, MASK>(gv, mask, v + 3 * kWave);
         }
         bool in_a = true;  // which set holds the batch that is still to be reduced
         while (cur + nwaves < nbatches) {
             {
-                const uint4 *p = gv + (cur + nwaves) * (4 * kWave) + lane;
-                b0 = load_stream16(p); b1 = load_stream16(p + kWave); b2 = load_stream16(p + 2 * kWave); b3 = load_stream16(p + 3 * kWave);
+                const uint64_t v = (cur + nwaves) * (4 * kWave) + lane;
+                b0 = load_row<DTYPE, MASK>(gv, mask, v); b1 = load_row<DTYPE, MASK>(gv, mask, v + kWave);
+                b2 = load_row<DTYPE, MASK>(gv, mask, v + 2 * kWave); b3 = load_row<DTYPE, MASK>(gv, mask, v + 3 * kWave);
             }
-            cnt += accumulate_vec<DTYPE>(a0, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(a1, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(a2, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(a3, pivot_bits, pivot, t);
+            reduce(a0); reduce(a1); reduce(a2); reduce(a3);
             cur += nwaves;
             if (!(cur + nwaves < nbatches)) {
                 in_a = false;
                 break;
             }
             {
-                const uint4 *p = gv + (cur + nwaves) * (4 * kWave) + lane;
-                a0 = load_stream16(p); a1 = load_stream16(p + kWave); a2 = load_stream16(p + 2 * kWave); a3 = load_stream16(p + 3 * kWave);
+                const uint64_t v = (cur + nwaves) * (4 * kWave) + lane;
+                a0 = load_row<DTYPE, MASK>(gv, mask, v); a1 = load_row<DTYPE, MASK>(gv, mask, v + kWave);
+                a2 = load_row<DTYPE, MASK>(gv, mask, v + 2 * kWave); a3 = load_row<DTYPE, MASK>(gv, mask, v + 3 * kWave);
             }
-            cnt += accumulate_vec<DTYPE>(b0, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(b1, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(b2, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(b3, pivot_bits, pivot, t);
+            reduce(b0); reduce(b1); reduce(b2); reduce(b3);
             cur += nwaves;
         }
         if (in_a) {
-            cnt += accumulate_vec<DTYPE>(a0, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(a1, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(a2, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(a3, pivot_bits, pivot, t);
+            reduce(a0); reduce(a1); reduce(a2); reduce(a3);
         } else {
-            cnt += accumulate_vec<DTYPE>(b0, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(b1, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(b2, pivot_bits, pivot, t);
-            cnt += accumulate_vec<DTYPE>(b3, pivot_bits, pivot, t);
+            reduce(b0); reduce(b1); reduce(b2); reduce(b3);
         }
     }
     // up to three full rows after the last batch
     for (uint64_t row = nbatches * 4 + wave; row < nrows; row += nwaves)
-        cnt += accumulate_vec<DTYPE>(gv[row * kWave + lane], pivot_bits, pivot, t);
+        reduce(load_row<DTYPE, MASK>(gv, mask, row * kWave + lane));
 
     // what is left: fewer than 64 vectors, then fewer than EPV elements; one wave, careful path
     if (wave == nwaves - 1) {
         const uint64_t v = nrows * kWave + lane;
         if (v < nvec) {
-            const uint4 x = gv[v];
+            const R r = load_row<DTYPE, MASK>(gv, mask, v);
+            const uint4 x = apply_mask<DTYPE, MASK>(r.g, r.m);
             const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -309,7 +401,8 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, uint64_t
             }
         }
         const uint64_t tail = nvec * EPV + lane;
-        if (lane < (uint32_t)EPV && tail < n) accumulate_careful(load_elem<DTYPE>(g, tail), pivot, t);
+        if (lane < (uint32_t)EPV && tail < n && mask_elem<DTYPE, MASK>(mask, tail))
+            accumulate_careful(load_elem<DTYPE>(g, tail), pivot, t);
     }
 
     // wave totals relative to the wave's pivot, then (count, mean, M2)
@@ -337,11 +430,12 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, uint64_t
     }
 }
 
-template <int DTYPE>
-__global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ g, uint64_t n,
+template <int DTYPE, int MASK>
+__global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ g,
+                                                       const void *__restrict__ mask, uint64_t n,
                                                        Partial *__restrict__ partials)
 {
-    stage1_body<DTYPE, false>(g, n, partials);
+    stage1_body<DTYPE, false, MASK>(g, mask, n, partials);
 }
 
 // Merges `count` per-block records; thread 0 writes the result to *out and, if given, to *lds_out.
@@ -424,14 +518,15 @@ struct SolveRequest {
     double scale_arg;
 };
 
-template <int DTYPE>
-__global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restrict__ g, uint64_t n,
+template <int DTYPE, int MASK>
+__global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restrict__ g,
+                                                             const void *__restrict__ mask, uint64_t n,
                                                              Partial *partials, unsigned int *ticket,
                                                              SolveRequest rq, lgn_stats_t *st_out,
                                                              lgn_prune_params_t *p_out,
                                                              lgn_fp_params_t *f_out)
 {
-    stage1_body<DTYPE, true>(g, n, partials);
+    stage1_body<DTYPE, true, MASK>(g, mask, n, partials);
     __shared__ bool is_last;
     __shared__ lgn_stats_t st_lds;
     if (threadIdx.x == 0) {
@@ -485,26 +580,68 @@ hipError_t launch_workspace_init(void *ws, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws,
-                        int max_blocks, hipStream_t stream)
+// Calls f.template operator()<DTYPE, MASK>() for the run-time pair (dtype, mask_kind).
+template <typename F>
+static void dispatch_dtype_mask(int dtype, int mask_kind, F &&f)
+{
+    if (dtype == LGN_F32) {
+        if (mask_kind == LGN_MASK_SAME_DTYPE) f.template operator()<LGN_F32, 1>();
+        else if (mask_kind == LGN_MASK_U8) f.template operator()<LGN_F32, 2>();
+        else f.template operator()<LGN_F32, 0>();
+    } else {
+        if (mask_kind == LGN_MASK_SAME_DTYPE) f.template operator()<LGN_BF16, 1>();
+        else if (mask_kind == LGN_MASK_U8) f.template operator()<LGN_BF16, 2>();
+        else f.template operator()<LGN_BF16, 0>();
+    }
+}
+
+struct Stage1Launch {
+    const void *g, *mask;
+    uint64_t n;
+    Partial *partials;
+    int blocks;
+    hipStream_t stream;
+    template <int DTYPE, int MASK>
+    void operator()() const
+    {
+        stats_stage1<DTYPE, MASK><<<blocks, kBlock, 0, stream>>>(g, mask, n, partials);
+    }
+};
+
+struct SolveLaunch {
+    const void *g, *mask;
+    uint64_t n;
+    Partial *partials;
+    unsigned int *ticket;
+    SolveRequest rq;
+    lgn_stats_t *st;
+    lgn_prune_params_t *p;
+    lgn_fp_params_t *f;
+    int blocks;
+    hipStream_t stream;
+    template <int DTYPE, int MASK>
+    void operator()() const
+    {
+        stats_solve_kernel<DTYPE, MASK><<<blocks, kBlock, 0, stream>>>(g, mask, n, partials, ticket, rq, st, p, f);
+    }
+};
+
+hipError_t launch_stats(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                        lgn_stats_t *out, void *ws, int max_blocks, hipStream_t stream)
 {
     int blocks = stats_blocks(n, dtype);
     if (blocks > max_blocks) blocks = max_blocks;
     Partial *partials = static_cast<Partial *>(ws);
-    if (dtype == LGN_F32)
-        stats_stage1<LGN_F32><<<blocks, kBlock, 0, stream>>>(g, n, partials);
-    else
-        stats_stage1<LGN_BF16><<<blocks, kBlock, 0, stream>>>(g, n, partials);
+    dispatch_dtype_mask(dtype, mask_kind, Stage1Launch{g, mask, n, partials, blocks, stream});
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     stats_stage2<<<1, kBlock, 0, stream>>>(partials, blocks, n, out);
     return hipGetLastError();
 }
 
-
-hipError_t launch_stats_solve(const void *g, uint64_t n, int dtype, double target_sparsity,
-                              int alpha_dtype, int n_bits, int e_bits, int scale_mode,
-                              double scale_arg, int sigma_units, lgn_stats_t *st,
+hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                              double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
+                              int scale_mode, double scale_arg, int sigma_units, lgn_stats_t *st,
                               lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
                               hipStream_t stream)
 {
@@ -513,10 +650,8 @@ hipError_t launch_stats_solve(const void *g, uint64_t n, int dtype, double targe
     Partial *partials = static_cast<Partial *>(ws);
     unsigned int *ticket = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset);
     const SolveRequest rq = {target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode, sigma_units, scale_arg};
-    if (dtype == LGN_F32)
-        stats_solve_kernel<LGN_F32><<<blocks, kBlock, 0, stream>>>(g, n, partials, ticket, rq, st, p, f);
-    else
-        stats_solve_kernel<LGN_BF16><<<blocks, kBlock, 0, stream>>>(g, n, partials, ticket, rq, st, p, f);
+    dispatch_dtype_mask(dtype, mask_kind,
+                        SolveLaunch{g, mask, n, partials, ticket, rq, st, p, f, blocks, stream});
     return hipGetLastError();
 }
 
