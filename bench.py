@@ -58,6 +58,10 @@ def parse():
     ap.add_argument("--event-every", type=int, default=10,
                     help="record the per-kernel HIP events on every N-th timed step (each record "
                          "costs a few microseconds of stream time; 1 = every step)")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="workload c3 only: tensors are dealt round-robin to this many HIP streams (default "
+                         "priority, one workspace each), so one tensor's solver tail overlaps the next "
+                         "tensor's streaming kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain elementwise copy of the tensor before the timed region "
@@ -81,23 +85,32 @@ def bench_c3(args, lgn, SI, torch, np):
                           st=torch.empty(72, dtype=torch.uint8, device="cuda"),
                           pp=torch.empty(24, dtype=torch.uint8, device="cuda"),
                           fp=torch.empty(32, dtype=torch.uint8, device="cuda")))
-    ws = lgn.workspace(items[0]["d"].device)
     total_n = sum(c["n"] for c in tensors)
+    nstreams = max(1, min(args.streams, 4))
+    streams = [torch.cuda.Stream() for _ in range(nstreams)]
+    wss = []
+    for _ in range(nstreams):   # a workspace per stream: calls that overlap must not share one
+        w = torch.empty(lgn.lgn_workspace_bytes(0, lgn.LGN_F32), dtype=torch.uint8, device="cuda")
+        lgn.lgn_workspace_init(w)
+        wss.append(w)
+    torch.cuda.synchronize()
 
     merged = args.launches == "merged"
 
     def one_step():
-        for it in items:
+        for i, it in enumerate(items):
             c = it["cfg"]
-            if merged:
-                lgn.lgn_stats_solve(it["d"], c["sparsity"], lgn.LGN_F32, c["n_bits"], st=it["st"],
-                                    p=it["pp"], f=it["fp"], ws=ws)
-            else:
-                lgn.lgn_stats(it["d"], out=it["st"], ws=ws)
-                lgn.lgn_threshold(it["st"], c["sparsity"], lgn.LGN_F32, out=it["pp"])
-                lgn.lgn_fp_params(it["st"], c["n_bits"], out=it["fp"])
-            lgn.lgn_prune_quantize_fused(it["d"], it["pp"], it["fp"], rounding, c["rng_seed"], 0,
-                                         out=it["out"], out_kind=lgn.LGN_OUT_CODE8)
+            ws = wss[i % nstreams]
+            with torch.cuda.stream(streams[i % nstreams]):
+                if merged:
+                    lgn.lgn_stats_solve(it["d"], c["sparsity"], lgn.LGN_F32, c["n_bits"], st=it["st"],
+                                        p=it["pp"], f=it["fp"], ws=ws)
+                else:
+                    lgn.lgn_stats(it["d"], out=it["st"], ws=ws)
+                    lgn.lgn_threshold(it["st"], c["sparsity"], lgn.LGN_F32, out=it["pp"])
+                    lgn.lgn_fp_params(it["st"], c["n_bits"], out=it["fp"])
+                lgn.lgn_prune_quantize_fused(it["d"], it["pp"], it["fp"], rounding, c["rng_seed"], 0,
+                                             out=it["out"], out_kind=lgn.LGN_OUT_CODE8)
 
     for _ in range(args.warmup):
         one_step()
@@ -117,7 +130,7 @@ def bench_c3(args, lgn, SI, torch, np):
         "dtype": "u32 (bit-level prune/quantize) + f64 (statistics, solver)", "data": "synthetic",
         "config": {"workload": "c3: 20 fp32 tensors with ResNet-18 activation-gradient shapes at batch 256, "
                                "per-tensor mu, sigma and target sparsity, 20 whole chains back to back "
-                               f"({'2' if merged else '5'} launches each), "
+                               f"({'2' if merged else '5'} launches each) on {nstreams} streams, "
                                f"{args.rounding} rounding, code8 output",
                    "elements": total_n, "algorithmic_bytes_per_step": alg,
                    "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)},

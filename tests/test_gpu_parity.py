@@ -428,3 +428,37 @@ def test_stats_solve_chain_c1(lgn):
     want = O.prune_quantize(g, hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp, O.ROUND_STOCHASTIC,
                             cfg["rng_seed"], 0, O.OUT_CODE8)
     assert np.array_equal(to_host(codes), want)
+
+
+def test_two_streams_two_workspaces(lgn):
+    """Chains of different tensors issued on two streams, each with a workspace of its own, give the
+    bits of the same chains run one after the other."""
+    tensors = [mixed_tensor(3_000_001 + 4099 * i, 500 + i, SI.F32, mu=-10.0 - i, sigma=1.5 + 0.2 * i)
+               for i in range(6)]
+    devs = [to_dev(t) for t in tensors]
+    serial = []
+    for d in devs:
+        st, p, f = lgn.lgn_stats_solve(d, 0.8, lgn.LGN_F32, 6)
+        codes = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 9, 0, out_kind=O.OUT_CODE8)
+        serial.append((bytes(lgn.read_stats(st)), bytes(lgn.read_prune_params(p)), bytes(lgn.read_fp_params(f)), codes))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = []
+    for _ in streams:
+        w = torch.empty(lgn.lgn_workspace_bytes(0, lgn.LGN_F32), dtype=torch.uint8, device="cuda")
+        lgn.lgn_workspace_init(w)
+        wss.append(w)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        got = []
+        for i, d in enumerate(devs):
+            with torch.cuda.stream(streams[i % 2]):
+                st, p, f = lgn.lgn_stats_solve(d, 0.8, lgn.LGN_F32, 6, ws=wss[i % 2])
+                codes = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 9, 0, out_kind=O.OUT_CODE8)
+                got.append((st, p, f, codes))
+        torch.cuda.synchronize()
+        for (st, p, f, codes), want in zip(got, serial):
+            assert bytes(lgn.read_stats(st)) == want[0]
+            assert bytes(lgn.read_prune_params(p)) == want[1]
+            assert bytes(lgn.read_fp_params(f)) == want[2]
+            assert torch.equal(codes, want[3])
