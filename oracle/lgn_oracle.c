@@ -695,3 +695,174 @@ void orc_prefix_decode(const uint8_t *stream, const uint64_t *table, uint64_t n,
         }
     }
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Cosine similarity of stochastic pruning and heterogeneous sparsity allocation (appendix
+ * "Cosine similarity and heterogeneous stochastic pruning").
+ *
+ * Model: ln|x| - mu ~ N(0, sigma^2) truncated at c = k sigma above mu ("maximum value of
+ * k sigma"; the section on truncated lognormals measures the cut in standard deviations of the
+ * logarithm, 3 to 5, so the cut-off is taken in the log domain -- the derivation's ln(k sigma)
+ * is the same formula with another name for the cut-off).  With L = ln(alpha) - mu and
+ * Phi the standard normal CDF, per element and up to the common factor e^{2 mu}:
+ *     E[x T(x)] = E[x^2] = e^{2 sigma^2} Phi((c - 2 sigma^2)/sigma)
+ *     E[T(x)^2] = e^{L + sigma^2/2} Phi((min(L, c) - sigma^2)/sigma)
+ *                 + e^{2 sigma^2} [Phi((c - 2 sigma^2)/sigma) - Phi((L - 2 sigma^2)/sigma)]_+
+ * (the printed equations with (1 +- erf)/2 written as Phi), and
+ *     cos = E[x T(x)] / sqrt(E[x^2] E[T(x)^2]) = sqrt(E[x^2] / E[T(x)^2]).
+ * Everything is divided by e^{2 sigma^2} before it is evaluated, so large sigma cannot overflow.
+ * ------------------------------------------------------------------------------------------ */
+double orc_cosine_similarity(double sigma, double L, double c)
+{
+    const double s2 = sigma * sigma;
+    const double q = normal_cdf((c - 2.0 * s2) / sigma);
+    const double below = exp(L + 0.5 * s2 - 2.0 * s2) * normal_cdf((fmin(L, c) - s2) / sigma);
+    double above = q - normal_cdf((L - 2.0 * s2) / sigma);
+    if (above < 0.0) above = 0.0;
+    return sqrt(q / (below + above));
+}
+
+/* Largest L (threshold in the log domain, relative to mu) whose cosine similarity is still at
+ * least min_cosine; the similarity falls from 1 as L grows.  Plain bisection. */
+double orc_log_alpha_for_cosine(double sigma, double c, double min_cosine)
+{
+    double lo = -40.0 * sigma - 2.0 * sigma * sigma - 50.0, hi = c;
+    if (orc_cosine_similarity(sigma, hi, c) >= min_cosine) return hi;
+    for (int it = 0; it < 400; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (orc_cosine_similarity(sigma, mid, c) >= min_cosine) lo = mid; else hi = mid;
+        if (hi - lo <= 1e-15 * fmax(1.0, fabs(mid))) break;
+    }
+    return 0.5 * (lo + hi);
+}
+
+/* Histogram of the magnitudes of the finite non-zero entries on a logarithmic grid with eight
+ * bins per binade: a value M 2^E with M in [1, 2) and E >= -126 falls in bin
+ * (E + 127) * 8 + floor((M - 1) * 8); smaller (subnormal) values in bin floor(|x| 2^129) < 8.
+ * 2048 bins.  Used to read off a high quantile of ln|g| (section "Neural gradients lognormal
+ * distributions are truncated": the sample maximum is too noisy, a quantile such as 0.997 is
+ * taken instead). */
+#define ORC_HIST_BINS 2048
+static int hist_bin(float x)
+{
+    const double a = fabs((double)x);
+    int e;
+    if (a < ldexp(1.0, -126)) return (int)floor(a * ldexp(1.0, 129));
+    const double m = 2.0 * frexp(a, &e); /* a = m 2^(e-1), m in [1, 2) */
+    return (e - 1 + 127) * 8 + (int)floor((m - 1.0) * 8.0);
+}
+
+void orc_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist)
+{
+    memset(hist, 0, ORC_HIST_BINS * sizeof *hist);
+    for (uint64_t i = 0; i < n; ++i) {
+        const float x = load_elem(g, i, dtype);
+        if (!isfinite(x) || x == 0.0f) continue;
+        ++hist[hist_bin(x)];
+    }
+}
+
+/* ln of the lower edge of bin b (b >= 8); the upper edge of b is the lower edge of b + 1. */
+static double bin_log_edge(int b)
+{
+    return log(1.0 + (double)(b % 8) / 8.0) + (double)(b / 8 - 127) * M_LN2;
+}
+
+/* Truncation point in units of sigma: k = (y_q - mu) / sigma with y_q the q-quantile of ln|g|
+ * read off the histogram -- the bin that holds the entry of rank ceil(q N), interpolated
+ * linearly in the logarithm inside the bin.  Without a histogram (hist == NULL) the quantile of
+ * the fitted normal is used. */
+double orc_truncation_k(const uint64_t *hist, double mu, double sigma, double q)
+{
+    if (!hist) return orc_normal_quantile(q);
+    uint64_t total = 0;
+    for (int b = 0; b < ORC_HIST_BINS; ++b) total += hist[b];
+    if (total == 0 || !(sigma > 0.0)) return orc_normal_quantile(q);
+    uint64_t rank = (uint64_t)ceil(q * (double)total);
+    if (rank < 1) rank = 1;
+    if (rank > total) rank = total;
+    uint64_t before = 0;
+    int b = 0;
+    for (; b < ORC_HIST_BINS; ++b) {
+        if (before + hist[b] >= rank) break;
+        before += hist[b];
+    }
+    if (b < 8) b = 8; /* subnormal magnitudes: the edge of the first normal bin */
+    const double lo = bin_log_edge(b), hi = bin_log_edge(b + 1);
+    const double frac = hist[b] ? (double)(rank - before) / (double)hist[b] : 1.0;
+    return (lo + (hi - lo) * frac - mu) / sigma;
+}
+
+typedef struct {
+    double sparsity; /* zero fraction of the whole tensor predicted at the layer's threshold */
+    double cosine;   /* predicted cosine similarity at that threshold (1 if not defined)      */
+    double k;        /* truncation point used, in units of sigma                               */
+    uint32_t status; /* bit 0: the threshold was lowered to keep the minimum cosine similarity;
+                        bit 1: the compensating sparsity hit the cap                           */
+    uint32_t reserved;
+} orc_alloc_t;
+
+static double whole_tensor_sparsity(const orc_stats_t *st, const orc_prune_params_t *p)
+{
+    const double zero_frac = st->n ? 1.0 - (double)st->nnz / (double)st->n : 0.0;
+    return zero_frac + (1.0 - zero_frac) * (p->alpha > 0.0f ? p->s_pred : 0.0);
+}
+
+/* Heterogeneous allocation (appendix "Heterogeneous algorithm").  Layers are given in the order
+ * of the backward pass, deepest first.  For each of the first n_deep layers the threshold for the
+ * overall sparsity is computed; if the predicted cosine similarity falls short of the layer's
+ * minimum, the threshold is lowered until it is met.  The sparsity those layers lose is made up by
+ * the remaining layers, weighted by element counts, so that the element-weighted mean stays at
+ * the overall sparsity -- but never above max_sparsity.  hists: n_layers x 2048 counts, or NULL. */
+void orc_sparsity_allocate(const orc_stats_t *stats, const uint64_t *hists, int n_layers,
+                           double overall_sparsity, int n_deep, const double *min_cosine,
+                           double max_sparsity, double quantile, int alpha_dtype,
+                           orc_prune_params_t *p_out, orc_alloc_t *a_out)
+{
+    double total = 0.0, deep_elems = 0.0, deep_zeros = 0.0;
+    for (int i = 0; i < n_layers; ++i) total += (double)stats[i].n;
+    if (n_deep > n_layers) n_deep = n_layers;
+    for (int i = 0; i < n_layers; ++i) {
+        const orc_stats_t *st = &stats[i];
+        memset(&a_out[i], 0, sizeof a_out[i]);
+        double target = overall_sparsity;
+        if (i >= n_deep) {
+            const double rest = total - deep_elems;
+            target = rest > 0.0 ? (overall_sparsity * total - deep_zeros) / rest : overall_sparsity;
+            if (target > max_sparsity) {
+                target = max_sparsity;
+                a_out[i].status |= 2u;
+            }
+            if (target < 0.0) target = 0.0;
+        }
+        orc_threshold(st, target, alpha_dtype, &p_out[i]);
+        const int fitted = st->nnz != 0 && st->sigma >= 1e-12;
+        const double k = fitted ? orc_truncation_k(hists ? hists + (size_t)i * ORC_HIST_BINS : NULL,
+                                                   st->mu, st->sigma, quantile)
+                                : 0.0;
+        a_out[i].k = k;
+        a_out[i].cosine = 1.0;
+        if (fitted && p_out[i].alpha > 0.0f) {
+            const double c = k * st->sigma;
+            double L = log((double)p_out[i].alpha) - st->mu;
+            if (i < n_deep && orc_cosine_similarity(st->sigma, L, c) < min_cosine[i]) {
+                /* lower the threshold to the one that just keeps the minimum similarity */
+                L = orc_log_alpha_for_cosine(st->sigma, c, min_cosine[i]);
+                double alpha = exp(st->mu + L);
+                float af = alpha >= (double)FLT_MAX ? FLT_MAX : (float)alpha;
+                if (alpha_dtype == ORC_BF16) af = bf16_to_float(float_to_bf16(af));
+                p_out[i].alpha = af;
+                p_out[i].s_pred = af > 0.0f ? orc_sparsity_of_alpha(st->mu, st->sigma, (double)af) : 0.0;
+                p_out[i].s_eff = p_out[i].s_pred;
+                a_out[i].status |= 1u;
+                L = af > 0.0f ? log((double)af) - st->mu : L;
+            }
+            if (p_out[i].alpha > 0.0f) a_out[i].cosine = orc_cosine_similarity(st->sigma, L, c);
+        }
+        a_out[i].sparsity = whole_tensor_sparsity(st, &p_out[i]);
+        if (i < n_deep) {
+            deep_elems += (double)st->n;
+            deep_zeros += (double)st->n * a_out[i].sparsity;
+        }
+    }
+}

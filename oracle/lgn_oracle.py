@@ -91,6 +91,14 @@ def lib():
         L.orc_quantize_one.restype = u32
         L.orc_prune_one.argtypes = [f32, f32, u32]
         L.orc_prune_one.restype = f32
+        L.orc_cosine_similarity.argtypes = [dbl, dbl, dbl]
+        L.orc_cosine_similarity.restype = dbl
+        L.orc_log_alpha_for_cosine.argtypes = [dbl, dbl, dbl]
+        L.orc_log_alpha_for_cosine.restype = dbl
+        L.orc_log_histogram.argtypes = [vp, u64, i32, vp]
+        L.orc_truncation_k.argtypes = [vp, dbl, dbl, dbl]
+        L.orc_truncation_k.restype = dbl
+        L.orc_sparsity_allocate.argtypes = [vp, vp, i32, dbl, i32, vp, dbl, dbl, i32, vp, vp]
         L.orc_prefix_chunks.argtypes = [u64]
         L.orc_prefix_chunks.restype = u64
         L.orc_prefix_bound_bytes.argtypes = [u64, i32]
@@ -320,3 +328,50 @@ def prefix_decode(stream: np.ndarray, table: np.ndarray, n: int, width: int, spe
     out = np.empty(n, dtype={32: np.uint32, 16: np.uint16}.get(width, np.uint8))
     lib().orc_prefix_decode(_ptr(stream), _ptr(table), int(n), int(width), int(special), _ptr(out))
     return out
+
+
+# ---- cosine similarity of stochastic pruning, heterogeneous allocation -----------------------
+HIST_BINS = 2048
+
+
+class Alloc(C.Structure):
+    _fields_ = [("sparsity", C.c_double), ("cosine", C.c_double), ("k", C.c_double),
+                ("status", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+def cosine_similarity(sigma: float, log_alpha_rel: float, cutoff: float) -> float:
+    """Closed-form cos(X, T(X)) for ln|x| - mu ~ N(0, sigma^2) truncated at `cutoff` above mu;
+    log_alpha_rel = ln(alpha) - mu."""
+    return float(lib().orc_cosine_similarity(float(sigma), float(log_alpha_rel), float(cutoff)))
+
+
+def log_alpha_for_cosine(sigma: float, cutoff: float, min_cosine: float) -> float:
+    return float(lib().orc_log_alpha_for_cosine(float(sigma), float(cutoff), float(min_cosine)))
+
+
+def log_histogram(g: np.ndarray) -> np.ndarray:
+    g = np.ascontiguousarray(g).reshape(-1)
+    h = np.zeros(HIST_BINS, dtype=np.uint64)
+    lib().orc_log_histogram(_ptr(g), g.size, _dtype_of(g), _ptr(h))
+    return h
+
+
+def truncation_k(hist, mu: float, sigma: float, q: float = 0.997) -> float:
+    h = None if hist is None else _ptr(np.ascontiguousarray(hist, dtype=np.uint64))
+    return float(lib().orc_truncation_k(h, float(mu), float(sigma), float(q)))
+
+
+def sparsity_allocate(stats_list, hists, overall_sparsity: float, min_cosine, max_sparsity: float = 0.97,
+                      quantile: float = 0.997, alpha_dtype: int = F32):
+    """Layers deepest first; min_cosine has one entry per deep layer.  Returns (prune params, allocs)."""
+    n = len(stats_list)
+    st = (Stats * n)(*stats_list)
+    mc = np.ascontiguousarray(min_cosine, dtype=np.float64)
+    hs = None if hists is None else np.ascontiguousarray(hists, dtype=np.uint64).reshape(n, HIST_BINS)
+    p = (PruneParams * n)()
+    a = (Alloc * n)()
+    lib().orc_sparsity_allocate(C.cast(st, C.c_void_p), _ptr(hs) if hs is not None else None, n,
+                                float(overall_sparsity), int(mc.size), _ptr(mc) if mc.size else None,
+                                float(max_sparsity), float(quantile), int(alpha_dtype),
+                                C.cast(p, C.c_void_p), C.cast(a, C.c_void_p))
+    return list(p), list(a)
