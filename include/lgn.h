@@ -289,6 +289,51 @@ int lgn_prefix_encode(const void *in, uint64_t n, int in_kind, int dtype, const 
 int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_kind, int dtype,
                       const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out, void *stream);
 
+/*
+ * Histogram of the finite non-zero magnitudes of g on a logarithmic grid with eight bins per
+ * binade (LGN_HIST_BINS = 2048 bins: bin = top eleven bits of the fp32 magnitude pattern, i.e.
+ * exponent and three mantissa bits).  A high quantile of ln|g| read off it serves as the
+ * truncation point of the lognormal model (section "Neural gradients lognormal distributions are
+ * truncated": the sample maximum is too noisy, a quantile such as 0.997 is taken).
+ *   hist   device, LGN_HIST_BINS counts of 64 bits, overwritten (cleared by a small kernel first)
+ */
+#define LGN_HIST_BINS 2048
+int lgn_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, void *stream);
+
+/* Per-layer result of lgn_sparsity_allocate (device memory, 32 bytes). */
+typedef struct lgn_alloc_t {
+    double sparsity;  /* zero fraction of the whole tensor predicted at the layer's threshold      */
+    double cosine;    /* closed-form cosine similarity between the layer and its pruned version   */
+    double k;         /* truncation point of the lognormal model in units of sigma                */
+    uint32_t status;  /* LGN_ALLOC_* bits */
+    uint32_t reserved;
+} lgn_alloc_t;
+#define LGN_ALLOC_LOWERED 1u /* threshold lowered to keep the layer's minimum cosine similarity */
+#define LGN_ALLOC_CAPPED 2u  /* the compensating sparsity was limited by max_sparsity           */
+
+/*
+ * Heterogeneous stochastic pruning (appendix "Cosine similarity and heterogeneous stochastic
+ * pruning", "Heterogeneous algorithm"), one launch for all layers of a network.
+ *   stats          device, n_layers structs in the order of the backward pass (deepest layer first)
+ *   hists          device, n_layers x LGN_HIST_BINS counts from lgn_log_histogram, or null: then the
+ *                  truncation point is the `quantile` of the fitted normal itself
+ *   overall_sparsity  the element-weighted mean sparsity wanted over all layers
+ *   n_deep, min_cosine  the first n_deep layers each have a minimum cosine similarity
+ *                  (device, n_deep doubles): where the threshold for overall_sparsity would give
+ *                  less, the threshold is lowered until the closed form meets the minimum
+ *   max_sparsity   cap on the sparsity the remaining layers get to make up the difference
+ *                  (the paper suggests 0.96 to 0.98)
+ *   quantile       of ln|g| that defines the truncation point (the paper's example: 0.997)
+ *   p_out          device, n_layers lgn_prune_params_t, ready for lgn_prune / the fused pass
+ *   a_out          device, n_layers lgn_alloc_t
+ * The cosine similarity uses the truncated-lognormal closed forms of the appendix with the cut-off
+ * k sigma taken in the log domain.
+ */
+int lgn_sparsity_allocate(const lgn_stats_t *stats, const uint64_t *hists, int n_layers,
+                          double overall_sparsity, int n_deep, const double *min_cosine,
+                          double max_sparsity, double quantile, int alpha_dtype,
+                          lgn_prune_params_t *p_out, lgn_alloc_t *a_out, void *stream);
+
 const char *lgn_last_error(void);
 int lgn_version(void);
 

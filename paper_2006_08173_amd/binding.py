@@ -26,6 +26,8 @@ LGN_ST_EMPTY, LGN_ST_SIGMA0, LGN_ST_NOTHING_TO_PRUNE, LGN_ST_NOT_CONVERGED = 1, 
 LGN_ST_ALPHA_BELOW_FP_RANGE, LGN_ST_HAS_NONFINITE = 16, 32
 LGN_PREFIX_CHUNK = 4096
 LGN_MASK_NONE, LGN_MASK_SAME_DTYPE, LGN_MASK_U8 = 0, 1, 2
+LGN_HIST_BINS = 2048
+LGN_ALLOC_LOWERED, LGN_ALLOC_CAPPED = 1, 2
 
 
 class LgnStats(C.Structure):
@@ -47,7 +49,13 @@ class LgnFpParams(C.Structure):
                 ("status", C.c_uint32), ("reserved", C.c_uint32)]
 
 
+class LgnAlloc(C.Structure):
+    _fields_ = [("sparsity", C.c_double), ("cosine", C.c_double), ("k", C.c_double),
+                ("status", C.c_uint32), ("reserved", C.c_uint32)]
+
+
 assert C.sizeof(LgnStats) == 72 and C.sizeof(LgnPruneParams) == 24 and C.sizeof(LgnFpParams) == 32
+assert C.sizeof(LgnAlloc) == 32
 
 
 class LgnError(RuntimeError):
@@ -61,7 +69,8 @@ _lib = None
 EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshold",
            "lgn_fp_params", "lgn_prune", "lgn_fp_quantize", "lgn_prune_quantize_fused",
            "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_stats_masked", "lgn_prefix_encode",
-           "lgn_prefix_decode", "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes",
+           "lgn_prefix_decode", "lgn_log_histogram", "lgn_sparsity_allocate",
+           "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes",
            "lgn_last_error", "lgn_version")
 
 
@@ -100,7 +109,9 @@ def load():
     L.lgn_prefix_table_bytes.restype = sz
     L.lgn_prefix_bound_bytes.argtypes = [u64, i32]
     L.lgn_prefix_bound_bytes.restype = sz
-    for name in EXPORTS[2:14]:
+    L.lgn_log_histogram.argtypes = [vp, u64, i32, vp, vp]
+    L.lgn_sparsity_allocate.argtypes = [vp, vp, i32, dbl, i32, vp, dbl, dbl, i32, vp, vp, vp]
+    for name in EXPORTS[2:16]:
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -349,6 +360,42 @@ def lgn_prefix_decode(stream_buf: torch.Tensor, table: torch.Tensor, n: int, in_
                                     int(dtype), p.data_ptr() if p is not None else None,
                                     f.data_ptr() if f is not None else None, out.data_ptr(), _stream()))
     return out
+
+
+def lgn_log_histogram(g: torch.Tensor, out: torch.Tensor = None, dtype=None) -> torch.Tensor:
+    g = _flat(g)
+    if out is None:
+        out = torch.empty(LGN_HIST_BINS, dtype=torch.int64, device=g.device)
+    _check(load().lgn_log_histogram(g.data_ptr(), g.numel(), _dtype_code(g, dtype), out.data_ptr(), _stream()))
+    return out
+
+
+def lgn_sparsity_allocate(stats: torch.Tensor, hists, n_layers: int, overall_sparsity: float,
+                          min_cosine: torch.Tensor = None, max_sparsity: float = 0.97,
+                          quantile: float = 0.997, alpha_dtype: int = LGN_F32,
+                          p_out: torch.Tensor = None, a_out: torch.Tensor = None):
+    """stats: n_layers lgn_stats_t back to back (deepest layer first); hists: n_layers x 2048 int64
+    or None; min_cosine: float64 tensor, one entry per deep layer.  Returns (p_out, a_out) buffers."""
+    if p_out is None:
+        p_out = torch.empty(max(n_layers, 1) * C.sizeof(LgnPruneParams), dtype=torch.uint8, device=stats.device)
+    if a_out is None:
+        a_out = torch.empty(max(n_layers, 1) * C.sizeof(LgnAlloc), dtype=torch.uint8, device=stats.device)
+    n_deep = 0 if min_cosine is None else int(min_cosine.numel())
+    if n_deep and min_cosine.dtype != torch.float64:
+        raise TypeError("min_cosine must be float64")
+    _check(load().lgn_sparsity_allocate(stats.data_ptr(), hists.data_ptr() if hists is not None else None,
+                                        int(n_layers), float(overall_sparsity), n_deep,
+                                        min_cosine.data_ptr() if n_deep else None, float(max_sparsity),
+                                        float(quantile), int(alpha_dtype), p_out.data_ptr(), a_out.data_ptr(),
+                                        _stream()))
+    return p_out, a_out
+
+
+def read_array(buf: torch.Tensor, cls, count: int):
+    """`count` structs of type cls stored back to back in a device buffer."""
+    raw = bytes(buf.cpu().numpy().tobytes())
+    size = C.sizeof(cls)
+    return [cls.from_buffer_copy(raw[i * size:(i + 1) * size]) for i in range(count)]
 
 
 # ---- moving the small structs between host and device (tests, logging) ------------------------

@@ -7,7 +7,7 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblgn.so")
-SOURCES = ["api.hip", "stats.hip", "solver.hip", "stream.hip", "prefix.hip"]
+SOURCES = ["api.hip", "stats.hip", "solver.hip", "stream.hip", "prefix.hip", "alloc.hip"]
 HEADERS = [os.path.join(CSRC, "lgn_device.hpp"), os.path.join(CSRC, "solver_device.hpp"),
            os.path.join(CSRC, "fpcode_device.hpp"),
            os.path.join(os.path.dirname(PKG), "include", "lgn.h")]

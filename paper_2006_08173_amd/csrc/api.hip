@@ -39,6 +39,12 @@ hipError_t launch_prefix_encode(int width_class, const void *in, uint64_t n, con
 hipError_t launch_prefix_decode(int width_class, const void *in, const uint64_t *table, uint64_t n,
                                 const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out,
                                 hipStream_t stream);
+hipError_t launch_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, int max_blocks,
+                                hipStream_t stream);
+hipError_t launch_sparsity_allocate(const lgn_stats_t *stats, const uint64_t *hists, int n_layers,
+                                    double overall, int n_deep, const double *min_cosine,
+                                    double max_sparsity, double quantile, int alpha_dtype,
+                                    lgn_prune_params_t *p_out, lgn_alloc_t *a_out, hipStream_t stream);
 }  // namespace lgn
 
 namespace {
@@ -359,6 +365,39 @@ int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_
     const hipError_t e = lgn::launch_prefix_decode(wc, in, table, n, p, f, out,
                                                    static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_prefix_decode", e);
+}
+
+int lgn_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, void *stream)
+{
+    if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (!hist || !aligned(hist, 8)) return fail(LGN_ERR_INVALID_ARG, "histogram null or not 8-byte aligned");
+    if (n && (!g || !aligned(g, 16))) return fail(LGN_ERR_INVALID_ARG, "input null or not 16-byte aligned");
+    if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
+    const hipError_t e = lgn::launch_log_histogram(g, n, dtype, hist, stream_blocks(),
+                                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_log_histogram", e);
+}
+
+int lgn_sparsity_allocate(const lgn_stats_t *stats, const uint64_t *hists, int n_layers,
+                          double overall_sparsity, int n_deep, const double *min_cosine,
+                          double max_sparsity, double quantile, int alpha_dtype,
+                          lgn_prune_params_t *p_out, lgn_alloc_t *a_out, void *stream)
+{
+    if (n_layers < 0 || n_layers > (1 << 20)) return fail(LGN_ERR_INVALID_ARG, "n_layers %d out of range", n_layers);
+    if (n_layers == 0) return LGN_OK;
+    if (!stats || !p_out || !a_out) return fail(LGN_ERR_INVALID_ARG, "null struct pointer");
+    if (!aligned(stats, 8) || !aligned(p_out, 8) || !aligned(a_out, 8) || !aligned(hists, 8) || !aligned(min_cosine, 8))
+        return fail(LGN_ERR_INVALID_ARG, "pointer not 8-byte aligned");
+    if (n_deep < 0) return fail(LGN_ERR_INVALID_ARG, "negative n_deep");
+    if (n_deep > 0 && !min_cosine) return fail(LGN_ERR_INVALID_ARG, "deep layers need their minimum cosine similarities");
+    if (int rc = check_threshold_args(overall_sparsity, alpha_dtype)) return rc;
+    if (!(max_sparsity >= 0.0 && max_sparsity < 1.0))
+        return fail(LGN_ERR_INVALID_ARG, "max_sparsity %g outside [0, 1)", max_sparsity);
+    if (!(quantile > 0.0 && quantile < 1.0)) return fail(LGN_ERR_INVALID_ARG, "quantile %g outside (0, 1)", quantile);
+    const hipError_t e = lgn::launch_sparsity_allocate(stats, hists, n_layers, overall_sparsity, n_deep,
+                                                       min_cosine, max_sparsity, quantile, alpha_dtype,
+                                                       p_out, a_out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_sparsity_allocate", e);
 }
 
 }  // extern "C"
