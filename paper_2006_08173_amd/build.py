@@ -6,7 +6,8 @@ import subprocess
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
-LIB = os.path.join(PKG, "liblgn.so")
+# LGN_LIB points the binding at another build of the library (A/B timing of kernel variants)
+LIB = os.environ.get("LGN_LIB") or os.path.join(PKG, "liblgn.so")
 SOURCES = ["api.hip", "stats.hip", "solver.hip", "stream.hip", "prefix.hip", "alloc.hip"]
 HEADERS = [os.path.join(CSRC, "lgn_device.hpp"), os.path.join(CSRC, "solver_device.hpp"),
            os.path.join(CSRC, "fpcode_device.hpp"),

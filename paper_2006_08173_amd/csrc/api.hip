@@ -69,15 +69,16 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 
 bool dtype_ok(int d) { return d == LGN_F32 || d == LGN_BF16; }
 
-// Workgroups of a streaming launch: enough waves to fill every SIMD eight deep.
+// Upper limit of the workgroups of a streaming launch (the launch itself sizes the grid by the
+// work per wave).
 int stream_blocks()
 {
     static int cached = 0;
     if (cached) return cached;
-    int per_cu = 8;
+    int per_cu = 1024;
     if (const char *e = getenv("LGN_STREAM_BLOCKS_PER_CU")) {
         const int v = atoi(e);
-        if (v >= 1 && v <= 64) per_cu = v;
+        if (v >= 1 && v <= 1024) per_cu = v;
     }
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) {

@@ -17,6 +17,8 @@
 // PACKED output: the four N-bit codes of a lane form a 4N-bit chunk; the 64 chunks of a tile are
 // one contiguous run of 8N dwords.  Lane k < 8N assembles dword k from the (at most five) chunks
 // that overlap it, fetched with cross-lane reads, and the wave stores 8N consecutive dwords.
+#include <stdlib.h>
+
 #include "lgn_device.hpp"
 #include "fpcode_device.hpp"
 
@@ -336,57 +338,91 @@ struct WalkState {
     bool fast_ok;
 };
 
-// The tile loop of one wave.  A wave walks PAIRS of consecutive tiles (2 KiB of fp32 input): both
+// The tile loops of one wave.  A wave walks PAIRS of consecutive tiles (2 KiB of fp32 input): both
 // loads of the next pair are issued before the current pair is processed, so every wave keeps
 // 2 KiB in flight while its Philox and quantizer arithmetic runs.  With eight waves per SIMD that
 // is 16 KiB per SIMD, twice what the measured latency x bandwidth product asks for; one tile per
 // step was not enough.  DO_PRUNE and CHECK_LO select the fast-tile variant once per kernel, so
-// the loop itself carries no variant dispatch.
+// the loops carry no variant dispatch.
+//
+// First loop: the fast pairs, with 32-bit scalar bookkeeping only (pair index, the low word of the
+// quad counter, one compare each) and two register sets used alternately, so that no prefetched
+// value is ever copied.  A pair is fast if both tiles are full and its 128 quad indices share the
+// upper counter word.  Second loop: whatever the first one left out (the ragged tail, a pair that
+// straddles a 2^34-element boundary, everything if the call does not qualify) on the general path.
 template <int DTYPE, bool PRUNE, bool DO_PRUNE, bool QUANT, int ROUND, int OUT, bool CHECK_LO>
 __device__ __forceinline__ void walk_pairs(const WalkState &s)
 {
     const uint64_t n = s.a.n;
-    // a tile is fast if it is full and its 64 quad indices share the upper counter word
-    auto is_fast = [&](uint64_t t) {
-        return s.fast_ok && t < s.ntiles && (t + 1) * 256 <= n &&
-               (uint32_t)(s.qoff + t * kWave) <= 0xffffffffu - (uint32_t)kWave;
+    const uint64_t npairs = (s.ntiles + 1) / 2;
+    // pairs [0, fast_pairs) consist of full tiles; 32-bit bookkeeping covers tensors below 2^40 elements
+    const bool small = npairs <= 0x7fffffffull && s.nwaves <= 0x00ffffffull;
+    const uint32_t fast_pairs = (s.fast_ok && small) ? (uint32_t)((n / 256) / 2) : 0u;
+    const uint32_t nw = (uint32_t)s.nwaves;
+    const uint32_t qstep = nw * 128u;  // quads between two pairs of this wave (mod 2^32)
+    auto q_first = [&](uint32_t pair) { return (uint32_t)s.qoff + pair * 128u; };
+    auto no_wrap = [](uint32_t q0) { return q0 <= 0xffffff7fu; };  // q0 + 127 stays in the word
+    auto load_pair = [&](uint32_t pair, uint32_t *r) {
+        const char *base = tile_in<DTYPE>(s.a, 2ull * pair);
+        constexpr int QB = DTYPE == LGN_F32 ? 16 : 8;
+        load_quad<DTYPE>(base, (uint32_t)s.lane, r);
+        load_quad<DTYPE>(base + kWave * QB, (uint32_t)s.lane, r + 4);
     };
-    auto run_fast = [&](uint64_t t, uint32_t *b) {
+    auto run_pair = [&](uint32_t pair, uint32_t *r) {
+        const uint64_t t = 2ull * pair;
         const uint64_t qbase = s.qoff + t * kWave;  // global quad index of lane 0
         fast_tile<DTYPE, PRUNE, DO_PRUNE, QUANT, ROUND, OUT, CHECK_LO>(s.a, t, qbase, s.lane, s.key,
-                                                                       s.c, s.q, s.pk, b);
+                                                                       s.c, s.q, s.pk, r);
+        // keep the two tiles' instruction streams apart: interleaving them doubles the live
+        // registers and costs two waves of occupancy
+        __builtin_amdgcn_sched_barrier(0);
+        fast_tile<DTYPE, PRUNE, DO_PRUNE, QUANT, ROUND, OUT, CHECK_LO>(s.a, t + 1, qbase + kWave, s.lane,
+                                                                       s.key, s.c, s.q, s.pk, r + 4);
     };
-    const uint64_t npairs = (s.ntiles + 1) / 2;
-    uint64_t pair = s.wave;
-    uint32_t nb[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    bool have = is_fast(2 * pair) && is_fast(2 * pair + 1);
-    if (have) {
-        load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * pair), (uint32_t)s.lane, nb);
-        load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * pair + 1), (uint32_t)s.lane, nb + 4);
+
+    {
+        // Runs of consecutive fast pairs of this wave.  Inside a run every load is unconditional,
+        // so the compiler waits for exactly the older pair while the younger one stays in flight.
+        uint32_t ra[8], rb[8];
+        uint32_t pair = (uint32_t)min(s.wave, (uint64_t)fast_pairs), q0 = q_first(pair);
+        while (pair < fast_pairs) {
+            if (!no_wrap(q0)) {  // left to the second loop
+                pair += nw; q0 += qstep;
+                continue;
+            }
+            load_pair(pair, ra);
+            for (;;) {
+                // current pair in set A
+                uint32_t next = pair + nw, qn = q0 + qstep;
+                if (!(next < fast_pairs && no_wrap(qn))) {
+                    run_pair(pair, ra);
+                    pair = next; q0 = qn;
+                    break;
+                }
+                load_pair(next, rb);
+                run_pair(pair, ra);
+                pair = next; q0 = qn;
+                // current pair in set B
+                next = pair + nw; qn = q0 + qstep;
+                if (!(next < fast_pairs && no_wrap(qn))) {
+                    run_pair(pair, rb);
+                    pair = next; q0 = qn;
+                    break;
+                }
+                load_pair(next, ra);
+                run_pair(pair, rb);
+                pair = next; q0 = qn;
+            }
+        }
     }
-    while (pair < npairs) {
-        const uint64_t next = pair + s.nwaves;
-        const bool was = have;
-        uint32_t b[8] = {nb[0], nb[1], nb[2], nb[3], nb[4], nb[5], nb[6], nb[7]};
-        have = is_fast(2 * next) && is_fast(2 * next + 1);
-        if (have) {
-            load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * next), (uint32_t)s.lane, nb);
-            load_quad<DTYPE>(tile_in<DTYPE>(s.a, 2 * next + 1), (uint32_t)s.lane, nb + 4);
-        }
-        if (was) {
-            run_fast(2 * pair, b);
-            // keep the two tiles' instruction streams apart: interleaving them doubles the live
-            // registers and costs two waves of occupancy
-            __builtin_amdgcn_sched_barrier(0);
-            run_fast(2 * pair + 1, b + 4);
-        } else {
-            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(s.a, 2 * pair, s.lane, s.key, s.alpha, s.q,
+
+    for (uint64_t pair = s.wave; pair < npairs; pair += s.nwaves) {
+        if (pair < fast_pairs && no_wrap(q_first((uint32_t)pair))) continue;  // done above
+        general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(s.a, 2 * pair, s.lane, s.key, s.alpha, s.q, s.pk,
+                                                      s.packed_total);
+        if (2 * pair + 1 < s.ntiles)
+            general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(s.a, 2 * pair + 1, s.lane, s.key, s.alpha, s.q,
                                                           s.pk, s.packed_total);
-            if (2 * pair + 1 < s.ntiles)
-                general_tile<DTYPE, PRUNE, QUANT, ROUND, OUT>(s.a, 2 * pair + 1, s.lane, s.key,
-                                                              s.alpha, s.q, s.pk, s.packed_total);
-        }
-        pair = next;
     }
 }
 
@@ -500,7 +536,21 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
                   : pick_round_out<LGN_BF16, false, true>(rounding, out_kind);
     }
     const uint64_t npairs = ((args.n + 255) / 256 + 1) / 2;  // a wave step covers two tiles
-    uint64_t blocks = (npairs + (kBlock / kWave) - 1) / (kBlock / kWave);
+    // A wave gets about `per_wave` pairs.  Far more workgroups than the device holds at once
+    // (measured best at eight pairs per wave, 49 workgroups per CU on the 205 M-element tensor,
+    // against 8 per CU with ~50 pairs each: -4 % on the whole path): workgroups then start
+    // staggered, so the waves' load and arithmetic phases do not march in step.
+    static int per_wave = 0;
+    if (!per_wave) {
+        per_wave = 8;
+        if (const char *e = getenv("LGN_STREAM_PAIRS_PER_WAVE")) {
+            const int v = atoi(e);
+            if (v >= 1 && v <= 4096) per_wave = v;
+        }
+    }
+    const uint64_t per_block = (uint64_t)per_wave * (kBlock / kWave);
+    uint64_t blocks = (npairs + per_block - 1) / per_block;
+    if (blocks < 1) blocks = 1;
     if (blocks > (uint64_t)max_blocks) blocks = (uint64_t)max_blocks;
     hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(kBlock), 0, stream, args);
     return hipGetLastError();
