@@ -537,12 +537,13 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
     }
     const uint64_t npairs = ((args.n + 255) / 256 + 1) / 2;  // a wave step covers two tiles
     // A wave gets about `per_wave` pairs.  Far more workgroups than the device holds at once
-    // (measured best at eight pairs per wave, 49 workgroups per CU on the 205 M-element tensor,
-    // against 8 per CU with ~50 pairs each: -4 % on the whole path): workgroups then start
-    // staggered, so the waves' load and arithmetic phases do not march in step.
+    // (measured best at four to eight pairs per wave for every variant, i.e. ~65 workgroups per CU
+    // on the 205 M-element tensor, against 8 per CU with ~50 pairs each: -10 % on the fused
+    // pass): workgroups then start staggered, so the waves' load and arithmetic phases do not
+    // march in step.
     static int per_wave = 0;
     if (!per_wave) {
-        per_wave = 8;
+        per_wave = 6;
         if (const char *e = getenv("LGN_STREAM_PAIRS_PER_WAVE")) {
             const int v = atoi(e);
             if (v >= 1 && v <= 4096) per_wave = v;
