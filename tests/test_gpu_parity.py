@@ -462,3 +462,21 @@ def test_two_streams_two_workspaces(lgn):
             assert bytes(lgn.read_prune_params(p)) == want[1]
             assert bytes(lgn.read_fp_params(f)) == want[2]
             assert torch.equal(codes, want[3])
+
+
+def test_counter_word_boundary_in_the_middle_of_a_wave_run(lgn):
+    """The low word of the Philox quad counter wraps at element 2^34.  Place that boundary deep inside
+    the tensor, so that it falls on a pair some wave reaches in the middle of its run of pairs (not
+    on its first one): that pair must leave the fast path and come back identical."""
+    n = 2_000_000 + 77
+    g = mixed_tensor(n, 91, SI.F32)
+    d = to_dev(g)
+    p = dev_prune_params(lgn, 2e-4)
+    f = dev_fp_params(lgn, 3, 2, -13)
+    for back in (512 * 2000, 512 * 2000 + 256, 512 * 701 + 4, 512 * 3905):
+        off = (1 << 34) - back                            # multiples of four: the fast path stays eligible
+        got = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 17, off, out_kind=O.OUT_CODE8)
+        want = O.prune_quantize(g, 2e-4, 3, 2, -13, O.ROUND_STOCHASTIC, 17, off, O.OUT_CODE8)
+        assert np.array_equal(to_host(got), want), back
+        y = lgn.lgn_prune(d, p, 17, off)
+        assert np.array_equal(bits(to_host(y)), bits(O.prune(g, 2e-4, 17, off))), back
