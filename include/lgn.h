@@ -210,6 +210,19 @@ int lgn_threshold(const lgn_stats_t *st, double target_sparsity, int alpha_dtype
                   lgn_prune_params_t *out, void *stream);
 
 /*
+ * Stochastic underflow: raises a pruning threshold to the smallest magnitude the format *f can
+ * represent, alpha_out = max(alpha_in, 2^(E_min + s)), E_min = 1 - 2^(e-1) (Section 4.1).  With it
+ * the fused pass sends |g| below the format's range to 0 or +-alpha_out with the mean kept (the
+ * pruning operator of Section 5) instead of flushing it to zero.
+ *   f     device, read
+ *   in    device or null (null: alpha_in = 0, no pruning besides the underflow rule)
+ *   out   device, written; may equal in.  LGN_ST_ALPHA_BELOW_FP_RANGE is set if the threshold was
+ *         raised.  A floor outside the fp32 normal range is not applied.
+ */
+int lgn_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in, lgn_prune_params_t *out,
+                        void *stream);
+
+/*
  * FP-n format and scale (Section 4.3: minimise the expected relative error over the splits with
  * e + m = n_bits - 1; Section 4.4 and Alg. 1: per-tensor power-of-two scale).
  *   n_bits      total bits N in [2, 8]

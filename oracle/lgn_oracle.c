@@ -866,3 +866,26 @@ void orc_sparsity_allocate(const orc_stats_t *stats, const uint64_t *hists, int 
         }
     }
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Stochastic underflow.  Section 4.1 sends every magnitude below the smallest representable one,
+ * 2^(E_min + s) with E_min = 1 - 2^(e-1), to zero; the stochastic pruning operator of Section 5
+ * with alpha equal to that smallest magnitude sends it to 0 or +-alpha with the probabilities
+ * that keep the mean instead.  The threshold to use is therefore the larger of the pruning
+ * threshold (0 if there is none) and 2^(E_min + s); status bit 16 reports that the given
+ * threshold was below the format's range.  A floor below the normal range of the element type
+ * cannot be expressed and is dropped.
+ * ------------------------------------------------------------------------------------------ */
+void orc_threshold_floor(int e_bits, int scale_exp, const orc_prune_params_t *in, int alpha_dtype,
+                         orc_prune_params_t *out)
+{
+    (void)alpha_dtype; /* a power of two in the normal range is exact in both element types */
+    if (in) *out = *in; else memset(out, 0, sizeof *out);
+    const int k = 1 - (1 << (e_bits - 1)) + scale_exp;
+    if (k < -126 || k > 127) return;
+    const float floor_alpha = (float)ldexp(1.0, k);
+    if (out->alpha < floor_alpha) {
+        out->alpha = floor_alpha;
+        out->status |= 16u;
+    }
+}

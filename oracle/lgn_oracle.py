@@ -99,6 +99,7 @@ def lib():
         L.orc_truncation_k.argtypes = [vp, dbl, dbl, dbl]
         L.orc_truncation_k.restype = dbl
         L.orc_sparsity_allocate.argtypes = [vp, vp, i32, dbl, i32, vp, dbl, dbl, i32, vp, vp]
+        L.orc_threshold_floor.argtypes = [i32, i32, vp, i32, vp]
         L.orc_prefix_chunks.argtypes = [u64]
         L.orc_prefix_chunks.restype = u64
         L.orc_prefix_bound_bytes.argtypes = [u64, i32]
@@ -375,3 +376,11 @@ def sparsity_allocate(stats_list, hists, overall_sparsity: float, min_cosine, ma
                                 float(max_sparsity), float(quantile), int(alpha_dtype),
                                 C.cast(p, C.c_void_p), C.cast(a, C.c_void_p))
     return list(p), list(a)
+
+
+def threshold_floor(e_bits: int, scale_exp: int, p_in: PruneParams = None, alpha_dtype: int = F32) -> PruneParams:
+    """Pruning threshold raised to the format's smallest magnitude (stochastic underflow)."""
+    out = PruneParams()
+    lib().orc_threshold_floor(int(e_bits), int(scale_exp), C.byref(p_in) if p_in is not None else None,
+                              int(alpha_dtype), C.byref(out))
+    return out

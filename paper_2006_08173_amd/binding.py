@@ -69,7 +69,7 @@ _lib = None
 EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshold",
            "lgn_fp_params", "lgn_prune", "lgn_fp_quantize", "lgn_prune_quantize_fused",
            "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_stats_masked", "lgn_prefix_encode",
-           "lgn_prefix_decode", "lgn_log_histogram", "lgn_sparsity_allocate",
+           "lgn_prefix_decode", "lgn_log_histogram", "lgn_sparsity_allocate", "lgn_threshold_floor",
            "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes",
            "lgn_last_error", "lgn_version")
 
@@ -111,7 +111,8 @@ def load():
     L.lgn_prefix_bound_bytes.restype = sz
     L.lgn_log_histogram.argtypes = [vp, u64, i32, vp, vp]
     L.lgn_sparsity_allocate.argtypes = [vp, vp, i32, dbl, i32, vp, dbl, dbl, i32, vp, vp, vp]
-    for name in EXPORTS[2:16]:
+    L.lgn_threshold_floor.argtypes = [vp, vp, vp, vp]
+    for name in EXPORTS[2:17]:
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -251,6 +252,14 @@ def lgn_threshold(st: torch.Tensor, target_sparsity: float, alpha_dtype: int = L
         out = _struct_buf(C.sizeof(LgnPruneParams), st.device)
     _check(load().lgn_threshold(st.data_ptr(), float(target_sparsity), int(alpha_dtype),
                                 out.data_ptr(), _stream()))
+    return out
+
+
+def lgn_threshold_floor(f: torch.Tensor, p: torch.Tensor = None, out: torch.Tensor = None) -> torch.Tensor:
+    if out is None:
+        out = _struct_buf(C.sizeof(LgnPruneParams), f.device)
+    _check(load().lgn_threshold_floor(f.data_ptr(), p.data_ptr() if p is not None else None,
+                                      out.data_ptr(), _stream()))
     return out
 
 

@@ -26,6 +26,8 @@ hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, ui
                               hipStream_t stream);
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
                             lgn_prune_params_t *out, hipStream_t stream);
+hipError_t launch_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in,
+                                  lgn_prune_params_t *out, hipStream_t stream);
 hipError_t launch_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
                             double scale_arg, int sigma_units, lgn_fp_params_t *out,
                             hipStream_t stream);
@@ -252,6 +254,16 @@ int lgn_threshold(const lgn_stats_t *st, double target_sparsity, int alpha_dtype
     const hipError_t e = lgn::launch_threshold(st, target_sparsity, alpha_dtype, out,
                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_threshold", e);
+}
+
+int lgn_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in, lgn_prune_params_t *out,
+                        void *stream)
+{
+    if (!f || !out) return fail(LGN_ERR_INVALID_ARG, "null struct pointer");
+    if (!aligned(f, 8) || !aligned(in, 8) || !aligned(out, 8))
+        return fail(LGN_ERR_INVALID_ARG, "struct not 8-byte aligned");
+    const hipError_t e = lgn::launch_threshold_floor(f, in, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_threshold_floor", e);
 }
 
 int lgn_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode, double scale_arg,

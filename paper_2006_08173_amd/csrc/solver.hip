@@ -18,6 +18,42 @@ __global__ __launch_bounds__(kWave) void fp_params_kernel(const lgn_stats_t *__r
     fp_params_body(st, n_bits, e_fixed, scale_mode, scale_arg, sigma_units, out);
 }
 
+// Stochastic underflow: the pruning threshold raised to the smallest magnitude the format can
+// represent, 2^(E_min + s) with E_min = 1 - 2^(e-1) (Section 4.1), so that the pruning operator of
+// Section 5 sends smaller values to 0 or +-alpha with their mean kept instead of flushing them.
+__global__ __launch_bounds__(kWave) void threshold_floor_kernel(const lgn_fp_params_t *__restrict__ f,
+                                                                const lgn_prune_params_t *in,
+                                                                lgn_prune_params_t *out)
+{
+    if (threadIdx.x != 0) return;
+    lgn_prune_params_t r;
+    if (in) {
+        r = *in;
+    } else {
+        r.alpha = 0.0f;
+        r.status = 0u;
+        r.s_eff = 0.0;
+        r.s_pred = 0.0;
+    }
+    const int e = min(max(f->e_bits, 1), 7);
+    const int k = 1 - (1 << (e - 1)) + f->scale_exp;
+    if (k >= -126 && k <= 127) {  // otherwise the floor is not a normal number of the element type
+        const float floor_alpha = __uint_as_float((uint32_t)(k + 127) << 23);
+        if (r.alpha < floor_alpha) {
+            r.alpha = floor_alpha;
+            r.status |= LGN_ST_ALPHA_BELOW_FP_RANGE;
+        }
+    }
+    *out = r;
+}
+
+hipError_t launch_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in,
+                                  lgn_prune_params_t *out, hipStream_t stream)
+{
+    threshold_floor_kernel<<<1, kWave, 0, stream>>>(f, in, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
                             lgn_prune_params_t *out, hipStream_t stream)
 {

@@ -480,3 +480,34 @@ def test_counter_word_boundary_in_the_middle_of_a_wave_run(lgn):
         assert np.array_equal(to_host(got), want), back
         y = lgn.lgn_prune(d, p, 17, off)
         assert np.array_equal(bits(to_host(y)), bits(O.prune(g, 2e-4, 17, off))), back
+
+
+def test_stochastic_underflow_on_device(lgn):
+    """lgn_threshold_floor + the fused pass: values below the format's range become 0 or +-2^(E_min+s)
+    with the mean kept; parameters and codes equal the oracle's."""
+    for e, m, s in ((3, 2, -12), (4, 1, -20), (2, 3, 3)):
+        f = dev_fp_params(lgn, e, m, s)
+        want_p = O.threshold_floor(e, s)
+        got = lgn.read_prune_params(lgn.lgn_threshold_floor(f))
+        assert (got.alpha, got.status) == (want_p.alpha, want_p.status)
+        for a_in in (0.25 * want_p.alpha, 4.0 * want_p.alpha):
+            pin = dev_prune_params(lgn, a_in)
+            wp = O.threshold_floor(e, s, O.PruneParams(alpha=np.float32(a_in), s_eff=0.0, s_pred=0.0, status=0))
+            gp = lgn.read_prune_params(lgn.lgn_threshold_floor(f, pin))
+            assert (gp.alpha, gp.status) == (wp.alpha, wp.status)
+    e, m, s = 3, 2, -12
+    f = dev_fp_params(lgn, e, m, s)
+    p = lgn.lgn_threshold_floor(f)
+    floor = lgn.read_prune_params(p).alpha
+    g = SI.lognormal_tensor(1 << 21, seed=5, mu=math.log(floor) - 1.0, sigma=1.5, zero_frac=0.1)
+    d = to_dev(g)
+    codes = lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 21, 0, out_kind=O.OUT_CODE8)
+    want = O.prune_quantize(g, floor, e, m, s, O.ROUND_STOCHASTIC, 21, 0, O.OUT_CODE8)
+    assert np.array_equal(to_host(codes), want)
+    y = O.dequantize(to_host(codes), e, m, s).astype(np.float64)
+    small = np.abs(g) < floor
+    assert set(np.unique(np.abs(y[small]))) <= {0.0, float(floor)}
+    var = float((np.abs(g[small]).astype(np.float64) * (floor - np.abs(g[small]))).sum())
+    assert abs(float(y[small].sum() - g[small].astype(np.float64).sum())) < 6 * math.sqrt(var)
+    flushed = lgn.lgn_fp_quantize(d, f, O.ROUND_STOCHASTIC, 21, 0, out_kind=O.OUT_CODE8)
+    assert np.all(to_host(flushed)[small] == 0)           # without the floor they are lost

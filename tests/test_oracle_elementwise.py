@@ -414,3 +414,34 @@ def test_pack_layout_by_hand():
         assert np.array_equal(O.unpack(pk, 1237, n_bits), codes)
         bits = np.unpackbits(pk, bitorder="little")[: 1237 * n_bits].reshape(1237, n_bits)
         assert np.array_equal((bits * (1 << np.arange(n_bits))).sum(1), codes)
+
+
+# ------------------------------------------------------------------------ stochastic underflow
+def test_threshold_floor_is_the_smallest_magnitude_of_the_format():
+    for e, m, s in ((3, 2, -14), (2, 1, 0), (5, 2, -30), (4, 1, 7)):
+        p = O.threshold_floor(e, s)
+        # the smallest non-zero code decodes to the floor
+        assert p.alpha == O.decode(1 << m, e, m, s) and p.status == 16
+        big = O.PruneParams(alpha=np.float32(2.0 * p.alpha), s_eff=0.5, s_pred=0.5, status=0)
+        kept = O.threshold_floor(e, s, big)
+        assert kept.alpha == big.alpha and kept.status == 0 and kept.s_pred == 0.5
+        small = O.PruneParams(alpha=np.float32(0.25 * p.alpha), s_eff=0.5, s_pred=0.5, status=0)
+        raised = O.threshold_floor(e, s, small)
+        assert raised.alpha == p.alpha and raised.status == 16
+    assert O.threshold_floor(3, -200).alpha == 0.0        # below the fp32 normal range: no floor
+
+
+def test_stochastic_underflow_keeps_the_mean_where_flushing_loses_it():
+    e, m, s = 3, 2, -10
+    floor = O.threshold_floor(e, s).alpha                 # 2^-13
+    n = 1 << 20
+    for frac in (0.9, 0.5, 0.1, 0.01):
+        x = np.full(n, frac * floor, np.float32)
+        flushed = O.dequantize(O.fp_quantize(x, e, m, s, O.ROUND_STOCHASTIC, 3, 0, O.OUT_CODE8), e, m, s)
+        assert np.all(flushed == 0)                       # Section 4.1: underflow goes to zero
+        codes = O.prune_quantize(x, floor, e, m, s, O.ROUND_STOCHASTIC, 3, 0, O.OUT_CODE8)
+        y = O.dequantize(codes, e, m, s)
+        assert set(np.unique(y)) <= {0.0, np.float32(floor)}
+        keep = float(np.mean(y != 0))
+        assert abs(keep - frac) < 5 * math.sqrt(frac * (1 - frac) / n) + 1e-6
+        assert abs(float(y.mean()) - frac * floor) < 6 * floor * math.sqrt(frac * (1 - frac) / n) + 1e-12
