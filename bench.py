@@ -63,6 +63,7 @@ def parse():
                          "priority, one workspace each), so one tensor's solver tail overlaps the next "
                          "tensor's streaming kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-beyond", action="store_true", help="skip the timings of the rows beyond the hot path")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain elementwise copy of the tensor before the timed region "
                          "(known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -273,28 +274,51 @@ def main():
                                   "solve_ms": round(t_solve, 4), "fused_ms": round(t_fused, 4),
                                   "fused_GBps": round(fused_gbs, 1)}}
 
-    # Outside the timed region: the prefix code of the step's output (appendix "Encoding"), the
-    # first row beyond the hot path.  Reported beside the headline, never part of `value`.
-    extras = None
-    if out_kind == lgn.LGN_OUT_CODE8:
-        nchunks = (n + lgn.LGN_PREFIX_CHUNK - 1) // lgn.LGN_PREFIX_CHUNK
-        pbuf, ptab = lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, width=n_bits)
+    # Outside the timed region: the rows built beyond the hot path, each timed on the same tensor with
+    # HIP events.  Reported beside the headline, never part of `value`.
+    def timed(fn, reps=30):
+        fn()
         torch.cuda.synchronize()
-        reps = 30
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(reps):
-            lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, out=pbuf, table=ptab)
+            fn()
         e1.record()
         torch.cuda.synchronize()
-        enc_ms = e0.elapsed_time(e1) / reps
+        return e0.elapsed_time(e1) / reps
+
+    extras = None
+    if out_kind == lgn.LGN_OUT_CODE8 and not args.no_beyond:
+        nchunks = (n + lgn.LGN_PREFIX_CHUNK - 1) // lgn.LGN_PREFIX_CHUNK
+        pbuf, ptab = lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, width=n_bits)
+        enc_ms = timed(lambda: lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, out=pbuf, table=ptab))
         words = int(ptab[nchunks].item())
-        extras = {"prefix_encode_ms": round(enc_ms, 4), "prefix_bits_per_value": round(words * 32 / n, 3),
-                  "prefix_encode_GBps": round((2 * n + words * 4) / (enc_ms * 1e-3) / 1e9, 1),
-                  "note": "lgn_prefix_encode of the step's CODE8 output (reads it twice, writes the stream); "
-                          "not part of the timed step"}
-        log(f"[bench] prefix code of the output: {enc_ms:.4f} ms, {words * 32 / n:.3f} bits per value")
         del pbuf, ptab
+        hist = torch.empty(lgn.LGN_HIST_BINS, dtype=torch.int64, device="cuda")
+        hist_ms = timed(lambda: lgn.lgn_log_histogram(d, out=hist))
+        bmask = (view != 0).to(torch.uint8)              # a ReLU-style byte mask: the non-zero entries
+        masked_ms = timed(lambda: lgn.lgn_stats_masked(d, bmask, out=st, ws=ws))
+        del bmask
+        fmask = d.clone()                                # a second tensor of the same dtype as the mask
+        masked_same_ms = timed(lambda: lgn.lgn_stats_masked(d, fmask, out=st, ws=ws))
+        del fmask
+        gb = lambda b, ms: round(b / (ms * 1e-3) / 1e9, 1)
+        extras = {
+            "prefix_encode": {"ms": round(enc_ms, 4), "bits_per_value": round(words * 32 / n, 3),
+                              "GBps": gb(2 * n + words * 4, enc_ms),
+                              "what": "lgn_prefix_encode of the step's CODE8 output: reads it twice, writes the stream"},
+            "log_histogram": {"ms": round(hist_ms, 4), "GBps": gb(n * in_bytes, hist_ms),
+                              "what": "lgn_log_histogram of the tensor (one read)"},
+            "stats_masked_u8": {"ms": round(masked_ms, 4), "GBps": gb(n * (in_bytes + 1), masked_ms),
+                                "what": "lgn_stats_masked with a byte mask (tensor + 1 B/elem)"},
+            "stats_masked_same_dtype": {"ms": round(masked_same_ms, 4), "GBps": gb(2 * n * in_bytes, masked_same_ms),
+                                        "what": "lgn_stats_masked with a mask tensor of the same dtype (two reads)"},
+            "note": "measured after the timed region; not part of the step"}
+        log(f"[bench] beyond the hot path: prefix code {enc_ms:.4f} ms ({words * 32 / n:.3f} bits per value), "
+            f"histogram {hist_ms:.4f} ms, masked stats {masked_ms:.4f} ms (byte mask) / {masked_same_ms:.4f} ms (same dtype)")
+        # leave the structs as the timed step wrote them
+        one_step()
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline:

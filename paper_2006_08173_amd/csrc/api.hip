@@ -92,6 +92,19 @@ int stream_blocks()
     return cached;
 }
 
+// Workgroups of a resident (grid-stride) launch: eight per CU.
+int resident_blocks()
+{
+    static int cached = 0;
+    if (cached) return cached;
+    int dev = 0, cus = 256, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        cus = v;
+    cached = cus * 8;
+    return cached;
+}
+
 // Workgroups of the statistics pass.  Read-only streaming likes few, long-lived waves: for fp32
 // two workgroups per CU (each wave keeps 8 KiB in flight) measured best, 6.3 TB/s against 5.9 at
 // four; bf16 has twice the arithmetic per byte and wants four.  Fewer workgroups also mean fewer
@@ -386,7 +399,7 @@ int lgn_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, void
     if (!hist || !aligned(hist, 8)) return fail(LGN_ERR_INVALID_ARG, "histogram null or not 8-byte aligned");
     if (n && (!g || !aligned(g, 16))) return fail(LGN_ERR_INVALID_ARG, "input null or not 16-byte aligned");
     if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
-    const hipError_t e = lgn::launch_log_histogram(g, n, dtype, hist, stream_blocks(),
+    const hipError_t e = lgn::launch_log_histogram(g, n, dtype, hist, resident_blocks(),
                                                    static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_log_histogram", e);
 }
