@@ -3,7 +3,7 @@
  * gradients after "Neural gradients are near-lognormal: improved quantized and sparse training"
  * (Chmiel et al., ICLR 2021).
  *
- * The path, per gradient tensor g (contiguous, 1-D view, fp32 or bf16):
+ * The path, per gradient tensor g (contiguous, 1-D view, fp32, bf16 or fp16):
  *
  *   lgn_stats      lognormal parameters: mean and standard deviation of ln|g| over the non-zero
  *                  entries, plus counts and extrema                      (Section 3)
@@ -56,6 +56,7 @@ extern "C" {
 /* element types */
 #define LGN_F32 0
 #define LGN_BF16 1
+#define LGN_F16 2 /* IEEE half precision */
 
 /* rounding of the mantissa */
 #define LGN_ROUND_NEAREST_EVEN 0 /* ties to the even FP-n code          */
@@ -201,7 +202,7 @@ int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, 
  * existing zeros are credited as in Appendix "Algorithm for bi-Modal lognormal pruning", step 2).
  *   st              device, read
  *   target_sparsity in [0, 1)
- *   alpha_dtype     LGN_F32 or LGN_BF16: alpha is rounded to this type (it is compared with,
+ *   alpha_dtype     LGN_F32, LGN_BF16 or LGN_F16: alpha is rounded to this type (it is compared with,
  *                   and stored into, tensors of this type)
  *   out             device, written
  * One single-wave launch: safeguarded Newton iteration on ln(alpha) in fp64.

@@ -46,7 +46,7 @@
 #endif
 
 /* ---- enumerations (oracle's own; values are part of the documented C interface) ---------- */
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
 enum { ORC_ROUND_NEAREST_EVEN = 0, ORC_ROUND_STOCHASTIC = 1 };
 enum { ORC_OUT_VALUE = 0, ORC_OUT_CODE8 = 1, ORC_OUT_PACKED = 2 };
 enum { ORC_SCALE_QUANTILE = 0, ORC_SCALE_MAX = 1, ORC_SCALE_CENTER = 2 };
@@ -110,15 +110,63 @@ static uint16_t float_to_bf16(float f)
     b += 0x7fffu + ((b >> 16) & 1u);
     return (uint16_t)(b >> 16);
 }
+/* IEEE half precision in the value domain: 1 sign, 5 exponent (bias 15), 10 fraction bits;
+ * exponent field 0 holds the subnormals k 2^-24, field 31 infinity and NaN. */
+static float f16_to_float(uint16_t h)
+{
+    const int sign = h >> 15, ex = (h >> 10) & 31, fr = h & 1023;
+    double v;
+    if (ex == 31) v = fr ? (double)NAN : (double)INFINITY;
+    else if (ex == 0) v = ldexp((double)fr, -24);
+    else v = ldexp(1.0 + (double)fr / 1024.0, ex - 15);
+    return (float)(sign ? -v : v);
+}
+/* fp32 -> fp16, round to nearest, ties to even (nearbyint in the default rounding mode);
+ * magnitudes that round to 2^16 or more become infinity. */
+static uint16_t float_to_f16(float f)
+{
+    const uint16_t sign = signbit(f) ? 0x8000u : 0u;
+    const double a = fabs((double)f);
+    if (isnan(f)) return (uint16_t)(sign | 0x7e00u);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e); /* a = m 2^e, m in [0.5, 1): the binade is 2^(e-1) */
+    int E = e - 1;
+    if (E < -14) E = -14;                              /* subnormal range: spacing 2^-24 */
+    const double units = nearbyint(ldexp(a, 10 - E));  /* a in units of the spacing 2^(E-10) */
+    const double r = ldexp(units, E - 10);
+    if (r >= 65536.0) return (uint16_t)(sign | 0x7c00u);
+    if (r < ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)units); /* subnormal or zero */
+    int e2;
+    const double m = frexp(r, &e2); /* r = m 2^e2; rounding may have moved r to the next binade */
+    return (uint16_t)(sign | (uint16_t)((e2 - 1 + 15) << 10) | (uint16_t)nearbyint((2.0 * m - 1.0) * 1024.0));
+}
 static float load_elem(const void *g, uint64_t i, int dtype)
 {
-    return dtype == ORC_F32 ? ((const float *)g)[i] : bf16_to_float(((const uint16_t *)g)[i]);
+    if (dtype == ORC_F32) return ((const float *)g)[i];
+    if (dtype == ORC_BF16) return bf16_to_float(((const uint16_t *)g)[i]);
+    return f16_to_float(((const uint16_t *)g)[i]);
 }
 static void store_elem(void *out, uint64_t i, int dtype, float v)
 {
     if (dtype == ORC_F32) ((float *)out)[i] = v;
-    else ((uint16_t *)out)[i] = float_to_bf16(v);
+    else if (dtype == ORC_BF16) ((uint16_t *)out)[i] = float_to_bf16(v);
+    else ((uint16_t *)out)[i] = float_to_f16(v);
 }
+/* alpha rounded to the element type, saturating at the largest finite value of that type */
+static float round_alpha(float af, int alpha_dtype)
+{
+    if (alpha_dtype == ORC_BF16) {
+        af = bf16_to_float(float_to_bf16(af));
+        if (!isfinite(af)) af = bf16_to_float(0x7f7f);
+    } else if (alpha_dtype == ORC_F16) {
+        af = f16_to_float(float_to_f16(af));
+        if (!isfinite(af)) af = 65504.0f;
+    }
+    return af;
+}
+float orc_f16_to_float(uint16_t h) { return f16_to_float(h); }
+uint16_t orc_float_to_f16(float f) { return float_to_f16(f); }
 
 /* ==========================================================================================
  * Step 1.  Lognormal parameters (Section "Neural gradients distribution": the fit is made on
@@ -288,10 +336,7 @@ void orc_threshold(const orc_stats_t *st, double target_sparsity, int alpha_dtyp
     }
     double alpha = exp(v);
     float af = alpha >= (double)FLT_MAX ? FLT_MAX : (float)alpha;
-    if (alpha_dtype == ORC_BF16) {
-        af = bf16_to_float(float_to_bf16(af));
-        if (!isfinite(af)) af = bf16_to_float(0x7f7f);
-    }
+    af = round_alpha(af, alpha_dtype);
     out->alpha = af;
     if (af > 0.0f)
         out->s_pred = sigma < 1e-12 ? fmax(0.0, 1.0 - exp(mu) / (double)af)
@@ -850,7 +895,7 @@ void orc_sparsity_allocate(const orc_stats_t *stats, const uint64_t *hists, int 
                 L = orc_log_alpha_for_cosine(st->sigma, c, min_cosine[i]);
                 double alpha = exp(st->mu + L);
                 float af = alpha >= (double)FLT_MAX ? FLT_MAX : (float)alpha;
-                if (alpha_dtype == ORC_BF16) af = bf16_to_float(float_to_bf16(af));
+                af = round_alpha(af, alpha_dtype);
                 p_out[i].alpha = af;
                 p_out[i].s_pred = af > 0.0f ? orc_sparsity_of_alpha(st->mu, st->sigma, (double)af) : 0.0;
                 p_out[i].s_eff = p_out[i].s_pred;

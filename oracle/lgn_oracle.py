@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lgn_oracle.c")
 _LIB = os.path.join(_HERE, "liblgn_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 OUT_VALUE, OUT_CODE8, OUT_PACKED = 0, 1, 2
 SCALE_QUANTILE, SCALE_MAX, SCALE_CENTER = 0, 1, 2
@@ -99,6 +99,10 @@ def lib():
         L.orc_truncation_k.argtypes = [vp, dbl, dbl, dbl]
         L.orc_truncation_k.restype = dbl
         L.orc_sparsity_allocate.argtypes = [vp, vp, i32, dbl, i32, vp, dbl, dbl, i32, vp, vp]
+        L.orc_f16_to_float.argtypes = [C.c_uint16]
+        L.orc_f16_to_float.restype = f32
+        L.orc_float_to_f16.argtypes = [f32]
+        L.orc_float_to_f16.restype = C.c_uint16
         L.orc_threshold_floor.argtypes = [i32, i32, vp, i32, vp]
         L.orc_prefix_chunks.argtypes = [u64]
         L.orc_prefix_chunks.restype = u64
@@ -124,7 +128,9 @@ def _dtype_of(g: np.ndarray) -> int:
         return F32
     if g.dtype == np.uint16:
         return BF16
-    raise TypeError("oracle tensors are float32 (fp32) or uint16 bit patterns (bf16)")
+    if g.dtype == np.float16:
+        return F16
+    raise TypeError("oracle tensors are float32 (fp32), uint16 bit patterns (bf16) or float16 (fp16)")
 
 
 def _ptr(a: np.ndarray):
@@ -259,7 +265,7 @@ def decode(code: int, e: int, m: int, s: int) -> float:
 
 def dequantize(codes: np.ndarray, e: int, m: int, s: int, dtype: int = F32) -> np.ndarray:
     codes = np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1)
-    out = np.empty(codes.size, dtype=np.float32 if dtype == F32 else np.uint16)
+    out = np.empty(codes.size, dtype={F32: np.float32, BF16: np.uint16, F16: np.float16}[dtype])
     lib().orc_dequantize(_ptr(codes), codes.size, int(e), int(m), int(s), int(dtype), _ptr(out))
     return out
 
@@ -290,14 +296,16 @@ def prefix_width(a: np.ndarray, n_bits: int = None) -> int:
     """Bits of an element's pattern: 32 (fp32), 16 (bf16 bit patterns) or N (FP-n codes)."""
     if a.dtype == np.float32:
         return 32
-    if a.dtype == np.uint16:
+    if a.dtype in (np.uint16, np.float16):
         return 16
     assert a.dtype == np.uint8 and n_bits is not None
     return int(n_bits)
 
 
-def prefix_special_of_alpha(alpha: float, width: int) -> int:
-    """Magnitude pattern of alpha as an fp32 (width 32) or bf16 (width 16) value."""
+def prefix_special_of_alpha(alpha: float, width: int, fp16: bool = False) -> int:
+    """Magnitude pattern of alpha as an fp32 (width 32), bf16 or fp16 (width 16) value."""
+    if fp16:
+        return int(np.float16(alpha).view(np.uint16)) & 0x7FFF
     b = int(np.float32(alpha).view(np.uint32)) & 0x7FFFFFFF
     return b if width == 32 else b >> 16
 
@@ -384,3 +392,11 @@ def threshold_floor(e_bits: int, scale_exp: int, p_in: PruneParams = None, alpha
     lib().orc_threshold_floor(int(e_bits), int(scale_exp), C.byref(p_in) if p_in is not None else None,
                               int(alpha_dtype), C.byref(out))
     return out
+
+
+def f16_to_float(h: int) -> float:
+    return float(lib().orc_f16_to_float(int(h)))
+
+
+def float_to_f16(x) -> int:
+    return int(lib().orc_float_to_f16(np.float32(x)))

@@ -17,7 +17,7 @@ from . import build as _build
 # ---- constants of include/lgn.h ---------------------------------------------------------------
 LGN_OK = 0
 LGN_ERR_INVALID_ARG, LGN_ERR_UNSUPPORTED, LGN_ERR_WORKSPACE, LGN_ERR_DEVICE = -1, -2, -3, -4
-LGN_F32, LGN_BF16 = 0, 1
+LGN_F32, LGN_BF16, LGN_F16 = 0, 1, 2
 LGN_ROUND_NEAREST_EVEN, LGN_ROUND_STOCHASTIC = 0, 1
 LGN_OUT_VALUE, LGN_OUT_CODE8, LGN_OUT_PACKED = 0, 1, 2
 LGN_SCALE_QUANTILE, LGN_SCALE_MAX, LGN_SCALE_CENTER = 0, 1, 2
@@ -134,6 +134,8 @@ def _dtype_code(t: torch.Tensor, dtype=None) -> int:
         return LGN_F32
     if t.dtype in (torch.bfloat16, torch.int16, torch.uint16):
         return LGN_BF16  # 16-bit integer tensors are taken as bf16 bit patterns
+    if t.dtype == torch.float16:
+        return LGN_F16
     raise TypeError(f"unsupported tensor dtype {t.dtype}")
 
 
@@ -324,8 +326,8 @@ def lgn_prune_quantize_fused(g: torch.Tensor, p: torch.Tensor, f: torch.Tensor,
 def lgn_dequantize(codes: torch.Tensor, n: int, in_kind: int, f: torch.Tensor,
                    dtype: int = LGN_F32, out: torch.Tensor = None) -> torch.Tensor:
     if out is None:
-        out = torch.empty(int(n), dtype=torch.float32 if dtype == LGN_F32 else torch.bfloat16,
-                          device=codes.device)
+        out = torch.empty(int(n), dtype={LGN_F32: torch.float32, LGN_BF16: torch.bfloat16,
+                                         LGN_F16: torch.float16}[dtype], device=codes.device)
     _check(load().lgn_dequantize(codes.data_ptr(), int(n), int(in_kind), f.data_ptr(), int(dtype),
                                  out.data_ptr(), _stream()))
     return out
@@ -363,7 +365,8 @@ def lgn_prefix_decode(stream_buf: torch.Tensor, table: torch.Tensor, n: int, in_
                       p: torch.Tensor = None, f: torch.Tensor = None, dtype: int = LGN_F32,
                       out: torch.Tensor = None) -> torch.Tensor:
     if out is None:
-        tdt = torch.uint8 if in_kind == LGN_OUT_CODE8 else (torch.float32 if dtype == LGN_F32 else torch.bfloat16)
+        tdt = torch.uint8 if in_kind == LGN_OUT_CODE8 else {LGN_F32: torch.float32, LGN_BF16: torch.bfloat16,
+                                                            LGN_F16: torch.float16}[dtype]
         out = torch.empty(int(n), dtype=tdt, device=stream_buf.device)
     _check(load().lgn_prefix_decode(stream_buf.data_ptr(), table.data_ptr(), int(n), int(in_kind),
                                     int(dtype), p.data_ptr() if p is not None else None,

@@ -59,8 +59,10 @@ __global__ __launch_bounds__(kBlock) void hist_kernel(const void *__restrict__ g
                 if (DTYPE == LGN_F32) {
                     hist_count(lds, w[j]);
                 } else {
-                    hist_count(lds, w[j] << 16);
-                    hist_count(lds, w[j] & 0xffff0000u);
+                    uint32_t lo, hi;
+                    widen_pair<DTYPE>(w[j], lo, hi);
+                    hist_count(lds, lo);
+                    hist_count(lds, hi);
                 }
             }
         }
@@ -97,7 +99,8 @@ hipError_t launch_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *
     if (blocks < 1) blocks = 1;
     if (blocks > (uint64_t)max_blocks) blocks = max_blocks;
     if (dtype == LGN_F32) hist_kernel<LGN_F32><<<(int)blocks, kBlock, 0, stream>>>(g, n, h);
-    else hist_kernel<LGN_BF16><<<(int)blocks, kBlock, 0, stream>>>(g, n, h);
+    else if (dtype == LGN_BF16) hist_kernel<LGN_BF16><<<(int)blocks, kBlock, 0, stream>>>(g, n, h);
+    else hist_kernel<LGN_F16><<<(int)blocks, kBlock, 0, stream>>>(g, n, h);
     return hipGetLastError();
 }
 
@@ -186,7 +189,7 @@ __device__ void allocate_layer(const AllocArgs &a, int i, double target, uint32_
             L = log_alpha_for_cosine(sigma, c, a.min_cosine[i]);
             const double av = exp(mu + L);
             alpha = av >= 3.4028234663852886e38 ? 3.4028234663852886e38f : (float)av;
-            if (a.alpha_dtype == LGN_BF16) alpha = round_to_bf16(alpha);
+            alpha = round_alpha(alpha, a.alpha_dtype);
             double B;
             s_pred = 0.0;
             if (alpha > 0.0f) {

@@ -35,12 +35,12 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
                          const StreamArgs &args, int max_blocks, hipStream_t stream);
 hipError_t launch_dequant(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f,
                           int dtype, void *out, hipStream_t stream);
-hipError_t launch_prefix_encode(int width_class, const void *in, uint64_t n, const lgn_prune_params_t *p,
-                                const lgn_fp_params_t *f, void *out, uint64_t capacity_words,
-                                uint64_t *table, hipStream_t stream);
-hipError_t launch_prefix_decode(int width_class, const void *in, const uint64_t *table, uint64_t n,
+hipError_t launch_prefix_encode(int width_class, int dtype, const void *in, uint64_t n,
                                 const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out,
-                                hipStream_t stream);
+                                uint64_t capacity_words, uint64_t *table, hipStream_t stream);
+hipError_t launch_prefix_decode(int width_class, int dtype, const void *in, const uint64_t *table,
+                                uint64_t n, const lgn_prune_params_t *p, const lgn_fp_params_t *f,
+                                void *out, hipStream_t stream);
 hipError_t launch_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, int max_blocks,
                                 hipStream_t stream);
 hipError_t launch_sparsity_allocate(const lgn_stats_t *stats, const uint64_t *hists, int n_layers,
@@ -69,7 +69,7 @@ int device_fail(const char *what, hipError_t e)
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-bool dtype_ok(int d) { return d == LGN_F32 || d == LGN_BF16; }
+bool dtype_ok(int d) { return d == LGN_F32 || d == LGN_BF16 || d == LGN_F16; }
 
 // Upper limit of the workgroups of a streaming launch (the launch itself sizes the grid by the
 // work per wave).
@@ -374,7 +374,7 @@ int lgn_prefix_encode(const void *in, uint64_t n, int in_kind, int dtype, const 
     if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
     if (n && (!in || !aligned(in, 16))) return fail(LGN_ERR_INVALID_ARG, "input null or not 16-byte aligned");
     if (out_capacity && (!out || !aligned(out, 4))) return fail(LGN_ERR_INVALID_ARG, "stream buffer null or not 4-byte aligned");
-    const hipError_t e = lgn::launch_prefix_encode(wc, in, n, p, f, out, out_capacity / 4, table,
+    const hipError_t e = lgn::launch_prefix_encode(wc, dtype, in, n, p, f, out, out_capacity / 4, table,
                                                    static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_prefix_encode", e);
 }
@@ -388,7 +388,7 @@ int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_
     if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
     if (n && (!in || !out || !aligned(in, 4) || !aligned(out, 16)))
         return fail(LGN_ERR_INVALID_ARG, "null or misaligned buffer (stream 4, output 16 bytes)");
-    const hipError_t e = lgn::launch_prefix_decode(wc, in, table, n, p, f, out,
+    const hipError_t e = lgn::launch_prefix_decode(wc, dtype, in, table, n, p, f, out,
                                                    static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_prefix_decode", e);
 }

@@ -109,8 +109,8 @@ __device__ __forceinline__ void philox_finish(uint32_t hi0, uint32_t lo0, uint32
 
 // ---------------------------------------------------------------------------------------------
 // Element access.  A "quad" is four consecutive elements: 16 bytes of fp32 or 8 bytes of bf16.
-// Elements are handled as fp32 bit patterns (bf16 widens exactly by a 16-bit shift), so nothing
-// below depends on the floating-point mode of the device.
+// Elements are handled as fp32 bit patterns (bf16 widens exactly by a 16-bit shift, fp16 by the
+// exact hardware conversion).
 // ---------------------------------------------------------------------------------------------
 // Streaming accesses: every byte is touched once per pass, so loads and stores carry the
 // non-temporal hint (measured on MI355X: +10..15 % bandwidth for the read-16-write-4 pattern at
@@ -124,6 +124,31 @@ __device__ __forceinline__ uint4 load_stream16(const void *p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// fp16 <-> fp32 patterns with the hardware conversions (v_cvt_f32_f16 is exact, subnormals
+// included; v_cvt_f16_f32 rounds to nearest even, overflows to infinity).
+__device__ __forceinline__ uint32_t f16_to_f32_bits(uint32_t h)
+{
+    return __float_as_uint((float)__builtin_bit_cast(_Float16, (unsigned short)h));
+}
+
+__device__ __forceinline__ uint32_t f32_bits_to_f16(uint32_t b)
+{
+    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)__uint_as_float(b));
+}
+
+// The two 16-bit elements of a dword as fp32 patterns (low half first).
+template <int DTYPE>
+__device__ __forceinline__ void widen_pair(uint32_t w, uint32_t &lo, uint32_t &hi)
+{
+    if (DTYPE == LGN_BF16) {
+        lo = w << 16;
+        hi = w & 0xffff0000u;
+    } else {
+        lo = f16_to_f32_bits(w & 0xffffu);
+        hi = f16_to_f32_bits(w >> 16);
+    }
+}
+
 template <int DTYPE>
 __device__ __forceinline__ void load_quad(const void *g, uint64_t quad, uint32_t b[4])
 {
@@ -132,7 +157,8 @@ __device__ __forceinline__ void load_quad(const void *g, uint64_t quad, uint32_t
         b[0] = v.x; b[1] = v.y; b[2] = v.z; b[3] = v.w;
     } else {
         const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(g) + quad);
-        b[0] = v.x << 16; b[1] = v.x & 0xffff0000u; b[2] = v.y << 16; b[3] = v.y & 0xffff0000u;
+        widen_pair<DTYPE>(v.x, b[0], b[1]);
+        widen_pair<DTYPE>(v.y, b[2], b[3]);
     }
 }
 
@@ -140,7 +166,8 @@ template <int DTYPE>
 __device__ __forceinline__ uint32_t load_elem(const void *g, uint64_t i)
 {
     if (DTYPE == LGN_F32) return reinterpret_cast<const uint32_t *>(g)[i];
-    return (uint32_t) reinterpret_cast<const uint16_t *>(g)[i] << 16;
+    const uint32_t h = reinterpret_cast<const uint16_t *>(g)[i];
+    return DTYPE == LGN_BF16 ? h << 16 : f16_to_f32_bits(h);
 }
 
 // fp32 pattern -> bf16 pattern in the upper half, round to nearest even.  Everything the kernels
@@ -157,9 +184,13 @@ __device__ __forceinline__ void store_quad(void *out, uint64_t quad, const uint3
     if (DTYPE == LGN_F32) {
         u32x4_t v = {b[0], b[1], b[2], b[3]};
         __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(out) + quad);
-    } else {
+    } else if (DTYPE == LGN_BF16) {
         u32x2_t v = {(bf16_round_hi(b[0]) >> 16) | bf16_round_hi(b[1]),
                      (bf16_round_hi(b[2]) >> 16) | bf16_round_hi(b[3])};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t *>(out) + quad);
+    } else {
+        u32x2_t v = {f32_bits_to_f16(b[0]) | (f32_bits_to_f16(b[1]) << 16),
+                     f32_bits_to_f16(b[2]) | (f32_bits_to_f16(b[3]) << 16)};
         __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t *>(out) + quad);
     }
 }
@@ -168,7 +199,8 @@ template <int DTYPE>
 __device__ __forceinline__ void store_elem(void *out, uint64_t i, uint32_t b)
 {
     if (DTYPE == LGN_F32) reinterpret_cast<uint32_t *>(out)[i] = b;
-    else reinterpret_cast<uint16_t *>(out)[i] = (uint16_t)(bf16_round_hi(b) >> 16);
+    else if (DTYPE == LGN_BF16) reinterpret_cast<uint16_t *>(out)[i] = (uint16_t)(bf16_round_hi(b) >> 16);
+    else reinterpret_cast<uint16_t *>(out)[i] = (uint16_t)f32_bits_to_f16(b);
 }
 
 }  // namespace lgn

@@ -35,9 +35,11 @@ struct PrefixArgs {
     uint64_t *table;
     const lgn_prune_params_t *p;
     const lgn_fp_params_t *f;
+    int dtype;           // element type of VALUE input (tells bf16 from fp16 among the 16-bit patterns)
 };
 
-// WIDTH_CLASS: 0 = FP-n codes in bytes (W = n_bits of *f), 1 = bf16 patterns, 2 = fp32 patterns.
+// WIDTH_CLASS: 0 = FP-n codes in bytes (W = n_bits of *f), 1 = 16-bit patterns (bf16 or fp16),
+// 2 = fp32 patterns.
 template <int WC>
 struct Elem;
 template <>
@@ -59,7 +61,7 @@ __device__ __forceinline__ void prefix_consts(const PrefixArgs &a, int &width, u
         special = ab;
     } else if (WC == 1) {
         width = 16;
-        special = bf16_round_hi(ab) >> 16;
+        special = a.dtype == LGN_F16 ? (f32_bits_to_f16(ab) & 0x7fffu) : (bf16_round_hi(ab) >> 16);
     } else {
         QuantConst q = {8, 1, 6, 0, 0, 1, 255u};
         if (a.f) load_quant_const(a.f, q);
@@ -387,23 +389,23 @@ static hipError_t encode_launches(const PrefixArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_prefix_encode(int width_class, const void *in, uint64_t n, const lgn_prune_params_t *p,
-                                const lgn_fp_params_t *f, void *out, uint64_t capacity_words,
-                                uint64_t *table, hipStream_t stream)
+hipError_t launch_prefix_encode(int width_class, int dtype, const void *in, uint64_t n,
+                                const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out,
+                                uint64_t capacity_words, uint64_t *table, hipStream_t stream)
 {
-    const PrefixArgs a = {in, out, n, capacity_words, table, p, f};
+    const PrefixArgs a = {in, out, n, capacity_words, table, p, f, dtype};
     if (width_class == 2) return encode_launches<2>(a, stream);
     if (width_class == 1) return encode_launches<1>(a, stream);
     return encode_launches<0>(a, stream);
 }
 
-hipError_t launch_prefix_decode(int width_class, const void *in, const uint64_t *table, uint64_t n,
-                                const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out,
-                                hipStream_t stream)
+hipError_t launch_prefix_decode(int width_class, int dtype, const void *in, const uint64_t *table,
+                                uint64_t n, const lgn_prune_params_t *p, const lgn_fp_params_t *f,
+                                void *out, hipStream_t stream)
 {
     const uint64_t nchunks = (n + kChunk - 1) / kChunk;
     if (!nchunks) return hipSuccess;
-    const PrefixArgs a = {in, out, n, 0, const_cast<uint64_t *>(table), p, f};
+    const PrefixArgs a = {in, out, n, 0, const_cast<uint64_t *>(table), p, f, dtype};
     const int blocks = (int)((nchunks + kBlock - 1) / kBlock);
     if (width_class == 2) prefix_decode_kernel<2><<<blocks, kBlock, 0, stream>>>(a);
     else if (width_class == 1) prefix_decode_kernel<1><<<blocks, kBlock, 0, stream>>>(a);

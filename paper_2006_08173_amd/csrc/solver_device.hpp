@@ -83,6 +83,23 @@ __device__ __forceinline__ float round_to_bf16(float f)
     return __uint_as_float(b);
 }
 
+// fp32 -> fp16 -> fp32, round to nearest even, saturating at the largest finite fp16 value.
+__device__ __forceinline__ float round_to_f16(float f)
+{
+    const float r = (float)(_Float16)f;
+    if (r > 65504.0f) return 65504.0f;
+    if (r < -65504.0f) return -65504.0f;
+    return r;
+}
+
+// alpha rounded to the element type of the tensor it will be compared with and stored into
+__device__ __forceinline__ float round_alpha(float alpha, int alpha_dtype)
+{
+    if (alpha_dtype == LGN_BF16) return round_to_bf16(alpha);
+    if (alpha_dtype == LGN_F16) return round_to_f16(alpha);
+    return alpha;
+}
+
 // Runs in one lane (the caller picks it); `st` may point to LDS or global memory.
 __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double target, int alpha_dtype,
                                                lgn_prune_params_t *out)
@@ -151,7 +168,7 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
     }
     const double alpha = exp(v);
     float af = alpha >= 3.4028234663852886e38 ? 3.4028234663852886e38f : (float)alpha;
-    if (alpha_dtype == LGN_BF16) af = round_to_bf16(af);
+    af = round_alpha(af, alpha_dtype);
     r.alpha = af;
     if (af > 0.0f) {
         if (point_mass) {

@@ -135,8 +135,13 @@ __device__ __forceinline__ uint32_t accumulate_vec(uint4 v, uint32_t pivot_bits,
                                                    LaneAcc &t)
 {
     if (DTYPE == LGN_F32) return accumulate_quad(v.x, v.y, v.z, v.w, pivot_bits, pivot, t);
-    return accumulate_quad(v.x << 16, v.x & 0xffff0000u, v.y << 16, v.y & 0xffff0000u, pivot_bits, pivot, t) +
-           accumulate_quad(v.z << 16, v.z & 0xffff0000u, v.w << 16, v.w & 0xffff0000u, pivot_bits, pivot, t);
+    uint32_t e[8];
+    widen_pair<DTYPE>(v.x, e[0], e[1]);
+    widen_pair<DTYPE>(v.y, e[2], e[3]);
+    widen_pair<DTYPE>(v.z, e[4], e[5]);
+    widen_pair<DTYPE>(v.w, e[6], e[7]);
+    return accumulate_quad(e[0], e[1], e[2], e[3], pivot_bits, pivot, t) +
+           accumulate_quad(e[4], e[5], e[6], e[7], pivot_bits, pivot, t);
 }
 
 template <typename T>
@@ -215,6 +220,10 @@ struct MaskVec<LGN_F32, 2> {
 };
 template <>
 struct MaskVec<LGN_BF16, 2> {
+    uint2 v;  // eight bytes
+};
+template <>
+struct MaskVec<LGN_F16, 2> {
     uint2 v;  // eight bytes
 };
 
@@ -322,8 +331,10 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
         uint32_t cand = 0u;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = (DTYPE == LGN_F32 ? w[i] : w[i] << 16) & 0x7fffffffu;
-            const uint32_t hi = DTYPE == LGN_F32 ? 0u : w[i] & 0x7fff0000u;
+            uint32_t lo = w[i], hi = 0u;
+            if (DTYPE != LGN_F32) widen_pair<DTYPE>(w[i], lo, hi);
+            lo &= 0x7fffffffu;
+            hi &= 0x7fffffffu;
             if (lo < 0x7f800000u) cand = max(cand, lo);
             if (hi < 0x7f800000u) cand = max(cand, hi);
         }
@@ -395,8 +406,10 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
                 if (DTYPE == LGN_F32) {
                     accumulate_careful(w[i], pivot, t);
                 } else {
-                    accumulate_careful(w[i] << 16, pivot, t);
-                    accumulate_careful(w[i] & 0xffff0000u, pivot, t);
+                    uint32_t lo, hi;
+                    widen_pair<DTYPE>(w[i], lo, hi);
+                    accumulate_careful(lo, pivot, t);
+                    accumulate_careful(hi, pivot, t);
                 }
             }
         }
@@ -588,10 +601,14 @@ static void dispatch_dtype_mask(int dtype, int mask_kind, F &&f)
         if (mask_kind == LGN_MASK_SAME_DTYPE) f.template operator()<LGN_F32, 1>();
         else if (mask_kind == LGN_MASK_U8) f.template operator()<LGN_F32, 2>();
         else f.template operator()<LGN_F32, 0>();
-    } else {
+    } else if (dtype == LGN_BF16) {
         if (mask_kind == LGN_MASK_SAME_DTYPE) f.template operator()<LGN_BF16, 1>();
         else if (mask_kind == LGN_MASK_U8) f.template operator()<LGN_BF16, 2>();
         else f.template operator()<LGN_BF16, 0>();
+    } else {
+        if (mask_kind == LGN_MASK_SAME_DTYPE) f.template operator()<LGN_F16, 1>();
+        else if (mask_kind == LGN_MASK_U8) f.template operator()<LGN_F16, 2>();
+        else f.template operator()<LGN_F16, 0>();
     }
 }
 

@@ -521,20 +521,22 @@ static StreamKernel pick_round_out(int rounding, int out_kind)
     return stream_kernel<DTYPE, PRUNE, true, LGN_ROUND_NEAREST_EVEN, LGN_OUT_PACKED>;
 }
 
+template <int DTYPE>
+static StreamKernel pick_kernel(bool prune, bool quant, int rounding, int out_kind)
+{
+    return prune ? (quant ? pick_round_out<DTYPE, true, true>(rounding, out_kind)
+                          : pick_round_out<DTYPE, true, false>(rounding, out_kind))
+                 : pick_round_out<DTYPE, false, true>(rounding, out_kind);
+}
+
 hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int out_kind,
                          const StreamArgs &args, int max_blocks, hipStream_t stream)
 {
     if (args.n == 0) return hipSuccess;
     StreamKernel k;
-    if (dtype == LGN_F32) {
-        k = prune ? (quant ? pick_round_out<LGN_F32, true, true>(rounding, out_kind)
-                           : pick_round_out<LGN_F32, true, false>(rounding, out_kind))
-                  : pick_round_out<LGN_F32, false, true>(rounding, out_kind);
-    } else {
-        k = prune ? (quant ? pick_round_out<LGN_BF16, true, true>(rounding, out_kind)
-                           : pick_round_out<LGN_BF16, true, false>(rounding, out_kind))
-                  : pick_round_out<LGN_BF16, false, true>(rounding, out_kind);
-    }
+    if (dtype == LGN_F32) k = pick_kernel<LGN_F32>(prune, quant, rounding, out_kind);
+    else if (dtype == LGN_BF16) k = pick_kernel<LGN_BF16>(prune, quant, rounding, out_kind);
+    else k = pick_kernel<LGN_F16>(prune, quant, rounding, out_kind);
     const uint64_t npairs = ((args.n + 255) / 256 + 1) / 2;  // a wave step covers two tiles
     // A wave gets about `per_wave` pairs.  Far more workgroups than the device holds at once
     // (measured best at four to eight pairs per wave for every variant, i.e. ~65 workgroups per CU
@@ -567,9 +569,12 @@ hipError_t launch_dequant(const void *codes, uint64_t n, int in_kind, const lgn_
     if (dtype == LGN_F32) {
         if (in_kind == LGN_OUT_CODE8) dequant_kernel<LGN_F32, LGN_OUT_CODE8><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
         else dequant_kernel<LGN_F32, LGN_OUT_PACKED><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
-    } else {
+    } else if (dtype == LGN_BF16) {
         if (in_kind == LGN_OUT_CODE8) dequant_kernel<LGN_BF16, LGN_OUT_CODE8><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
         else dequant_kernel<LGN_BF16, LGN_OUT_PACKED><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
+    } else {
+        if (in_kind == LGN_OUT_CODE8) dequant_kernel<LGN_F16, LGN_OUT_CODE8><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
+        else dequant_kernel<LGN_F16, LGN_OUT_PACKED><<<blocks, kBlock, 0, stream>>>(c, n, f, out);
     }
     return hipGetLastError();
 }

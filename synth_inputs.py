@@ -34,6 +34,7 @@ CHUNK = 1 << 20
 
 F32 = "f32"
 BF16 = "bf16"
+F16 = "f16"
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -75,6 +76,8 @@ def _chunk(c, lo, hi, seed, mu, sigma, zero_frac, dtype, outlier_frac, outlier_r
     g32 = g[lo:hi].astype(np.float32)
     if dtype == BF16:
         return f32_to_bf16_bits(g32)
+    if dtype == F16:
+        return g32.astype(np.float16)
     return g32
 
 
@@ -83,11 +86,11 @@ def lognormal_tensor(n, *, seed, mu, sigma, zero_frac=0.0, dtype=F32, start=0,
                      tiny_frac=0.0, tiny_range=(2.0 ** -133, 2.0 ** -120), workers=None):
     """Elements [start, start+n) of the seeded synthetic tensor (flat, contiguous).
 
-    Returns float32 for dtype 'f32' and uint16 bit patterns for dtype 'bf16'.
+    Returns float32 for dtype 'f32', uint16 bit patterns for dtype 'bf16', float16 for 'f16'.
     """
     n = int(n)
     start = int(start)
-    out = np.empty(n, dtype=np.float32 if dtype == F32 else np.uint16)
+    out = np.empty(n, dtype={F32: np.float32, BF16: np.uint16, F16: np.float16}[dtype])
     if n == 0:
         return out
     first, last = start // CHUNK, (start + n - 1) // CHUNK
