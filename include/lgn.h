@@ -14,10 +14,16 @@
  *   lgn_prune      stochastic pruning T_{alpha,eps}                      (Section 5, first equation)
  *   lgn_fp_quantize  FP(1,e,m) quantization with scale 2^s               (Section 4.1, Alg. 1)
  *   lgn_prune_quantize_fused   the two operators in one pass
+ *   lgn_stats_solve            the first three steps in one launch
+ *
+ * Beyond that path: the prefix code of a pruned tensor (lgn_prefix_encode / lgn_prefix_decode,
+ * appendix "Encoding"), statistics of one mode of a bi-modal gradient (lgn_stats_masked), the
+ * stochastic-underflow threshold (lgn_threshold_floor) and heterogeneous per-layer sparsity
+ * (lgn_log_histogram, lgn_sparsity_allocate).
  *
  * General rules
- *   - Every pointer named g, in, out, codes, ws, st, p, f is a DEVICE pointer owned by the
- *     caller.  The library never allocates, frees or keeps device memory.
+ *   - Every pointer argument is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or keeps device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
  *     enqueues kernels on that stream and returns; nothing synchronises with the host, and the
  *     parameter structs are read and written on the device, so a whole chain

@@ -4,15 +4,16 @@
 // One kernel template covers prune-only, quantize-only and the fused pass.  A wave owns tiles of
 // 256 consecutive elements; lane l owns elements 4l..4l+3 of the tile, i.e. exactly one Philox
 // block per purpose, one 16-byte load (fp32) and one 16-byte / 4-byte store.  Everything is
-// integer work on fp32 bit patterns (bf16 widens by a shift), except the one single-precision
-// product alpha * u that the pruning rule is defined with.
+// integer work on fp32 bit patterns (bf16 widens by a shift, fp16 by the exact conversion), except
+// the one single-precision product alpha * u that the pruning rule is defined with.
 //
 // Two code paths per tile.  The fast path covers full tiles whose global quad indices share the
 // upper counter word, with elem_offset a multiple of four, a normal-range alpha and a scale that
 // flushes fp32 subnormals (the case for any sane gradient scale): there the first Philox rounds
 // run partly on the scalar unit, the three-way xors are single v_bitop3 instructions, and the
-// per-element work is about sixteen integer instructions.  Everything else (ragged tail tile,
-// unaligned offsets, exotic scales) takes the general path; both give identical bits.
+// per-element work is ten instructions (stochastic rounding, re-biasing and the sign are one
+// 64-bit multiply-add).  Everything else (ragged tail tile, unaligned offsets, exotic scales)
+// takes the general path; both give identical bits.
 //
 // PACKED output: the four N-bit codes of a lane form a 4N-bit chunk; the 64 chunks of a tile are
 // one contiguous run of 8N dwords.  Lane k < 8N assembles dword k from the (at most five) chunks
