@@ -8,9 +8,10 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 # LGN_LIB points the binding at another build of the library (A/B timing of kernel variants)
 LIB = os.environ.get("LGN_LIB") or os.path.join(PKG, "liblgn.so")
-SOURCES = ["api.hip", "stats.hip", "solver.hip", "stream.hip", "prefix.hip", "alloc.hip"]
+SOURCES = ["api.hip", "stats.hip", "solver.hip", "stream.hip", "stream_f32.hip", "stream_bf16.hip",
+           "stream_f16.hip", "prefix.hip", "alloc.hip"]
 HEADERS = [os.path.join(CSRC, "lgn_device.hpp"), os.path.join(CSRC, "solver_device.hpp"),
-           os.path.join(CSRC, "fpcode_device.hpp"),
+           os.path.join(CSRC, "fpcode_device.hpp"), os.path.join(CSRC, "stream_kernels.hpp"),
            os.path.join(os.path.dirname(PKG), "include", "lgn.h")]
 
 
@@ -29,15 +30,32 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+         "-fno-gpu-flush-denormals-to-zero", "-ffp-contract=off",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-function"]
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every HIP source into one shared library.  Cross-compiles without a GPU."""
+    """Compile every HIP source for gfx950 (one object each, in parallel) and link them into one
+    shared library.  Cross-compiles without a GPU."""
     if not force and not is_stale():
         return LIB
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-fno-gpu-flush-denormals-to-zero", "-ffp-contract=off",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-function",
-           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = os.path.join(PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+
+    def compile_one(src):
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        cmd = [hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 8)) as ex:
+        objs = list(ex.map(compile_one, SOURCES))
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

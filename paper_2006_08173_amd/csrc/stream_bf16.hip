@@ -1,0 +1,11 @@
+// The streaming kernels for bf16 tensors (see stream_kernels.hpp).
+#include "stream_kernels.hpp"
+
+namespace lgn {
+
+StreamKernel pick_stream_kernel_bf16(bool prune, bool quant, int rounding, int out_kind)
+{
+    return pick_kernel<LGN_BF16>(prune, quant, rounding, out_kind);
+}
+
+}  // namespace lgn
