@@ -511,3 +511,46 @@ def test_stochastic_underflow_on_device(lgn):
     assert abs(float(y[small].sum() - g[small].astype(np.float64).sum())) < 6 * math.sqrt(var)
     flushed = lgn.lgn_fp_quantize(d, f, O.ROUND_STOCHASTIC, 21, 0, out_kind=O.OUT_CODE8)
     assert np.all(to_host(flushed)[small] == 0)           # without the floor they are lost
+
+
+def test_path_replays_from_a_hip_graph(lgn):
+    """The two-launch path holds no allocation, memset or host synchronisation, so it can be captured
+    in a HIP graph; every replay, on fresh input data, must give the bits of the eager calls."""
+    n = 1_500_007
+    tensors = [mixed_tensor(n, 800 + i, SI.F32, mu=-11.0 - i, sigma=1.6 + 0.3 * i) for i in range(3)]
+    d = torch.empty(n, dtype=torch.float32, device="cuda")
+    st = torch.empty(72, dtype=torch.uint8, device="cuda")
+    p = torch.empty(24, dtype=torch.uint8, device="cuda")
+    f = torch.empty(32, dtype=torch.uint8, device="cuda")
+    out = torch.empty(n, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(lgn.lgn_workspace_bytes(0, lgn.LGN_F32), dtype=torch.uint8, device="cuda")
+    lgn.lgn_workspace_init(ws)
+
+    def chain():
+        lgn.lgn_stats_solve(d, 0.85, lgn.LGN_F32, 6, st=st, p=p, f=f, ws=ws)
+        lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 3, 0, out=out, out_kind=O.OUT_CODE8)
+
+    eager = []
+    for t in tensors:
+        d.copy_(torch.from_numpy(t))
+        chain()
+        torch.cuda.synchronize()
+        eager.append((bytes(lgn.read_stats(st)), bytes(lgn.read_prune_params(p)), out.clone()))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()                                            # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    for rep in range(2):
+        for t, want in zip(tensors, eager):
+            d.copy_(torch.from_numpy(t))                   # eager work between the replays
+            out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert bytes(lgn.read_stats(st)) == want[0], rep
+            assert bytes(lgn.read_prune_params(p)) == want[1], rep
+            assert torch.equal(out, want[2]), rep
