@@ -16,6 +16,9 @@
 // Inf, NaN or subnormal is re-done by a careful path (wave-uniform branch) that normalises
 // subnormals with integer operations.  Zeros contribute a zero deviation and are counted out
 // with a ballot / popcount on the scalar unit.
+#include <cstdlib>
+#include <type_traits>
+
 #include "lgn_device.hpp"
 #include "solver_device.hpp"
 
@@ -292,18 +295,21 @@ struct Row {
     MaskVec<DTYPE, MASK> m;
 };
 
-template <int DTYPE, int MASK>
+// KEEP: the vector of g is loaded without the streaming hint, so that it stays in the memory-side
+// cache for the pass that reads the tensor next.
+template <int DTYPE, int MASK, bool KEEP = false>
 __device__ __forceinline__ Row<DTYPE, MASK> load_row(const uint4 *gv, const void *mask, uint64_t vec)
 {
     Row<DTYPE, MASK> r;
-    r.g = load_stream16(gv + vec);
+    if (KEEP) r.g = gv[vec];
+    else r.g = load_stream16(gv + vec);
     r.m = load_mask_vec<DTYPE, MASK>(mask, vec);
     return r;
 }
 
 template <int DTYPE, bool WRITE_THROUGH, int MASK>
 __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const void *__restrict__ mask,
-                                            uint64_t n, Partial *partials)
+                                            uint64_t n, uint64_t keep_vecs, Partial *partials)
 {
     constexpr int EPV = DTYPE == LGN_F32 ? 4 : 8;  // elements per 16-byte vector
     constexpr int kWavesPerBlock = kBlock / kWave;
@@ -351,35 +357,43 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
     // per wave): strides of a power-of-two number of rows between the loads of one wave alias in
     // the memory channels and cost ~20 % of the read bandwidth.  The next batch is requested
     // before the current one is reduced, so the arithmetic overlaps the memory latency.
+    //
+    // The last `keep_vecs` vectors of the tensor are loaded as ordinary (cache-allocating) reads and
+    // everything before them as streaming reads: what was read last is then still in the
+    // memory-side cache when the next pass over the same tensor arrives, and the streaming part
+    // does not push it out.  A wave meets its batches in increasing order, so it runs the loop
+    // once per flavour.
     const uint64_t nbatches = nrows / 4;
-    if (wave < nbatches) {
+    const uint64_t first_kept = keep_vecs >= nvec ? 0 : (nvec - keep_vecs + 4 * kWave - 1) / (4 * kWave);
+    auto walk = [&](auto keep_tag, uint64_t cur, const uint64_t limit) -> uint64_t {
+        constexpr bool KEEP = decltype(keep_tag)::value;
+        if (!(cur < limit)) return cur;
         // Two register sets used alternately.  Inside the loop every load is unconditional, so
         // the compiler waits for exactly the older loads while the younger ones stay in
         // flight; the last batch of the wave is reduced after the loop.
         R a0, a1, a2, a3, b0, b1, b2, b3;
-        uint64_t cur = wave;  // batch held in the a-set
         {
-            const uint64_t v = cur * (4 * kWave) + lane;
-            a0 = load_row<DTYPE, MASK>(gv, mask, v); a1 = load_row<DTYPE, MASK>(gv, mask, v + kWave);
-            a2 = load_row<DTYPE, MASK>(gv, mask, v + 2 * kWave); a3 = load_row<DTYPE, MASK>(gv, mask, v + 3 * kWave);
+            const uint64_t v = cur * (4 * kWave) + lane;  // batch held in the a-set
+            a0 = load_row<DTYPE, MASK, KEEP>(gv, mask, v); a1 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + kWave);
+            a2 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + 2 * kWave); a3 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + 3 * kWave);
         }
         bool in_a = true;  // which set holds the batch that is still to be reduced
-        while (cur + nwaves < nbatches) {
+        while (cur + nwaves < limit) {
             {
                 const uint64_t v = (cur + nwaves) * (4 * kWave) + lane;
-                b0 = load_row<DTYPE, MASK>(gv, mask, v); b1 = load_row<DTYPE, MASK>(gv, mask, v + kWave);
-                b2 = load_row<DTYPE, MASK>(gv, mask, v + 2 * kWave); b3 = load_row<DTYPE, MASK>(gv, mask, v + 3 * kWave);
+                b0 = load_row<DTYPE, MASK, KEEP>(gv, mask, v); b1 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + kWave);
+                b2 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + 2 * kWave); b3 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + 3 * kWave);
             }
             reduce(a0); reduce(a1); reduce(a2); reduce(a3);
             cur += nwaves;
-            if (!(cur + nwaves < nbatches)) {
+            if (!(cur + nwaves < limit)) {
                 in_a = false;
                 break;
             }
             {
                 const uint64_t v = (cur + nwaves) * (4 * kWave) + lane;
-                a0 = load_row<DTYPE, MASK>(gv, mask, v); a1 = load_row<DTYPE, MASK>(gv, mask, v + kWave);
-                a2 = load_row<DTYPE, MASK>(gv, mask, v + 2 * kWave); a3 = load_row<DTYPE, MASK>(gv, mask, v + 3 * kWave);
+                a0 = load_row<DTYPE, MASK, KEEP>(gv, mask, v); a1 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + kWave);
+                a2 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + 2 * kWave); a3 = load_row<DTYPE, MASK, KEEP>(gv, mask, v + 3 * kWave);
             }
             reduce(b0); reduce(b1); reduce(b2); reduce(b3);
             cur += nwaves;
@@ -389,6 +403,11 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
         } else {
             reduce(b0); reduce(b1); reduce(b2); reduce(b3);
         }
+        return cur + nwaves;
+    };
+    {
+        uint64_t cur = walk(std::false_type{}, wave, first_kept < nbatches ? first_kept : nbatches);
+        walk(std::true_type{}, cur, nbatches);
     }
     // up to three full rows after the last batch
     for (uint64_t row = nbatches * 4 + wave; row < nrows; row += nwaves)
@@ -446,9 +465,10 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
 template <int DTYPE, int MASK>
 __global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ g,
                                                        const void *__restrict__ mask, uint64_t n,
+                                                       uint64_t keep_vecs,
                                                        Partial *__restrict__ partials)
 {
-    stage1_body<DTYPE, false, MASK>(g, mask, n, partials);
+    stage1_body<DTYPE, false, MASK>(g, mask, n, keep_vecs, partials);
 }
 
 // Merges `count` per-block records; thread 0 writes the result to *out and, if given, to *lds_out.
@@ -534,12 +554,13 @@ struct SolveRequest {
 template <int DTYPE, int MASK>
 __global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restrict__ g,
                                                              const void *__restrict__ mask, uint64_t n,
+                                                             uint64_t keep_vecs,
                                                              Partial *partials, unsigned int *ticket,
                                                              SolveRequest rq, lgn_stats_t *st_out,
                                                              lgn_prune_params_t *p_out,
                                                              lgn_fp_params_t *f_out)
 {
-    stage1_body<DTYPE, true, MASK>(g, mask, n, partials);
+    stage1_body<DTYPE, true, MASK>(g, mask, n, keep_vecs, partials);
     __shared__ bool is_last;
     __shared__ lgn_stats_t st_lds;
     if (threadIdx.x == 0) {
@@ -593,6 +614,21 @@ hipError_t launch_workspace_init(void *ws, hipStream_t stream)
     return hipGetLastError();
 }
 
+// How much of the tensor's tail the statistics pass leaves in the memory-side cache (256 MB on
+// this chip), in 16-byte vectors.  LGN_STATS_KEEP_MB overrides the default; 0 switches it off.
+static uint64_t kept_vectors()
+{
+    static const uint64_t v = [] {
+        long mb = 224;
+        if (const char *e = getenv("LGN_STATS_KEEP_MB")) {
+            const long x = atol(e);
+            if (x >= 0 && x <= 4096) mb = x;
+        }
+        return (uint64_t)mb * ((1u << 20) / 16);
+    }();
+    return v;
+}
+
 // Calls f.template operator()<DTYPE, MASK>() for the run-time pair (dtype, mask_kind).
 template <typename F>
 static void dispatch_dtype_mask(int dtype, int mask_kind, F &&f)
@@ -621,7 +657,7 @@ struct Stage1Launch {
     template <int DTYPE, int MASK>
     void operator()() const
     {
-        stats_stage1<DTYPE, MASK><<<blocks, kBlock, 0, stream>>>(g, mask, n, partials);
+        stats_stage1<DTYPE, MASK><<<blocks, kBlock, 0, stream>>>(g, mask, n, kept_vectors(), partials);
     }
 };
 
@@ -639,7 +675,8 @@ struct SolveLaunch {
     template <int DTYPE, int MASK>
     void operator()() const
     {
-        stats_solve_kernel<DTYPE, MASK><<<blocks, kBlock, 0, stream>>>(g, mask, n, partials, ticket, rq, st, p, f);
+        stats_solve_kernel<DTYPE, MASK><<<blocks, kBlock, 0, stream>>>(g, mask, n, kept_vectors(), partials, ticket, rq,
+                                                                   st, p, f);
     }
 };
 
