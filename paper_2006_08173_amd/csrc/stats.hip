@@ -615,18 +615,17 @@ hipError_t launch_workspace_init(void *ws, hipStream_t stream)
 }
 
 // How much of the tensor's tail the statistics pass leaves in the memory-side cache (256 MB on
-// this chip), in 16-byte vectors.  LGN_STATS_KEEP_MB overrides the default; 0 switches it off.
+// this chip), in 16-byte vectors.  LGN_STATS_KEEP_MB overrides the default (read at every call, so
+// that a test can place the boundary inside a small tensor); 0 switches it off.  The result of
+// the pass does not depend on it: every wave still reduces its batches in the same order.
 static uint64_t kept_vectors()
 {
-    static const uint64_t v = [] {
-        long mb = 224;
-        if (const char *e = getenv("LGN_STATS_KEEP_MB")) {
-            const long x = atol(e);
-            if (x >= 0 && x <= 4096) mb = x;
-        }
-        return (uint64_t)mb * ((1u << 20) / 16);
-    }();
-    return v;
+    long mb = 224;
+    if (const char *e = getenv("LGN_STATS_KEEP_MB")) {
+        const long x = atol(e);
+        if (x >= 0 && x <= 4096) mb = x;
+    }
+    return (uint64_t)mb * ((1u << 20) / 16);
 }
 
 // Calls f.template operator()<DTYPE, MASK>() for the run-time pair (dtype, mask_kind).

@@ -125,6 +125,27 @@ def test_stats_config_c1_and_reproducible(lgn):
     assert abs(a.sigma - cfg["sigma"]) < 5 * cfg["sigma"] / math.sqrt(2 * a.nnz)
 
 
+def test_stats_do_not_depend_on_how_much_of_the_tail_stays_cached(lgn, monkeypatch):
+    """The statistics pass reads the tensor's tail with cache-allocating loads and the rest with
+    streaming loads (LGN_STATS_KEEP_MB sets where the tail begins).  The boundary is placed
+    before, inside (also off a batch boundary) and after a 5 M-element tensor: same bits each
+    time, and the oracle's values."""
+    n = 5_000_003
+    for dtype in (SI.F32, SI.BF16):
+        g = SI.lognormal_tensor(n, seed=31, mu=-11.0, sigma=2.5, zero_frac=0.2, dtype=dtype)
+        d = to_dev(g)
+        want = O.stats(g)
+        seen = []
+        for mb in ("0", "1", "3", "7", "64"):
+            monkeypatch.setenv("LGN_STATS_KEEP_MB", mb)
+            a = lgn.read_stats(lgn.lgn_stats(d))
+            st, _, _ = lgn.lgn_stats_solve(d, 0.9, lgn.LGN_F32 if dtype == SI.F32 else lgn.LGN_BF16, 6)
+            assert bytes(lgn.read_stats(st)) == bytes(a)
+            assert_stats_match(a, want)
+            seen.append(bytes(a))
+        assert len(set(seen)) == 1
+
+
 def test_stats_argument_errors(lgn):
     g = torch.zeros(1024, device="cuda")
     with pytest.raises(lgn.LgnError) as e:
