@@ -58,7 +58,7 @@ def parse():
     ap.add_argument("--event-every", type=int, default=10,
                     help="record the per-kernel HIP events on every N-th timed step (each record "
                          "costs a few microseconds of stream time; 1 = every step)")
-    ap.add_argument("--streams", type=int, default=4,
+    ap.add_argument("--streams", type=int, default=3,
                     help="workload c3 only: tensors are dealt round-robin to this many HIP streams (default "
                          "priority, one workspace each), so one tensor's solver tail overlaps the next "
                          "tensor's streaming kernels")
