@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
     if (overflow && threadIdx.x == 0) a.table[nchunks + 1] = 1;  // stream buffer too small
 }
 
-// ---- decode: one thread per chunk (sequential by nature; not on the hot path) ----------------
+// ---- decode: one thread per chunk (a chunk is sequential by nature; not on the hot path) ------
 template <int WC>
 __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
 {
@@ -323,35 +323,78 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
     const uint64_t nchunks = (a.n + kChunk - 1) / kChunk;
     const uint32_t *in = reinterpret_cast<const uint32_t *>(a.in);
     T *out = reinterpret_cast<T *>(a.out);
-    const uint64_t c = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (c >= nchunks) return;
-    const uint64_t first = c * kChunk, last = min(first + kChunk, a.n);
-    const uint64_t wend = a.table[c + 1];
-    uint64_t w = a.table[c];
-    uint64_t acc = 0;   // bits fetched and not yet consumed, low bits first
-    uint32_t have = 0;
-    auto take = [&](uint32_t k) {  // k <= 32 bits; zeros past the end of the chunk
-        if (have < k) {
-            const uint32_t x = w < wend ? in[w] : 0u;
-            ++w;
-            acc |= (uint64_t)x << have;
-            have += 32u;
-        }
-        const uint32_t r = k == 32u ? (uint32_t)acc : ((uint32_t)acc & ((1u << k) - 1u));
-        acc >>= k;
-        have -= k;
-        return r;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t c = (uint64_t)blockIdx.x * kBlock + tid;
+    // a thread without a chunk reads nothing and decodes zeros; it still helps to copy out
+    const uint64_t wend = c < nchunks ? a.table[c + 1] : 0;
+    uint64_t w = c < nchunks ? a.table[c] : 0;  // next word to request
+
+    // The threads of a wave sit in different symbols of different chunks, and a wait for memory
+    // holds the whole wave, so nothing that waits may sit in a branch only some threads take.
+    // Input therefore goes through a ring of 16 words per thread in LDS (word j of thread t at
+    // j * kBlock + t: a thread only ever touches its own column, and the bank is fixed by t).
+    // Once per step, at the same point for every thread, the free slots of the ring (at most six:
+    // a step consumes at most 160 bits) are requested from memory, and they are stored into the
+    // ring at the end of the step, after the step's symbols have been decoded.  Words past the
+    // end of the chunk read as zero.
+    constexpr uint32_t kRing = 16, kTop = 6;
+    __shared__ uint32_t ring[kRing * kBlock];
+    uint32_t rd = 0, wr = kRing;  // words moved to the accumulator / words stored in the ring
+#pragma unroll
+    for (uint32_t j = 0; j < kRing; ++j) ring[j * kBlock + tid] = w + j < wend ? in[w + j] : 0u;
+    w += kRing;
+    uint64_t acc = 0;   // bits not yet consumed, low bits first
+    uint32_t have = 0;  // how many
+    uint32_t next = ring[tid];  // word `rd` of the chunk, read ahead of its use
+    // Tops the accumulator up to at least 32 bits; selects, no branch, and the ring is read at
+    // every call so that the read is waited for at the next call, not in a branch.
+    auto refill = [&]() {
+        const bool need = have < 32u;
+        const uint64_t moved = (uint64_t)next << (have & 31u);
+        acc |= need ? moved : 0ull;
+        have += need ? 32u : 0u;
+        rd += need ? 1u : 0u;
+        next = ring[(rd & (kRing - 1u)) * kBlock + tid];
     };
+    const uint32_t payload_mask = width == 32 ? 0xffffffffu : (1u << width) - 1u;
+    // A symbol is classified from its first two bits, again with selects.
     auto symbol = [&]() {
-        uint32_t v = 0u;
-        if (take(1)) {
-            if (take(1)) v = take((uint32_t)width);
-            else v = special | (take(1) << (width - 1));
+        refill();
+        const uint32_t lo = (uint32_t)acc;
+        const bool nonzero = (lo & 1u) != 0u, value = (lo & 3u) == 3u;
+        uint32_t v = nonzero ? special | (((lo >> 2) & 1u) << (width - 1)) : 0u;
+        if (WC != 2) {  // 2 + width <= 18 bits: the whole symbol is in `lo`
+            const uint32_t len = nonzero ? (value ? 2u + (uint32_t)width : 3u) : 1u;
+            v = value ? (lo >> 2) & payload_mask : v;
+            acc >>= len;
+            have -= len;
+        } else {  // 2 + 32 bits: the head, then the payload after a second top-up
+            const uint32_t head = nonzero ? (value ? 2u : 3u) : 1u;
+            acc >>= head;
+            have -= head;
+            refill();
+            v = value ? (uint32_t)acc : v;
+            const uint32_t len = value ? 32u : 0u;
+            acc >>= len;
+            have -= len;
         }
         return v;
     };
-    uint64_t i = first;
-    for (; i + EPV <= last; i += EPV) {  // sixteen bytes of output at a time
+
+    // Output: a thread produces 16 bytes per step, 4 KiB-of-elements apart from its neighbours'.
+    // Eight steps are collected in LDS (128 bytes per thread, slots rotated by the thread index
+    // to spread the banks) and then written by the wave as whole 128-byte lines: lane l writes
+    // piece l % 8 of the thread l / 8 + 8 k, k = 0..7.  Only wave-level ordering is needed.
+    __shared__ uint4 stage[kBlock * 8];
+    const int lane = (int)tid & (kWave - 1);
+    const int wave_first = (int)tid - lane;                      // first thread of this wave
+    const uint64_t wave_chunk = (uint64_t)blockIdx.x * kBlock + (uint64_t)wave_first;
+    constexpr int kSteps = kChunk / EPV;
+    for (int step = 0; step < kSteps; ++step) {
+        const uint32_t fresh = min(kRing - (wr - rd), kTop);  // free slots of the ring
+        uint32_t top[kTop];
+#pragma unroll
+        for (uint32_t j = 0; j < kTop; ++j) top[j] = (j < fresh && w + j < wend) ? in[w + j] : 0u;
         uint32_t q[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int j = 0; j < EPV; ++j) {
@@ -360,9 +403,38 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
             else if (WC == 1) q[j / 2] |= v << (16 * (j % 2));
             else q[j / 4] |= v << (8 * (j % 4));
         }
-        *reinterpret_cast<uint4 *>(out + i) = make_uint4(q[0], q[1], q[2], q[3]);
+#pragma unroll
+        for (uint32_t j = 0; j < kTop; ++j)
+            if (j < fresh) ring[((wr + j) & (kRing - 1u)) * kBlock + tid] = top[j];
+        wr += fresh;
+        w += fresh;
+        stage[tid * 8 + ((step + (int)tid) & 7)] = make_uint4(q[0], q[1], q[2], q[3]);
+        if ((step & 7) != 7) continue;
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        const int piece = lane & 7;                       // 16-byte piece of the 128-byte line
+        const int pstep = (step & ~7) + piece;            // the step that produced it
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int t = wave_first + k * 8 + (lane >> 3);  // thread whose line this lane writes
+            const uint64_t chunk = wave_chunk + (uint64_t)(k * 8 + (lane >> 3));
+            const uint4 x = stage[t * 8 + ((pstep + t) & 7)];
+            if (chunk >= nchunks) continue;
+            const uint64_t e0 = chunk * kChunk + (uint64_t)pstep * EPV;  // first element of the piece
+            if (e0 + EPV <= a.n) {
+                *reinterpret_cast<uint4 *>(out + e0) = x;
+            } else if (e0 < a.n) {  // the ragged end of the tensor, element by element
+                const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
+                for (int j = 0; e0 + j < a.n; ++j) {
+                    if (WC == 2) out[e0 + j] = (T)xs[j];
+                    else if (WC == 1) out[e0 + j] = (T)(xs[j / 2] >> (16 * (j % 2)));
+                    else out[e0 + j] = (T)(xs[j / 4] >> (8 * (j % 4)));
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
-    for (; i < last; ++i) out[i] = (T)symbol();
 }
 
 static int prefix_grid(uint64_t nchunks)
