@@ -293,7 +293,10 @@ def main():
         pbuf, ptab = lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, width=n_bits)
         enc_ms = timed(lambda: lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, out=pbuf, table=ptab))
         words = int(ptab[nchunks].item())
-        del pbuf, ptab
+        dec = torch.empty(n, dtype=torch.uint8, device="cuda")
+        dec_ms = timed(lambda: lgn.lgn_prefix_decode(pbuf, ptab, n, lgn.LGN_OUT_CODE8, pp, fp, out=dec))
+        assert torch.equal(dec, out), "prefix round trip"
+        del pbuf, ptab, dec
         hist = torch.empty(lgn.LGN_HIST_BINS, dtype=torch.int64, device="cuda")
         hist_ms = timed(lambda: lgn.lgn_log_histogram(d, out=hist))
         bmask = (view != 0).to(torch.uint8)              # a ReLU-style byte mask: the non-zero entries
@@ -307,6 +310,8 @@ def main():
             "prefix_encode": {"ms": round(enc_ms, 4), "bits_per_value": round(words * 32 / n, 3),
                               "GBps": gb(2 * n + words * 4, enc_ms),
                               "what": "lgn_prefix_encode of the step's CODE8 output: reads it twice, writes the stream"},
+            "prefix_decode": {"ms": round(dec_ms, 4), "GBps": gb(n + words * 4, dec_ms),
+                              "what": "lgn_prefix_decode of that stream back to the codes (checked equal)"},
             "log_histogram": {"ms": round(hist_ms, 4), "GBps": gb(n * in_bytes, hist_ms),
                               "what": "lgn_log_histogram of the tensor (one read)"},
             "stats_masked_u8": {"ms": round(masked_ms, 4), "GBps": gb(n * (in_bytes + 1), masked_ms),
@@ -314,7 +319,7 @@ def main():
             "stats_masked_same_dtype": {"ms": round(masked_same_ms, 4), "GBps": gb(2 * n * in_bytes, masked_same_ms),
                                         "what": "lgn_stats_masked with a mask tensor of the same dtype (two reads)"},
             "note": "measured after the timed region; not part of the step"}
-        log(f"[bench] beyond the hot path: prefix code {enc_ms:.4f} ms ({words * 32 / n:.3f} bits per value), "
+        log(f"[bench] beyond the hot path: prefix code {enc_ms:.4f} ms ({words * 32 / n:.3f} bits per value, decode {dec_ms:.4f} ms), "
             f"histogram {hist_ms:.4f} ms, masked stats {masked_ms:.4f} ms (byte mask) / {masked_same_ms:.4f} ms (same dtype)")
         # leave the structs as the timed step wrote them
         one_step()
