@@ -235,7 +235,8 @@ int lgn_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in, 
  *   n_bits      total bits N in [2, 8]
  *   e_bits      exponent bits in [1, N-1], or -1 to take the minimiser
  *   scale_mode  LGN_SCALE_*;  scale_arg is the quantile (0,1) for LGN_SCALE_QUANTILE (the paper's
- *               example is 0.997), ignored otherwise
+ *               example is 0.997), ignored otherwise; its standard normal quantile is evaluated
+ *               on the host before the launch (it does not depend on the tensor)
  *   sigma_units LGN_SIGMA_*
  * One single-wave launch.
  */

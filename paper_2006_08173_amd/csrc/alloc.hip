@@ -172,7 +172,7 @@ __device__ void allocate_layer(const AllocArgs &a, int i, double target, uint32_
 {
     const lgn_stats_t *st = a.stats + i;
     lgn_prune_params_t *p = a.p_out + i;
-    threshold_body(st, target, a.alpha_dtype, p);
+    threshold_body<false>(st, target, a.alpha_dtype, p);
     lgn_alloc_t r;
     r.status = status;
     r.reserved = 0u;
@@ -190,11 +190,11 @@ __device__ void allocate_layer(const AllocArgs &a, int i, double target, uint32_
             const double av = exp(mu + L);
             alpha = av >= 3.4028234663852886e38 ? 3.4028234663852886e38f : (float)av;
             alpha = round_alpha(alpha, a.alpha_dtype);
-            double B;
+            double B, C;
             s_pred = 0.0;
             if (alpha > 0.0f) {
                 L = log((double)alpha) - mu;
-                sparsity_terms(mu, sigma, mu + L, s_pred, B);
+                sparsity_terms<false>(mu, sigma, mu + L, s_pred, B, C);
             }
             p->alpha = alpha;
             p->s_pred = s_pred;

@@ -1,4 +1,5 @@
 // C interface of the library (see include/lgn.h): argument checks and kernel launches only.
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -21,7 +22,7 @@ size_t stats_workspace_bytes();
 hipError_t launch_workspace_init(void *ws, hipStream_t stream);
 hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
                               double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
-                              int scale_mode, double scale_arg, int sigma_units, lgn_stats_t *st,
+                              int scale_mode, double scale_z, int sigma_units, lgn_stats_t *st,
                               lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
                               hipStream_t stream);
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
@@ -29,7 +30,7 @@ hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtyp
 hipError_t launch_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in,
                                   lgn_prune_params_t *out, hipStream_t stream);
 hipError_t launch_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
-                            double scale_arg, int sigma_units, lgn_fp_params_t *out,
+                            double scale_z, int sigma_units, lgn_fp_params_t *out,
                             hipStream_t stream);
 hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int out_kind,
                          const StreamArgs &args, int max_blocks, hipStream_t stream);
@@ -163,6 +164,29 @@ int check_threshold_args(double target_sparsity, int alpha_dtype)
     return LGN_OK;
 }
 
+// Standard normal quantile of the scale rule's probability.  It depends on an argument of the
+// call only, not on the tensor, so it is evaluated here instead of in the last workgroup of the
+// statistics pass, where every microsecond is on the critical path of the next launch.  A
+// rational first guess (Abramowitz & Stegun 26.2.23) polished by Newton steps on the tail
+// probability, which keeps full relative accuracy in both tails.
+double scale_rule_z(int scale_mode, double q)
+{
+    if (scale_mode != LGN_SCALE_QUANTILE) return 0.0;
+    const bool upper = q > 0.5;
+    const double p = upper ? 1.0 - q : q;  // tail probability, 0 < p <= 0.5 (checked by the caller)
+    const double t = sqrt(-2.0 * log(p));
+    double z = t - (2.515517 + 0.802853 * t + 0.010328 * t * t) /
+                       (1.0 + 1.432788 * t + 0.189269 * t * t + 0.001308 * t * t * t);
+    for (int it = 0; it < 8; ++it) {
+        const double qz = 0.5 * erfc(z / 1.41421356237309504880168872421);
+        const double pdf = exp(-0.5 * z * z) * 0.398942280401432677939946059934;
+        const double step = (qz - p) / pdf;
+        z += step;
+        if (fabs(step) <= 1e-16 * fmax(1.0, fabs(z))) break;
+    }
+    return upper ? z : -z;
+}
+
 int check_fp_args(int n_bits, int e_bits, int scale_mode, double scale_arg, int sigma_units)
 {
     if (n_bits < 2 || n_bits > 8) return fail(LGN_ERR_INVALID_ARG, "n_bits %d outside [2, 8]", n_bits);
@@ -253,7 +277,7 @@ int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, 
     }
     const hipError_t e = lgn::launch_stats_solve(
         g, mask, mask_kind, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
-        scale_arg, sigma_units, st_out, want_p ? p_out : nullptr, n_bits ? f_out : nullptr, ws,
+        n_bits ? scale_rule_z(scale_mode, scale_arg) : 0.0, sigma_units, st_out, want_p ? p_out : nullptr, n_bits ? f_out : nullptr, ws,
         stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_solve", e);
 }
@@ -285,8 +309,9 @@ int lgn_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
     if (!st || !out) return fail(LGN_ERR_INVALID_ARG, "null struct pointer");
     if (!aligned(st, 8) || !aligned(out, 8)) return fail(LGN_ERR_INVALID_ARG, "struct not 8-byte aligned");
     if (int rc = check_fp_args(n_bits, e_bits, scale_mode, scale_arg, sigma_units)) return rc;
-    const hipError_t e = lgn::launch_fp_params(st, n_bits, e_bits, scale_mode, scale_arg,
-                                               sigma_units, out, static_cast<hipStream_t>(stream));
+    const hipError_t e = lgn::launch_fp_params(st, n_bits, e_bits, scale_mode,
+                                               scale_rule_z(scale_mode, scale_arg), sigma_units, out,
+                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_fp_params", e);
 }
 

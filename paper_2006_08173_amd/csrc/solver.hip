@@ -7,15 +7,15 @@ __global__ __launch_bounds__(kWave) void threshold_kernel(const lgn_stats_t *__r
                                                           double target, int alpha_dtype,
                                                           lgn_prune_params_t *__restrict__ out)
 {
-    if (threadIdx.x == 0) threshold_body(st, target, alpha_dtype, out);
+    threshold_body<true>(st, target, alpha_dtype, out);
 }
 
 __global__ __launch_bounds__(kWave) void fp_params_kernel(const lgn_stats_t *__restrict__ st,
                                                           int n_bits, int e_fixed, int scale_mode,
-                                                          double scale_arg, int sigma_units,
+                                                          double scale_z, int sigma_units,
                                                           lgn_fp_params_t *__restrict__ out)
 {
-    fp_params_body(st, n_bits, e_fixed, scale_mode, scale_arg, sigma_units, out);
+    fp_params_body(st, n_bits, e_fixed, scale_mode, scale_z, sigma_units, out);
 }
 
 // Stochastic underflow: the pruning threshold raised to the smallest magnitude the format can
@@ -62,10 +62,10 @@ hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtyp
 }
 
 hipError_t launch_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
-                            double scale_arg, int sigma_units, lgn_fp_params_t *out,
+                            double scale_z, int sigma_units, lgn_fp_params_t *out,
                             hipStream_t stream)
 {
-    fp_params_kernel<<<1, kWave, 0, stream>>>(st, n_bits, e_bits, scale_mode, scale_arg,
+    fp_params_kernel<<<1, kWave, 0, stream>>>(st, n_bits, e_bits, scale_mode, scale_z,
                                               sigma_units, out);
     return hipGetLastError();
 }

@@ -56,22 +56,42 @@ __device__ __forceinline__ double normal_quantile_guess(double q)
     return upper ? z : -z;
 }
 
-// S(v) and its derivative B(v) = dS/dv.
-__device__ __forceinline__ void sparsity_terms(double mu, double sigma, double v, double &S, double &B)
+// S(v), its derivative B(v) = dS/dv and its second derivative C(v).  The second derivative of the
+// second term of S is -B + phi(L/sigma)/sigma (the exponents of its two factors add up to
+// -L^2 / (2 sigma^2)).
+//
+// COOP = false: an ordinary per-lane function.  COOP = true: called by all lanes of a wave, the two
+// lanes of a pair (2p, 2p+1) with the same arguments.  The chain of one evaluation is
+// erfc -> log -> exp; the two erfc calls and the two exp calls are independent of each other, so
+// the even and the odd lane of a pair take one each and swap the values: the same operations on
+// the same operands as the per-lane form, in three transcendental latencies instead of five.
+template <bool COOP>
+__device__ __forceinline__ void sparsity_terms(double mu, double sigma, double v, double &S, double &B,
+                                               double &C)
 {
     const double L = v - mu;
-    const double A = 0.5 * erfc(-L / (kSqrt2 * sigma));
-    const double tail = erfc((sigma * sigma - L) / (kSqrt2 * sigma));
-    B = tail > 0.0 ? 0.5 * exp(0.5 * sigma * sigma - L + log(tail)) : 0.0;
+    const double a = L / sigma;
+    const double za = -L / (kSqrt2 * sigma), zb = (sigma * sigma - L) / (kSqrt2 * sigma);
+    const double xb = -0.5 * a * a;  // exponent of the density term
+    double A, tail, eb, ec;
+    if (COOP) {
+        const bool odd = (threadIdx.x & 1u) != 0u;
+        const double e = erfc(odd ? zb : za), e_other = __shfl_xor(e, 1);
+        A = 0.5 * (odd ? e_other : e);
+        tail = odd ? e : e_other;
+        const double x = exp(odd ? xb : 0.5 * sigma * sigma - L + (tail > 0.0 ? log(tail) : 0.0));
+        const double x_other = __shfl_xor(x, 1);
+        eb = odd ? x_other : x;
+        ec = odd ? x : x_other;
+    } else {
+        A = 0.5 * erfc(za);
+        tail = erfc(zb);
+        eb = exp(0.5 * sigma * sigma - L + (tail > 0.0 ? log(tail) : 0.0));
+        ec = exp(xb);
+    }
+    B = tail > 0.0 ? 0.5 * eb : 0.0;
+    C = ec * (0.398942280401432677939946059934 / sigma) - B;
     S = A - B;
-}
-
-// Second derivative of S given B: the derivative of the second term of S is -B + phi(L/sigma)/sigma
-// (the exponents of its two factors add up to -L^2 / (2 sigma^2)).
-__device__ __forceinline__ double sparsity_curvature(double mu, double sigma, double v, double B)
-{
-    const double a = (v - mu) / sigma;
-    return exp(-0.5 * a * a) * (0.398942280401432677939946059934 / sigma) - B;
 }
 
 __device__ __forceinline__ float round_to_bf16(float f)
@@ -100,7 +120,10 @@ __device__ __forceinline__ float round_alpha(float alpha, int alpha_dtype)
     return alpha;
 }
 
-// Runs in one lane (the caller picks it); `st` may point to LDS or global memory.
+// COOP = false: runs in one lane (the caller picks it).  COOP = true: runs in all lanes of one wave,
+// every lane with the same values, and lane 0 stores the result.  `st` may point to LDS or global
+// memory.
+template <bool COOP>
 __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double target, int alpha_dtype,
                                                lgn_prune_params_t *out)
 {
@@ -110,8 +133,9 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
     r.s_pred = 0.0;
     r.status = st->status & (LGN_ST_EMPTY | LGN_ST_SIGMA0 | LGN_ST_HAS_NONFINITE);
     const uint64_t nn = st->n, nz = st->nnz;
+    const bool writer = !COOP || (threadIdx.x & (kWave - 1)) == 0;
     if (nz == 0) {
-        *out = r;
+        if (writer) *out = r;
         return;
     }
     const double n = (double)nn, nnz = (double)nz;
@@ -119,11 +143,13 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
     r.s_eff = s_eff;
     if (!(s_eff > 0.0)) {
         r.status |= LGN_ST_NOTHING_TO_PRUNE;
-        *out = r;
+        if (writer) *out = r;
         return;
     }
     const double mu = st->mu, sigma = st->sigma;
     double v;
+    double v_at = 0.0, S_at = 0.0, B_at = 0.0, C_at = 0.0;  // last point evaluated; S, S', S'' there
+    bool evaluated = false;
     const bool point_mass = sigma < 1e-12;
     if (point_mass) {
         v = mu - log1p(-s_eff);
@@ -132,27 +158,61 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
         // Bracket: stochastic pruning zeroes less than a hard threshold at the same alpha, so the
         // lognormal quantile of s_eff is a lower bound of the root; the unpolished guess of the
         // normal quantile, lowered by more than its error, is enough for that.
-        double lo = mu + sigma * (normal_quantile_guess(s_eff) - 1e-3), hi = lo, S, B;
-        double step = sigma;
+        double lo = mu + sigma * (normal_quantile_guess(s_eff) - 1e-3), hi = lo;
+        double S = 0.0, B = 0.0, C = 0.0;
         bool ok = false;
-        for (int i = 0; i < 64; ++i) {
-            hi += step;
-            step *= 2.0;
-            sparsity_terms(mu, sigma, hi, S, B);
-            if (S > s_eff) { ok = true; break; }
-            lo = hi;
+        v = lo;
+        if constexpr (COOP) {
+            // One evaluation time buys 32 points, one per lane pair, at distances from the lower
+            // bound that grow by sqrt(2) per pair (0.02 sigma (2^(p/2) - 1): pair 0 sits on the
+            // bound, pair 31 at 927 sigma).  S is increasing, so the first pair above the target
+            // and the pair before it bracket the root within a factor sqrt(2) of its distance;
+            // the iteration starts from a third-order step taken at the nearer of the two.
+            const int lane = (int)(threadIdx.x & (kWave - 1)), pair = lane >> 1;
+            const double vp = lo + sigma * 0.02 * (ldexp((pair & 1) ? kSqrt2 : 1.0, pair >> 1) - 1.0);
+            double Sp, Bp, Cp;
+            sparsity_terms<true>(mu, sigma, vp, Sp, Bp, Cp);
+            const uint64_t above = __ballot(Sp > s_eff);
+            if (above != 0ull && (above & 1ull) == 0ull) {
+                const int up = __ffsll((long long)above) - 1, down = up - 2;  // even lanes of the two pairs
+                hi = __shfl(vp, up);
+                lo = __shfl(vp, down);
+                const double f_up = __shfl(Sp, up) - s_eff, f_down = __shfl(Sp, down) - s_eff;
+                const int from = fabs(f_down) < fabs(f_up) ? down : up;
+                const double v0 = __shfl(vp, from), f0 = __shfl(Sp, from) - s_eff;
+                const double B0 = __shfl(Bp, from), C0 = __shfl(Cp, from);
+                v = 0.5 * (lo + hi);
+                if (B0 > 0.0) {
+                    const double h = v0 - 2.0 * f0 * B0 / (2.0 * B0 * B0 - f0 * C0);
+                    if (h > lo && h < hi) v = h;
+                }
+                ok = true;
+            }
+        }
+        if (!ok) {  // one lane, or the grid did not bracket the root: widen upwards step by step
+            hi = lo;
+            double step = sigma;
+            for (int i = 0; i < 64; ++i) {
+                hi += step;
+                step *= 2.0;
+                sparsity_terms<COOP>(mu, sigma, hi, S, B, C);
+                if (S > s_eff) { ok = true; break; }
+                lo = hi;
+            }
+            v = 0.5 * (lo + hi);
         }
         if (!ok) r.status |= LGN_ST_NOT_CONVERGED;
-        v = 0.5 * (lo + hi);
         bool converged = false;
         for (int it = 0; it < 200 && ok; ++it) {
-            sparsity_terms(mu, sigma, v, S, B);
+            sparsity_terms<COOP>(mu, sigma, v, S, B, C);
+            v_at = v;
+            evaluated = true;
             const double f = S - s_eff;
             if (f < 0.0) lo = v; else hi = v;
             double nv = 0.5 * (lo + hi);
             bool third_order = false;
             if (B > 0.0) {
-                const double den = 2.0 * B * B - f * sparsity_curvature(mu, sigma, v, B);
+                const double den = 2.0 * B * B - f * C;
                 const double h = v - 2.0 * f * B / den;
                 if (h > lo && h < hi) { nv = h; third_order = true; }
             }
@@ -165,6 +225,7 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
             if (done) { converged = true; break; }
         }
         if (ok && !converged) r.status |= LGN_ST_NOT_CONVERGED;
+        S_at = S; B_at = B; C_at = C;
     }
     const double alpha = exp(v);
     float af = alpha >= 3.4028234663852886e38 ? 3.4028234663852886e38f : (float)alpha;
@@ -174,12 +235,23 @@ __device__ __forceinline__ void threshold_body(const lgn_stats_t *st, double tar
         if (point_mass) {
             r.s_pred = fmax(0.0, 1.0 - exp(mu) / (double)af);
         } else {
-            double S, B;
-            sparsity_terms(mu, sigma, log((double)af), S, B);
-            r.s_pred = S;
+            // S at the rounded threshold.  Its logarithm is v plus log1p of the relative rounding
+            // error; if that lies within 1e-5 sigma of the last point the iteration evaluated,
+            // the second-order expansion there is exact to ~1e-16 (the next term is D^3 / 6 times
+            // the third derivative, which is O(1 / sigma^3)) and saves an evaluation; otherwise
+            // (16-bit thresholds, a last step that was not small) S is evaluated at the point.
+            const double rel = ((double)af - alpha) / alpha;
+            const double D = (v - v_at) + (rel - 0.5 * rel * rel);
+            if (evaluated && alpha < 3.4028234663852886e38 && fabs(rel) < 1e-6 && fabs(D) <= 1e-5 * sigma) {
+                r.s_pred = S_at + B_at * D + 0.5 * C_at * D * D;
+            } else {
+                double S, B, C;
+                sparsity_terms<COOP>(mu, sigma, log((double)af), S, B, C);
+                r.s_pred = S;
+            }
         }
     }
-    *out = r;
+    if (writer) *out = r;
 }
 
 // Expected relative error of FP(1,e,m) on lognormal data (Section 4.2, final expression; 2^m
@@ -198,8 +270,10 @@ __device__ double expected_relative_error(double sigma, int e_bits, int m_bits)
 }
 
 // Runs in all 64 lanes of one wave; `st` may point to LDS or global memory.
+// `scale_z` is the standard normal quantile of the scale rule's probability (the host evaluates
+// it: it depends on the call's argument only); unused by the other scale rules.
 __device__ __forceinline__ void fp_params_body(const lgn_stats_t *st, int n_bits, int e_fixed,
-                                               int scale_mode, double scale_arg, int sigma_units,
+                                               int scale_mode, double scale_z, int sigma_units,
                                                lgn_fp_params_t *out)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -213,10 +287,7 @@ __device__ __forceinline__ void fp_params_body(const lgn_stats_t *st, int n_bits
     double eta = __builtin_inf();
     if (spread && cand <= n_bits - 1 && (e_fixed < 1 || cand == e_fixed))
         eta = expected_relative_error(sg, cand, n_bits - 1 - cand);
-    // lane 63 meanwhile evaluates the quantile the scale rule needs
-    double zq = 0.0;
-    if (lane == kWave - 1 && nnz != 0 && scale_mode == LGN_SCALE_QUANTILE) zq = normal_quantile(scale_arg);
-    zq = __shfl(zq, kWave - 1);
+    const double zq = scale_z;
 
     double best = eta;
     int best_e = cand;

@@ -548,7 +548,7 @@ struct SolveRequest {
     int alpha_dtype;
     int n_bits;              // 0: no format asked for
     int e_bits, scale_mode, sigma_units;
-    double scale_arg;
+    double scale_z;  // standard normal quantile of the scale rule (evaluated by the host)
 };
 
 template <int DTYPE, int MASK>
@@ -582,9 +582,9 @@ __global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restr
     __syncthreads();
     const int wave = threadIdx.x / kWave;
     if (wave == 0 && p_out && rq.target_sparsity >= 0.0) {
-        if ((threadIdx.x & (kWave - 1)) == 0) threshold_body(&st_lds, rq.target_sparsity, rq.alpha_dtype, p_out);
+        threshold_body<true>(&st_lds, rq.target_sparsity, rq.alpha_dtype, p_out);
     } else if (wave == 1 && f_out && rq.n_bits != 0) {
-        fp_params_body(&st_lds, rq.n_bits, rq.e_bits, rq.scale_mode, rq.scale_arg, rq.sigma_units, f_out);
+        fp_params_body(&st_lds, rq.n_bits, rq.e_bits, rq.scale_mode, rq.scale_z, rq.sigma_units, f_out);
     }
     if (threadIdx.x == 0) *ticket = 0u;  // ready for the next call on this workspace
 }
@@ -694,7 +694,7 @@ hipError_t launch_stats(const void *g, const void *mask, int mask_kind, uint64_t
 
 hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
                               double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
-                              int scale_mode, double scale_arg, int sigma_units, lgn_stats_t *st,
+                              int scale_mode, double scale_z, int sigma_units, lgn_stats_t *st,
                               lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
                               hipStream_t stream)
 {
@@ -702,7 +702,7 @@ hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, ui
     if (blocks > max_blocks) blocks = max_blocks;
     Partial *partials = static_cast<Partial *>(ws);
     unsigned int *ticket = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset);
-    const SolveRequest rq = {target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode, sigma_units, scale_arg};
+    const SolveRequest rq = {target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode, sigma_units, scale_z};
     dispatch_dtype_mask(dtype, mask_kind,
                         SolveLaunch{g, mask, n, partials, ticket, rq, st, p, f, blocks, stream});
     return hipGetLastError();

@@ -187,6 +187,28 @@ def test_threshold_parity_identical_inputs(lgn, mu, sigma):
                 assert got.s_pred == pytest.approx(want.s_pred, abs=1e-13)
 
 
+def test_threshold_parity_random_sweep(lgn):
+    """3000 seeded (mu, sigma, target, zero share) draws over the whole range the solver accepts,
+    from nearly a point mass to sigma = 12 and from 0.1 % to 99.99 % sparsity: the threshold has
+    the oracle's bits, the predicted sparsity its value to 1e-13.  Covers the solver's wave-wide
+    first round (root up to hundreds of sigma above the hard-threshold quantile when sigma is
+    small) and its fall-back."""
+    rng = np.random.default_rng(20260)
+    for k in range(3000):
+        mu = float(rng.uniform(-25.0, 5.0))
+        sigma = float(rng.choice([rng.uniform(0.02, 0.3), rng.uniform(0.3, 4.0), rng.uniform(4.0, 12.0)]))
+        n = int(rng.integers(1000, 1 << 30))
+        nnz = int(n * rng.uniform(0.3, 1.0))
+        s = float(rng.choice([rng.uniform(0.001, 0.3), rng.uniform(0.3, 0.99), rng.uniform(0.99, 0.9999)]))
+        adt = (O.F32, O.F32, O.BF16, O.F16)[k % 4]
+        st = O.make_stats(n, nnz, mu, sigma, 1.0, 1e-30)
+        want = O.threshold(st, s, adt)
+        got = lgn.read_prune_params(lgn.lgn_threshold(dev_stats_from_oracle(lgn, st), s, adt))
+        assert np.float32(got.alpha).view(np.uint32) == np.float32(want.alpha).view(np.uint32), (mu, sigma, n, nnz, s, adt)
+        assert got.status == want.status, (mu, sigma, n, nnz, s, adt)
+        assert got.s_pred == pytest.approx(want.s_pred, abs=1e-13), (mu, sigma, n, nnz, s, adt)
+
+
 def test_threshold_parity_degenerate(lgn):
     cases = [O.make_stats(100, 0, float("nan"), float("nan"), status=O.ST_EMPTY),
              O.make_stats(100, 100, math.log(3e-4), 0.0, 3e-4, 3e-4, status=O.ST_SIGMA0),
@@ -207,7 +229,8 @@ def test_fp_params_parity_identical_inputs(lgn, mu, sigma):
     dst = dev_stats_from_oracle(lgn, st)
     for n_bits in range(2, 9):
         for e_bits in [-1] + list(range(1, n_bits)):
-            for mode, arg in ((O.SCALE_QUANTILE, 0.997), (O.SCALE_QUANTILE, 0.9), (O.SCALE_MAX, 0.0),
+            for mode, arg in ((O.SCALE_QUANTILE, 0.997), (O.SCALE_QUANTILE, 0.9), (O.SCALE_QUANTILE, 1e-7),
+                              (O.SCALE_QUANTILE, 0.5), (O.SCALE_QUANTILE, 1.0 - 1e-12), (O.SCALE_MAX, 0.0),
                               (O.SCALE_CENTER, 0.0)):
                 for units in (O.SIGMA_PAPER_LITERAL, O.SIGMA_BASE2):
                     want = O.fp_params(st, n_bits, e_bits, mode, arg, units)
