@@ -287,15 +287,15 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    extras = None
-    if out_kind == lgn.LGN_OUT_CODE8 and not args.no_beyond:
+    def measure_beyond():
         nchunks = (n + lgn.LGN_PREFIX_CHUNK - 1) // lgn.LGN_PREFIX_CHUNK
         pbuf, ptab = lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, width=n_bits)
         enc_ms = timed(lambda: lgn.lgn_prefix_encode(out, lgn.LGN_OUT_CODE8, pp, fp, out=pbuf, table=ptab))
         words = int(ptab[nchunks].item())
         dec = torch.empty(n, dtype=torch.uint8, device="cuda")
         dec_ms = timed(lambda: lgn.lgn_prefix_decode(pbuf, ptab, n, lgn.LGN_OUT_CODE8, pp, fp, out=dec))
-        assert torch.equal(dec, out), "prefix round trip"
+        if not torch.equal(dec, out):
+            raise RuntimeError("prefix round trip differs")
         del pbuf, ptab, dec
         hist = torch.empty(lgn.LGN_HIST_BINS, dtype=torch.int64, device="cuda")
         hist_ms = timed(lambda: lgn.lgn_log_histogram(d, out=hist))
@@ -306,7 +306,7 @@ def main():
         masked_same_ms = timed(lambda: lgn.lgn_stats_masked(d, fmask, out=st, ws=ws))
         del fmask
         gb = lambda b, ms: round(b / (ms * 1e-3) / 1e9, 1)
-        extras = {
+        return {
             "prefix_encode": {"ms": round(enc_ms, 4), "bits_per_value": round(words * 32 / n, 3),
                               "GBps": gb(2 * n + words * 4, enc_ms),
                               "what": "lgn_prefix_encode of the step's CODE8 output: reads it twice, writes the stream"},
@@ -319,14 +319,22 @@ def main():
             "stats_masked_same_dtype": {"ms": round(masked_same_ms, 4), "GBps": gb(2 * n * in_bytes, masked_same_ms),
                                         "what": "lgn_stats_masked with a mask tensor of the same dtype (two reads)"},
             "note": "measured after the timed region; not part of the step"}
-        log(f"[bench] beyond the hot path: prefix code {enc_ms:.4f} ms ({words * 32 / n:.3f} bits per value, decode {dec_ms:.4f} ms), "
-            f"histogram {hist_ms:.4f} ms, masked stats {masked_ms:.4f} ms (byte mask) / {masked_same_ms:.4f} ms (same dtype)")
+
+
+    extras = None
+    if out_kind == lgn.LGN_OUT_CODE8 and not args.no_beyond:
+        # a failure here must not take the headline line with it
+        try:
+            extras = measure_beyond()
+            log(f"[bench] beyond the hot path: { {k: v['ms'] for k, v in extras.items() if isinstance(v, dict)} } ms")
+        except Exception as e:  # noqa: BLE001
+            extras = {"error": f"{type(e).__name__}: {e}"}
+            log(f"[bench] beyond the hot path failed: {extras['error']}")
         # leave the structs as the timed step wrote them
         one_step()
         torch.cuda.synchronize()
 
-    cpu = None
-    if not args.no_cpu_baseline:
+    def measure_cpu_baseline():
         import oracle as O
         threads = O.max_threads()
         O.set_threads(threads)
@@ -343,9 +351,16 @@ def main():
                              seed, 0, {lgn.LGN_OUT_CODE8: O.OUT_CODE8, lgn.LGN_OUT_PACKED: O.OUT_PACKED,
                                        lgn.LGN_OUT_VALUE: O.OUT_VALUE}[out_kind])
         dt = (time.perf_counter() - t1) / reps
-        cpu = {"value": round(m * (2 * in_bytes + out_bytes_per_elem) / dt / 1e9, 3), "unit": "GB/s",
-               "cores": threads, "kind": "oracle",
-               "sample": f"first {m} elements of the same tensor, whole chain, {reps} repetitions of {dt:.2f} s"}
+        return {"value": round(m * (2 * in_bytes + out_bytes_per_elem) / dt / 1e9, 3), "unit": "GB/s",
+                "cores": threads, "kind": "oracle",
+                "sample": f"first {m} elements of the same tensor, whole chain, {reps} repetitions of {dt:.2f} s"}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        try:  # a failure here must not take the headline line with it
+            cpu = measure_cpu_baseline()
+        except Exception as e:  # noqa: BLE001
+            cpu = {"value": None, "unit": "GB/s", "cores": 0, "kind": "oracle", "sample": f"failed: {type(e).__name__}: {e}"}
         log(f"[bench] cpu oracle: {cpu}")
 
     line = {
