@@ -264,12 +264,37 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
     bool overflow = false;
     __syncthreads();
     for (uint64_t c = run.first; c < run.last; ++c) {
+        const uint64_t first = c * kChunk + (uint64_t)threadIdx.x * kPerThread;
+        // Byte codes, the usual case (most of them zero after pruning): the thread's sixteen codes
+        // stay packed in four words; which bytes are non-zero and which are the special magnitude
+        // is found for four bytes at a time, and only the non-zero ones are visited below.
+        const bool packed = WC == 0 && c * kChunk + kChunk <= a.n;  // workgroup-uniform
         uint32_t v[kPerThread];
-        const int count = load_thread_elems<WC>(a.in, c * kChunk + (uint64_t)threadIdx.x * kPerThread, a.n, v);
+        uint32_t d[4] = {0u, 0u, 0u, 0u}, nonzero = 0u, is_special16 = 0u;
+        int count = kPerThread;
         uint32_t bits = 0;
+        if (packed) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(static_cast<const uint8_t *>(a.in) + first);
+            d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+            const uint32_t mag = (((1u << (width - 1)) - 1u) & 0xffu) * 0x01010101u, sp4 = special * 0x01010101u;
 #pragma unroll
-        for (int j = 0; j < kPerThread; ++j)
-            if (j < count) bits += (uint32_t)symbol_len(v[j], width, special);
+            for (int k = 0; k < 4; ++k) {
+                // bit 7 of a byte of t: that byte of y is non-zero
+                auto byte_nonzero = [](uint32_t y) { return (((y & 0x7f7f7f7fu) + 0x7f7f7f7fu) | y) & 0x80808080u; };
+                const uint32_t nz = byte_nonzero(d[k]);
+                const uint32_t sp = special ? ~byte_nonzero((d[k] & mag) ^ sp4) & 0x80808080u : 0u;
+                // bits 7, 15, 23, 31 gathered into bits 0..3
+                nonzero |= (((nz >> 7) * 0x00204081u) >> 21 & 0xfu) << (4 * k);
+                is_special16 |= (((sp >> 7) * 0x00204081u) >> 21 & 0xfu) << (4 * k);
+            }
+            const uint32_t n_nz = (uint32_t)__popc(nonzero), n_sp = (uint32_t)__popc(is_special16);
+            bits = (uint32_t)kPerThread + n_nz * (1u + (uint32_t)width) - n_sp * ((uint32_t)width - 1u);
+        } else {
+            count = load_thread_elems<WC>(a.in, first, a.n, v);
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j)
+                if (j < count) bits += (uint32_t)symbol_len(v[j], width, special);
+        }
         const uint32_t incl = wave_inclusive_scan(bits);
         if (lane == kWave - 1) wave_sum[wave] = incl;
         __syncthreads();
@@ -280,9 +305,22 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
             total += wave_sum[w];
         }
         // zero symbols are the zero bits the image already holds: only the others are written
+        if (packed) {
+            uint32_t extra = 0;  // bits beyond one per element, of the elements before the current one
+            while (nonzero) {
+                const uint32_t j = (uint32_t)__ffs((int)nonzero) - 1u;
+                nonzero &= nonzero - 1u;
+                const uint32_t w = j < 8u ? (j < 4u ? d[0] : d[1]) : (j < 12u ? d[2] : d[3]);
+                const uint32_t x = (w >> (8u * (j & 3u))) & 0xffu;
+                const bool sp = ((is_special16 >> j) & 1u) != 0u;
+                const uint32_t word = sp ? (1u | (((x >> (width - 1)) & 1u) << 2)) : (3u | ((x & payload_mask) << 2));
+                lds_put(buf, pos + j + extra, word);
+                extra += sp ? 2u : 1u + (uint32_t)width;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < kPerThread; ++j) {
-            if (j < count) {
+            if (!packed && j < count) {
                 const uint32_t x = v[j];
                 const bool is_special = special != 0u && (x & ((1u << (width - 1)) - 1u)) == special;
                 const uint32_t head = is_special ? (1u | (((x >> (width - 1)) & 1u) << 2)) : 3u;

@@ -99,6 +99,32 @@ def test_code_streams_match_oracle(lgn, n_bits, e):
         assert np.array_equal(back.cpu().numpy(), codes), n
 
 
+def test_code_streams_dense_empty_and_without_special(lgn):
+    """Byte codes at the two ends of the density range (every code non-zero: the longest run of the
+    encoder's per-thread loop; every code zero) and without a pruning threshold (two classes)."""
+    n_bits, e, m, s = 6, 3, 2, -14
+    f = lgn.upload_struct(lgn.LgnFpParams(n_bits, e, m, s, 0.0, 0, 0))
+    alpha = 3.1e-4
+    special = O.prefix_special_of_code(alpha, e, m, s)
+    rng = np.random.default_rng(77)
+    n = 9 * 4096 + 777
+    dense = rng.integers(1, 1 << n_bits, n, dtype=np.uint8)
+    dense[rng.random(n) < 0.4] = special
+    cases = [(dense, alpha), (np.zeros(n, np.uint8), alpha), (dense, None),
+             (np.where(rng.random(n) < 0.03, dense, 0).astype(np.uint8), alpha)]
+    for codes, a in cases:
+        p = lgn.upload_struct(lgn.LgnPruneParams(a, 0, 0.0, 0.0)) if a is not None else None
+        sp = special if a is not None else 0
+        d = to_dev(codes)
+        buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_CODE8, p, f)
+        got, t = host_stream(buf, table, n)
+        want, wt = O.prefix_encode(codes, sp, n_bits)
+        assert np.array_equal(t, wt)
+        assert np.array_equal(got, want)
+        back = lgn.lgn_prefix_decode(buf, table, n, lgn.LGN_OUT_CODE8, p, f)
+        assert np.array_equal(back.cpu().numpy(), codes)
+
+
 def test_no_special_class_and_small_capacity(lgn):
     a = pruned_like(5 * 4096, 3, SI.F32)
     d = to_dev(a)
