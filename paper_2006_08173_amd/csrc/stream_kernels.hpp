@@ -70,41 +70,54 @@ __device__ __forceinline__ uint32_t prune_bits(uint32_t bits, uint32_t w, uint32
     return a > alpha_bits ? bits : small;
 }
 
-// PACKED output of one 256-element tile.  Lane k < 8N assembles dword k of the tile's 32N-byte run
-// from the chunks that overlap bits [32k, 32k+32): chunk index c0 = 32k / 4N onwards, at most
-// `nchunks` = ceil((4N - 1 + 32) / 4N) of them (wave-uniform; 2 for FP6, 5 for FP2).  c0 and the bit
-// offset `sh` depend only on the lane and on N, so they are computed once per kernel.
+// PACKED output of one 256-element tile: lane i holds the 4N-bit chunk of its four codes, and the
+// tile's run of 32N bytes is the chunks end to end.  The lane in whose chunk a dword of the run
+// begins assembles that dword: the rest of its own chunk from bit `o` on, then the chunks of the
+// next one to three lanes.  Lanes fall into aligned groups of 8 / gcd(N, 8) whose chunks make up
+// whole dwords, so the neighbours a dword needs are in the same row of 16 lanes and come over
+// with row shifts (plain vector instructions, no LDS).  Everything here depends on the lane and
+// on N only and is computed once per kernel.
 struct PackLane {
-    int c0, sh, cb, nchunks, ndwords;
+    bool owns;        // a dword begins in this lane's chunk
+    uint32_t dword;   // its index in the tile's run
+    uint32_t o;       // first bit of it inside the chunk
+    uint32_t s1, s2, s3;  // left shifts of the chunks of lanes i+1, i+2, i+3 (32 or more: not part of it)
+    int neighbours;   // how many of them some lane needs (wave-uniform)
 };
 
 __device__ __forceinline__ PackLane pack_lane(int n_bits, int lane)
 {
     PackLane p;
-    p.cb = 4 * n_bits;
-    p.c0 = (32 * lane) / p.cb;
-    p.sh = 32 * lane - p.c0 * p.cb;
-    p.nchunks = (p.cb - 1 + 32 + p.cb - 1) / p.cb;
-    p.ndwords = 8 * n_bits;
+    const uint32_t cb = 4u * (uint32_t)n_bits, first = cb * (uint32_t)lane;
+    p.dword = (first + 31u) / 32u;
+    p.owns = 32u * p.dword < first + cb;
+    p.o = p.owns ? 32u * p.dword - first : 0u;
+    p.s1 = cb - p.o;
+    p.s2 = 2u * cb - p.o;
+    p.s3 = 3u * cb - p.o;
+    p.neighbours = n_bits <= 3 ? 3 : (n_bits == 5 ? 2 : (n_bits == 8 ? 0 : 1));
     return p;
+}
+
+// The value lane i + K of the same row of 16 holds (0 past the end of the row).
+template <int K>
+__device__ __forceinline__ uint32_t from_lane_above(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x100 + K, 0xf, 0xf, true);  // row_shl:K
 }
 
 __device__ __forceinline__ void pack_store_n(const PackLane &p, int lane, uint32_t chunk,
                                              uint8_t *tile_out, uint64_t bytes_valid)
 {
-    uint64_t acc = 0;
-#pragma unroll
-    for (int t = 0; t < 5; ++t) {
-        if (t < p.nchunks) {  // wave-uniform
-            const uint32_t v = __shfl(chunk, (p.c0 + t) & (kWave - 1));
-            acc |= (uint64_t)v << (t * p.cb);  // (nchunks - 1) * cb < 64 for every N in [2, 8]
-        }
-    }
-    const uint32_t dword = (uint32_t)(acc >> p.sh);
-    if (lane < p.ndwords) {
-        const uint64_t byte = 4ull * lane;
+    uint32_t dword = chunk >> p.o;
+    // 64-bit shifts: a shift of 32 or more leaves nothing in the low word
+    if (p.neighbours >= 1) dword |= (uint32_t)((uint64_t)from_lane_above<1>(chunk) << p.s1);
+    if (p.neighbours >= 2) dword |= (uint32_t)((uint64_t)from_lane_above<2>(chunk) << p.s2);
+    if (p.neighbours >= 3) dword |= (uint32_t)((uint64_t)from_lane_above<3>(chunk) << p.s3);
+    if (p.owns) {
+        const uint64_t byte = 4ull * p.dword;
         if (byte + 4 <= bytes_valid) {
-            __builtin_nontemporal_store(dword, reinterpret_cast<uint32_t *>(tile_out) + lane);
+            __builtin_nontemporal_store(dword, reinterpret_cast<uint32_t *>(tile_out) + p.dword);
         } else {
             for (uint64_t b = byte; b < bytes_valid; ++b)
                 tile_out[b] = (uint8_t)(dword >> (8 * (b - byte)));
