@@ -37,7 +37,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_BYTES = {
     # profiles/hot_path_c4_hbm_traffic.txt: FETCH_SIZE x 2.000 KiB + WRITE_SIZE x 1.000 KiB per launch
     ("c4", "code8", "stochastic", "stream_kernel (fused prune+quantize)"): int((401498.7 * 2.0 + 200704.0) * 1024),
-    ("c4", "code8", "stochastic", "stats_solve_kernel"): int((402626.6 * 2.0 + 96.2) * 1024),
+    ("c4", "code8", "stochastic", "stats_solve_kernel"): int((402623.7 * 2.0 + 96.2) * 1024),
 }
 
 
