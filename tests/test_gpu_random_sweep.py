@@ -102,3 +102,60 @@ class _as_tensor:
 
     def numpy(self):
         return self.a
+
+
+def test_random_sweep_of_statistics_and_parameters(lgn):
+    """Random sizes, element types, zero shares, special values and masks: counts and extrema exact,
+    mu and sigma to 1e-6; then threshold and format from the device's own statistics: the oracle's
+    bits for alpha, its (e, m, s)."""
+    import math
+    rng = np.random.default_rng(4242)
+    lgn_dtype = {SI.F32: lgn.LGN_F32, SI.BF16: lgn.LGN_BF16, SI.F16: lgn.LGN_F16}
+    odt = {SI.F32: O.F32, SI.BF16: O.BF16, SI.F16: O.F16}
+    for case in range(70):
+        dtype = (SI.F32, SI.BF16, SI.F16)[case % 3]
+        n = int(rng.choice([rng.integers(1, 3000), rng.integers(3000, 300_000), rng.integers(300_000, 3_000_000)]))
+        mu = float(rng.uniform(-14.0, -4.0)) if dtype != SI.F16 else float(rng.uniform(-9.0, -3.0))
+        sigma = float(rng.uniform(0.2, 3.0))
+        g = SI.lognormal_tensor(n, seed=int(rng.integers(0, 1 << 30)), mu=mu, sigma=sigma,
+                                zero_frac=float(rng.uniform(0.0, 0.7)), dtype=dtype)
+        if n > 50 and dtype != SI.F16 and rng.random() < 0.5:      # a few special bit patterns
+            v = g.view(np.uint32 if dtype == SI.F32 else np.uint16)
+            pos = rng.choice(n, 6, replace=False)
+            pats = (0x7FC00000, 0xFF800000, 0x00000001, 0x807FFFFF, 0x80000000, 0x7F7FFFFF) if dtype == SI.F32 \
+                else (0x7FC0, 0xFF80, 0x0001, 0x807F, 0x8000, 0x7F7F)
+            v[pos] = pats
+        d = to_dev(g)
+        mode = case % 4
+        if mode == 0:
+            mask = (rng.random(n) < 0.6).astype(np.uint8)
+            want = O.stats_masked(g, mask)
+            st = lgn.lgn_stats_masked(d, torch.from_numpy(mask).cuda(), dtype=lgn_dtype[dtype])
+        elif mode == 1:
+            mask = g.copy()
+            mask.view(np.uint16 if dtype != SI.F32 else np.uint32)[rng.random(n) < 0.4] = 0
+            want = O.stats_masked(g, mask)
+            st = lgn.lgn_stats_masked(d, to_dev(mask), dtype=lgn_dtype[dtype])
+        else:
+            want = O.stats(g)
+            st = lgn.lgn_stats(d, dtype=lgn_dtype[dtype])
+        got = lgn.read_stats(st)
+        ctx = (case, dtype, n, mode)
+        assert (got.n, got.nnz, got.n_nonfinite, got.status) == (want.n, want.nnz, want.n_nonfinite, want.status), ctx
+        assert np.float32(got.max_abs) == np.float32(want.max_abs), ctx
+        assert np.float32(got.min_abs_nz) == np.float32(want.min_abs_nz), ctx
+        if want.nnz == 0:
+            assert math.isnan(got.mu) and math.isnan(got.sigma), ctx
+            continue
+        assert abs(got.mu - want.mu) <= 1e-6 * abs(want.mu) + 1e-12, ctx
+        assert abs(got.sigma - want.sigma) <= 1e-6 * want.sigma + 1e-12, ctx
+        # parameters from identical inputs: the device's statistics handed to the oracle
+        same = O.make_stats(got.n, got.nnz, got.mu, got.sigma, got.max_abs, got.min_abs_nz, got.n_nonfinite, got.status)
+        target = float(rng.uniform(0.05, 0.99))
+        nb = int(rng.integers(2, 9))
+        wp, wf = O.threshold(same, target, odt[dtype]), O.fp_params(same, nb)
+        gp = lgn.read_prune_params(lgn.lgn_threshold(st, target, lgn_dtype[dtype]))
+        gf = lgn.read_fp_params(lgn.lgn_fp_params(st, nb))
+        assert np.float32(gp.alpha).view(np.uint32) == np.float32(wp.alpha).view(np.uint32), ctx
+        assert gp.status == wp.status, ctx
+        assert (gf.e_bits, gf.m_bits, gf.scale_exp, gf.status) == (wf.e_bits, wf.m_bits, wf.scale_exp, wf.status), ctx
