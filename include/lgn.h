@@ -306,7 +306,11 @@ int lgn_prefix_encode(const void *in, uint64_t n, int in_kind, int dtype, const 
                       void *stream);
 
 /* Inverse of lgn_prefix_encode: writes n elements (values of `dtype`, or one code per byte) to
- * out.  in_kind, dtype, *p and *f must be those of the encoding call.  One thread per chunk. */
+ * out.  in_kind, dtype, *p and *f must be those of the encoding call.  One thread per chunk.
+ * `in` must hold at least table[nchunks] words and `table` must be the table of that stream
+ * (entries ascending, table[c + 1] <= table[nchunks]): the call has no size of `in` to check the
+ * entries against, and reads the words [table[c], table[c + 1]) of every chunk.  Bits of the
+ * stream itself are not trusted: whatever they are, exactly n elements are written. */
 int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_kind, int dtype,
                       const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out, void *stream);
 
