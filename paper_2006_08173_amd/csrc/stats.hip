@@ -93,6 +93,12 @@ __device__ __forceinline__ void accumulate_careful(uint32_t bits, float pivot, L
 
 // Four elements per lane.  Returns the number of valid elements the fast path counted for the
 // whole wave (wave-uniform), 0 if the careful path was taken.
+// SUM4_F32: the four deviations and their squares are first summed in fp32 and enter the fp64
+// accumulators as two numbers instead of eight.  Used for the 16-bit element types, where the
+// pass is bound by arithmetic (twice the elements per byte): the three extra fp32 roundings per
+// sum are unbiased and of the size of the logarithm's own error (~1e-7 relative on a partial
+// sum of four), far inside the 1e-6 budget on mu and sigma.
+template <bool SUM4_F32 = false>
 __device__ __forceinline__ uint32_t accumulate_quad(uint32_t b0, uint32_t b1, uint32_t b2,
                                                     uint32_t b3, uint32_t pivot_bits, float pivot,
                                                     LaneAcc &t)
@@ -124,6 +130,11 @@ __device__ __forceinline__ uint32_t accumulate_quad(uint32_t b0, uint32_t b1, ui
                          (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(v3));
     t.mx = max(t.mx, qmx);
     t.nmn = max(t.nmn, qnmn);
+    if (SUM4_F32) {
+        t.s1 += (double)((f0 + f1) + (f2 + f3));
+        t.s2 += (double)__builtin_fmaf(f0, f0, __builtin_fmaf(f1, f1, __builtin_fmaf(f2, f2, f3 * f3)));
+        return cnt;
+    }
     const double d0 = (double)f0, d1 = (double)f1, d2 = (double)f2, d3 = (double)f3;
     t.s1 += d0; t.s2 = fma(d0, d0, t.s2);
     t.s1 += d1; t.s2 = fma(d1, d1, t.s2);
@@ -143,8 +154,8 @@ __device__ __forceinline__ uint32_t accumulate_vec(uint4 v, uint32_t pivot_bits,
     widen_pair<DTYPE>(v.y, e[2], e[3]);
     widen_pair<DTYPE>(v.z, e[4], e[5]);
     widen_pair<DTYPE>(v.w, e[6], e[7]);
-    return accumulate_quad(e[0], e[1], e[2], e[3], pivot_bits, pivot, t) +
-           accumulate_quad(e[4], e[5], e[6], e[7], pivot_bits, pivot, t);
+    return accumulate_quad<true>(e[0], e[1], e[2], e[3], pivot_bits, pivot, t) +
+           accumulate_quad<true>(e[4], e[5], e[6], e[7], pivot_bits, pivot, t);
 }
 
 template <typename T>
