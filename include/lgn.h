@@ -204,8 +204,9 @@ int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, 
 
 /*
  * Threshold alpha such that stochastic pruning leaves a fraction `target_sparsity` of the WHOLE
- * tensor at zero (Section 5.1: "find alpha that induces sparsity S"; closed form of Section 5.2;
- * existing zeros are credited as in Appendix "Algorithm for bi-Modal lognormal pruning", step 2).
+ * tensor at zero (Section 5.1 poses the problem: the alpha that induces a given sparsity; closed
+ * form of Section 5.2; existing zeros are credited as in Appendix "Algorithm for bi-Modal lognormal
+ * pruning", step 2).
  *   st              device, read
  *   target_sparsity in [0, 1)
  *   alpha_dtype     LGN_F32, LGN_BF16 or LGN_F16: alpha is rounded to this type (it is compared with,
