@@ -143,8 +143,9 @@ def bench_c3(args, lgn, SI, torch, np):
 def main():
     args = parse()
     if args.gpus != 1:
-        sys.exit("bench.py: this build measures one GPU only (the path needs no communication; "
-                 "see DESIGN.md for how it would shard). Run with --gpus 1.")
+        sys.exit("bench.py: this build measures one GPU only (gradients are local to a data-parallel rank, "
+                 "so the path needs no communication and every rank would run it on its own tensors). "
+                 "Run with --gpus 1.")
     import numpy as np
     import torch
 

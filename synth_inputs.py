@@ -133,7 +133,7 @@ def bimodal_pair(n, *, seed, left_frac, mu_right, sigma_right, mu_left, sigma_le
 
 
 # ---------------------------------------------------------------------------------------------
-# The benchmark configurations (sizes, distributions and work) of the benchmark spec `configs`.
+# The five benchmark configurations (sizes, distributions and work).
 # `seed` is the data seed; `rng_seed` keys the random words the pruning / rounding steps draw.
 # ---------------------------------------------------------------------------------------------
 
