@@ -75,8 +75,8 @@ def log(*a):
 
 
 def bench_c3(args, lgn, SI, torch, np):
-    """Twenty tensors with ResNet-18 activation-gradient shapes, twenty whole chains back to back on
-    one stream (no host synchronisation in between): total algorithmic bytes / total time."""
+    """Twenty tensors with ResNet-18 activation-gradient shapes, twenty whole chains dealt round-robin
+    to a few streams (no host synchronisation in between): total algorithmic bytes / total time."""
     tensors = SI.config_c3()
     rounding = lgn.LGN_ROUND_STOCHASTIC if args.rounding == "stochastic" else lgn.LGN_ROUND_NEAREST_EVEN
     items = []

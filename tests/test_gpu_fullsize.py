@@ -1,7 +1,7 @@
 """Parity at the full sizes of the benchmark configurations, in the launch configuration the
 benchmark times (default grid sizes, fast tile path), and at sizes beyond 2^32 elements.
 
-The machine's host cores run the oracle over whole tensors in seconds, so configurations 2, 4 and 5
+The machine's host cores run the oracle over whole tensors in seconds, so configurations 2, 3, 4 and 5
 are compared element by element; the 4.3-billion-element case is compared on windows the oracle
 computes with the matching element offset."""
 import math
@@ -220,3 +220,47 @@ def test_prefix_code_at_full_size(lgn):
     assert np.array_equal(buf[: int(t[-2]) * 4].cpu().numpy(), want)
     assert torch.equal(lgn.lgn_prefix_decode(buf, table, g.size, lgn.LGN_OUT_CODE8, p, f), codes)
     assert want.size * 8 / g.size < 2.2                   # against 6 bits per value packed
+
+
+def test_config3_twenty_tensors_on_three_streams(lgn):
+    """Configuration 3 as the benchmark runs it: twenty tensors (6.4 M to 205.5 M elements, 2.5 GB in
+    all), each with its own statistics, threshold and format, dealt round-robin to three streams with
+    a workspace each, two launches per tensor, the whole sweep issued twice without a host
+    synchronisation in between.  Every tensor's statistics agree with the oracle, its parameters are
+    the oracle's for those statistics, and all of its codes are the oracle's."""
+    tensors = SI.config_c3()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    wss = []
+    for _ in streams:
+        w = torch.empty(lgn.lgn_workspace_bytes(0, lgn.LGN_F32), dtype=torch.uint8, device="cuda")
+        lgn.lgn_workspace_init(w)
+        wss.append(w)
+    items = []
+    for cfg in tensors:
+        g, d = upload(cfg)
+        items.append(dict(cfg=cfg, g=g, d=d, out=torch.empty(cfg["n"], dtype=torch.uint8, device="cuda"),
+                          st=torch.empty(72, dtype=torch.uint8, device="cuda"),
+                          pp=torch.empty(24, dtype=torch.uint8, device="cuda"),
+                          fp=torch.empty(32, dtype=torch.uint8, device="cuda")))
+    torch.cuda.synchronize()
+    for _ in range(2):
+        for i, it in enumerate(items):
+            c = it["cfg"]
+            with torch.cuda.stream(streams[i % 3]):
+                lgn.lgn_stats_solve(it["d"], c["sparsity"], lgn.LGN_F32, c["n_bits"], st=it["st"], p=it["pp"],
+                                    f=it["fp"], ws=wss[i % 3])
+                lgn.lgn_prune_quantize_fused(it["d"], it["pp"], it["fp"], O.ROUND_STOCHASTIC, c["rng_seed"], 0,
+                                             out=it["out"], out_kind=O.OUT_CODE8)
+    torch.cuda.synchronize()
+    for it in items:
+        c, g = it["cfg"], it["g"]
+        hs, hp, hf = lgn.read_stats(it["st"]), lgn.read_prune_params(it["pp"]), lgn.read_fp_params(it["fp"])
+        stats_close(hs, O.stats(g))
+        same_in = oracle_stats_like(hs)
+        op, of = O.threshold(same_in, c["sparsity"]), O.fp_params(same_in, c["n_bits"])
+        assert np.float32(hp.alpha) == np.float32(op.alpha), c["name"]
+        assert (hf.e_bits, hf.m_bits, hf.scale_exp) == (of.e_bits, of.m_bits, of.scale_exp), c["name"]
+        want = O.prune_quantize(g, hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp, O.ROUND_STOCHASTIC,
+                                c["rng_seed"], 0, O.OUT_CODE8)
+        assert np.array_equal(it["out"].cpu().numpy(), want), c["name"]
+        it["g"] = None
