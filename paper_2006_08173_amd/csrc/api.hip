@@ -108,7 +108,8 @@ int resident_blocks()
 
 // Workgroups of the statistics pass.  Read-only streaming likes few, long-lived waves: for fp32
 // two workgroups per CU (each wave keeps 8 KiB in flight) measured best, 6.3 TB/s against 5.9 at
-// four; bf16 has twice the arithmetic per byte and wants four.  Fewer workgroups also mean fewer
+// four; the 16-bit types have twice the arithmetic per byte and want six (10^9 bf16 elements:
+// 0.398 / 0.365 / 0.348 / 0.341 / 0.335 ms at 2 / 3 / 4 / 6 / 8).  Fewer workgroups also mean fewer
 // per-block records for the combine step.
 int stats_blocks_cap(int dtype)
 {
@@ -126,7 +127,7 @@ int stats_blocks_cap(int dtype)
             if (w >= 1 && w <= 8) env_per_cu = w;
         }
     }
-    const int per_cu = env_per_cu ? env_per_cu : (dtype == LGN_F32 ? 2 : 4);
+    const int per_cu = env_per_cu ? env_per_cu : (dtype == LGN_F32 ? 2 : 6);
     const int blocks = cus * per_cu;
     return blocks > 2048 ? 2048 : blocks;
 }
