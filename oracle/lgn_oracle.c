@@ -15,11 +15,16 @@
  *
  * Conventions the paper leaves open (all listed in the design document):
  *   - statistics use the population standard deviation over finite non-zero entries;
- *   - the uniform variable of stochastic pruning lives on a 23-bit midpoint grid,
- *     u = (k + 1/2) / 2^23 with k the top 23 bits of the random word, so 0 < u < 1, and the
- *     comparison value alpha*u is one IEEE single-precision product;
  *   - random words come from Philox4x32-10 (Salmon et al., SC'11) keyed by the 64-bit seed, with
- *     counter (lo32(j>>2), hi32(j>>2), purpose, 0) and word index j&3 for global element j;
+ *     counter (lo32(j>>2), hi32(j>>2), 0, 0) and word index j&3 for global element j: one 32-bit
+ *     word per element, whose upper half drives stochastic pruning and whose lower half drives
+ *     stochastic rounding (independent bits of one uniform word);
+ *   - the uniform variable of stochastic pruning lives on a 16-bit midpoint grid,
+ *     u = (k + 1/2) / 2^16 with k the upper 16 bits of the element's word, so 0 < u < 1, and the
+ *     comparison value alpha*u is one IEEE single-precision product;
+ *   - stochastic rounding goes up iff (cut-off part) + (r + 1/2) / 2^16 spacings reach one
+ *     spacing, r the lower 16 bits of the element's word: the up-probability is the cut-off
+ *     fraction rounded to the nearest multiple of 2^-16 (exact for 16-bit element types);
  *   - an FP(1,e,m) word has exponent field c in [1, 2^e-1] meaning E = c - 2^(e-1), field 0 is
  *     zero; saturation goes to the largest finite code; underflow flushes to zero and is decided
  *     on the exponent before rounding.
@@ -35,7 +40,7 @@
  * enumeration of all FP-n codes for the quantizer; exact results on powers of two for the
  * statistics; the code table of the appendix, an independent string decoder and the paper's
  * bits-per-value claim for the prefix code.  Parity unpinned (pure conventions): the 0.997 default quantile of the scale rule,
- * the tie rule of nearest rounding, the 23-bit midpoint grid of u.
+ * the tie rule of nearest rounding, the 16-bit midpoint grids of the two random variables.
  */
 #include <float.h>
 #include <math.h>
@@ -447,11 +452,11 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-/* The word that global element j draws for a purpose (0 = pruning, 1 = rounding). */
-uint32_t orc_random_word(uint64_t seed, uint64_t j, uint32_t purpose)
+/* The word of global element j: upper half for the pruning variable, lower half for rounding. */
+uint32_t orc_random_word(uint64_t seed, uint64_t j)
 {
     uint64_t q = j >> 2;
-    uint32_t ctr[4] = { (uint32_t)q, (uint32_t)(q >> 32), purpose, 0u };
+    uint32_t ctr[4] = { (uint32_t)q, (uint32_t)(q >> 32), 0u, 0u };
     uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
     uint32_t w[4];
     orc_philox4x32_10(ctr, key, w);
@@ -461,7 +466,7 @@ uint32_t orc_random_word(uint64_t seed, uint64_t j, uint32_t purpose)
 /* ==========================================================================================
  * Step 4.  Stochastic pruning T_{alpha,eps} (Section "Stochastic pruning", the three-case
  * definition):  |x| > alpha -> x;  alpha eps <= |x| <= alpha -> sign(x) alpha;
- * |x| < alpha eps -> 0.   eps = u = ((w >> 9) + 1/2) / 2^23 and alpha*u is one single-precision product.
+ * |x| < alpha eps -> 0.   eps = u = ((w >> 16) + 1/2) / 2^16 and alpha*u is one single-precision product.
  * Exact zeros stay zero whatever u is, NaN passes through.
  * ========================================================================================== */
 static float prune_one(float x, float alpha, uint32_t w)
@@ -470,7 +475,7 @@ static float prune_one(float x, float alpha, uint32_t w)
     float a = fabsf(x);
     if (a == 0.0f) return 0.0f;
     if (a > alpha) return x;
-    double u = ((double)(w >> 9) + 0.5) / 8388608.0; /* 23-bit midpoint grid, 0 < u < 1 */
+    double u = ((double)(w >> 16) + 0.5) / 65536.0; /* 16-bit midpoint grid, 0 < u < 1 */
     float t = (float)((double)alpha * u);             /* exact product, one rounding to single */
     if (a < t) return 0.0f;
     return copysignf(alpha, x);
@@ -483,7 +488,7 @@ void orc_prune(const void *g, uint64_t n, int dtype, float alpha, uint64_t seed,
 #pragma omp parallel for num_threads(g_threads)
     for (i = 0; i < N; ++i) {
         float x = load_elem(g, (uint64_t)i, dtype);
-        uint32_t w = orc_random_word(seed, elem_offset + (uint64_t)i, 0u);
+        uint32_t w = orc_random_word(seed, elem_offset + (uint64_t)i);
         float y = prune_one(x, alpha, w);
         if (dtype == ORC_F32) ((float *)out)[i] = y; /* keeps NaN payloads */
         else if (isnan(y)) ((uint16_t *)out)[i] = ((const uint16_t *)g)[i];
@@ -516,7 +521,8 @@ static uint32_t quantize_one(float x, int e, int m, int s, int rounding, uint32_
     double unit = ldexp(1.0, 23 - m);
     int up;
     if (rounding == ORC_ROUND_STOCHASTIC) {
-        double r = (double)(w >> (9 + m));
+        /* (r + 1/2) / 2^16 of a spacing, r the lower half of the element's word */
+        double r = ((double)(w & 0xffffu) + 0.5) / 65536.0 * unit;
         up = f + r >= unit;
     } else {
         uint32_t code_below = ((uint32_t)(E + emax) << m) | (uint32_t)k;
@@ -592,8 +598,8 @@ static void quantize_impl(const void *g, uint64_t n, int dtype, int do_prune, fl
     for (i = 0; i < N; ++i) {
         uint64_t j = elem_offset + (uint64_t)i;
         float x = load_elem(g, (uint64_t)i, dtype);
-        if (do_prune) x = prune_one(x, alpha, orc_random_word(seed, j, 0u));
-        uint32_t w = rounding == ORC_ROUND_STOCHASTIC ? orc_random_word(seed, j, 1u) : 0u;
+        uint32_t w = orc_random_word(seed, j); /* upper half prunes, lower half rounds */
+        if (do_prune) x = prune_one(x, alpha, w);
         uint32_t code = quantize_one(x, e, m, s, rounding, w);
         emit(out, (uint64_t)i, dtype, out_kind, g, x, code, e, m, s, codes);
     }
@@ -608,7 +614,8 @@ void orc_fp_quantize(const void *g, uint64_t n, int dtype, int e, int m, int s, 
                   scratch_codes);
 }
 
-/* Step 6 (composition): prune, then quantize what pruning returned, with independent words. */
+/* Step 6 (composition): prune, then quantize what pruning returned; the two decisions of an
+ * element use disjoint halves of its word. */
 void orc_prune_quantize(const void *g, uint64_t n, int dtype, float alpha, int e, int m, int s,
                         int rounding, uint64_t seed, uint64_t elem_offset, void *out, int out_kind,
                         uint8_t *scratch_codes)
@@ -921,6 +928,17 @@ void orc_sparsity_allocate(const orc_stats_t *stats, const uint64_t *hists, int 
  * threshold was below the format's range.  A floor below the normal range of the element type
  * cannot be expressed and is dropped.
  * ------------------------------------------------------------------------------------------ */
+/* Composition of the two operators (pruning first, then the quantizer of Section 4.1): every
+ * survivor of pruning with magnitude at most alpha comes out as +-alpha, and the quantizer sends a
+ * magnitude below 2^(E_min + s), E_min = 1 - 2^(e-1), to zero.  So when 0 < alpha < 2^(E_min + s)
+ * everything pruning touched is lost; that condition is reported as status bit 16 of the pruning
+ * parameters.  Returns 1 if it holds. */
+int orc_alpha_below_fp_range(float alpha, int e_bits, int scale_exp)
+{
+    const int emin = 1 - (1 << (e_bits - 1));
+    return alpha > 0.0f && (double)alpha < ldexp(1.0, emin + scale_exp);
+}
+
 void orc_threshold_floor(int e_bits, int scale_exp, const orc_prune_params_t *in, int alpha_dtype,
                          orc_prune_params_t *out)
 {

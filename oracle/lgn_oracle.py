@@ -75,7 +75,7 @@ def lib():
         L.orc_expected_relative_error.restype = dbl
         L.orc_fp_params.argtypes = [C.POINTER(Stats), i32, i32, i32, dbl, i32, C.POINTER(FpParams)]
         L.orc_philox4x32_10.argtypes = [C.POINTER(u32), C.POINTER(u32), C.POINTER(u32)]
-        L.orc_random_word.argtypes = [u64, u64, u32]
+        L.orc_random_word.argtypes = [u64, u64]
         L.orc_random_word.restype = u32
         L.orc_prune.argtypes = [vp, u64, i32, f32, u64, u64, vp]
         L.orc_decode.argtypes = [u32, i32, i32, i32]
@@ -104,6 +104,8 @@ def lib():
         L.orc_float_to_f16.argtypes = [f32]
         L.orc_float_to_f16.restype = C.c_uint16
         L.orc_threshold_floor.argtypes = [i32, i32, vp, i32, vp]
+        L.orc_alpha_below_fp_range.argtypes = [f32, i32, i32]
+        L.orc_alpha_below_fp_range.restype = i32
         L.orc_prefix_chunks.argtypes = [u64]
         L.orc_prefix_chunks.restype = u64
         L.orc_prefix_bound_bytes.argtypes = [u64, i32]
@@ -199,8 +201,8 @@ def philox4x32_10(ctr, key):
     return [int(x) for x in o]
 
 
-def random_word(seed, j, purpose) -> int:
-    return int(lib().orc_random_word(int(seed), int(j), int(purpose)))
+def random_word(seed, j) -> int:
+    return int(lib().orc_random_word(int(seed), int(j)))
 
 
 def prune(g: np.ndarray, alpha: float, seed: int, elem_offset: int = 0) -> np.ndarray:
@@ -392,6 +394,11 @@ def threshold_floor(e_bits: int, scale_exp: int, p_in: PruneParams = None, alpha
     lib().orc_threshold_floor(int(e_bits), int(scale_exp), C.byref(p_in) if p_in is not None else None,
                               int(alpha_dtype), C.byref(out))
     return out
+
+
+def alpha_below_fp_range(alpha: float, e_bits: int, scale_exp: int) -> bool:
+    """True if every survivor of pruning (+-alpha) would be flushed by the quantizer."""
+    return bool(lib().orc_alpha_below_fp_range(np.float32(alpha), int(e_bits), int(scale_exp)))
 
 
 def f16_to_float(h: int) -> float:

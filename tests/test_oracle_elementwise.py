@@ -88,9 +88,9 @@ def test_stats_special_values_and_bf16():
 # ----------------------------------------------------------------------- stochastic pruning
 def test_prune_three_cases_by_hand():
     alpha = np.float32(1.0)
-    w_of_k = lambda k: int(k) << 9            # u = (k + 1/2) / 2^23
-    half = w_of_k(1 << 22)                    # u = 0.5 + 2^-24
-    u_half = np.float32(0.5 + 2.0 ** -24)
+    w_of_k = lambda k: int(k) << 16           # u = (k + 1/2) / 2^16
+    half = w_of_k(1 << 15)                    # u = 0.5 + 2^-17
+    u_half = np.float32(0.5 + 2.0 ** -17)
     assert O.prune_one(1.5, alpha, half) == 1.5            # above: untouched
     assert O.prune_one(-1.5, alpha, half) == -1.5
     assert O.prune_one(1.0, alpha, half) == 1.0            # |x| = alpha -> sign * alpha = x
@@ -100,13 +100,15 @@ def test_prune_three_cases_by_hand():
     assert O.prune_one(0.5, alpha, half) == 0.0            # just below alpha*u
     assert O.prune_one(0.25, alpha, half) == 0.0           # |x| < alpha*u
     assert O.prune_one(-0.25, alpha, half) == 0.0
-    # zeros stay zeros for the smallest u; the low 9 bits of the word are not used
+    # zeros stay zeros for the smallest u; the low 16 bits of the word (the rounding variable) are not used
     assert O.prune_one(0.0, alpha, 0) == 0.0
     assert O.prune_one(-0.0, alpha, 0) == 0.0 and not math.copysign(1, O.prune_one(-0.0, alpha, 0)) < 0
-    assert O.prune_one(0.25, alpha, half | 0x1FF) == 0.0
-    assert O.prune_one(2.0 ** -24, alpha, 0) == 1.0        # smallest u = 2^-24
-    assert O.prune_one(2.0 ** -25, alpha, 0) == 0.0        # u is never 0: tiny values can vanish
-    assert O.prune_one(1.0 - 2.0 ** -24, alpha, 0xFFFFFFFF) == 1.0   # largest u = 1 - 2^-24
+    assert O.prune_one(0.25, alpha, half | 0xFFFF) == 0.0
+    assert O.prune_one(u_half, alpha, half | 0xFFFF) == 1.0
+    assert O.prune_one(2.0 ** -17, alpha, 0) == 1.0        # smallest u = 2^-17
+    assert O.prune_one(2.0 ** -18, alpha, 0) == 0.0        # u is never 0: tiny values can vanish
+    assert O.prune_one(1.0 - 2.0 ** -17, alpha, 0xFFFFFFFF) == 1.0   # largest u = 1 - 2^-17
+    assert O.prune_one(np.nextafter(np.float32(1.0 - 2.0 ** -17), np.float32(0)), alpha, 0xFFFFFFFF) == 0.0
     assert math.isnan(O.prune_one(float("nan"), alpha, half))
     assert O.prune_one(float("inf"), alpha, half) == float("inf")
     # alpha = 0 prunes nothing
@@ -116,13 +118,13 @@ def test_prune_three_cases_by_hand():
 def test_prune_threshold_product_is_single_precision():
     """alpha * u is rounded once to fp32 before the comparison."""
     alpha = np.float32(1.0 + 2.0 ** -23)
-    k = (1 << 23) - 1
-    u = (k + 0.5) / 2.0 ** 23
+    k = (1 << 16) - 1
+    u = (k + 0.5) / 2.0 ** 16
     t = np.float32(np.float64(alpha) * u)                   # exact product rounded once
     assert float(t) != float(np.float64(alpha) * u)         # the product really needs rounding
     below = np.nextafter(t, np.float32(0))
-    assert O.prune_one(t, alpha, k << 9) == alpha
-    assert O.prune_one(below, alpha, k << 9) == 0.0
+    assert O.prune_one(t, alpha, k << 16) == alpha
+    assert O.prune_one(below, alpha, k << 16) == 0.0
 
 
 def test_prune_outputs_sparsity_and_mean():
@@ -154,15 +156,14 @@ def test_prune_outputs_sparsity_and_mean():
 
 
 def test_prune_keep_probability_exact():
-    """Over the 2^23 grid values of u, P(keep) = |x|/alpha up to the grid; check on a sample."""
+    """Over ALL 2^16 grid values of u, P(keep) = |x|/alpha rounded to the grid."""
     alpha, x = np.float32(0.8), np.float32(0.3)
-    ks = np.arange(0, 1 << 23, 2053)
-    kept = sum(O.prune_one(x, alpha, int(k) << 9) != 0 for k in ks)
-    assert kept / ks.size == pytest.approx(0.3 / 0.8, abs=2e-3)
+    kept = sum(O.prune_one(x, alpha, k << 16) != 0 for k in range(1 << 16))
+    assert abs(kept - float(x) / float(alpha) * 2 ** 16) <= 1.0
     # threshold index: kept iff alpha*u <= x
-    k_star = int(math.floor(float(x) / float(alpha) * 2 ** 23))
-    assert O.prune_one(x, alpha, (k_star - 2) << 9) != 0
-    assert O.prune_one(x, alpha, (k_star + 2) << 9) == 0
+    k_star = int(math.floor(float(x) / float(alpha) * 2 ** 16))
+    assert O.prune_one(x, alpha, (k_star - 2) << 16) != 0
+    assert O.prune_one(x, alpha, (k_star + 2) << 16) == 0
 
 
 def test_prune_elem_offset_and_bf16():
@@ -269,17 +270,23 @@ def test_stochastic_rounding_against_enumeration(e, m):
         f = (xd - lo_v) / step * 2 ** nbits
         assert f == int(f)
         f = int(f)
-        # r is the top (23-m) bits of the word; up iff f + r >= 2^(23-m)
-        for r in (0, 1, (1 << nbits) - f - 1, (1 << nbits) - f, (1 << nbits) - 1):
-            if r < 0 or r >= (1 << nbits):
+        # r is the lower half of the word; up iff f / 2^nbits + (r + 1/2) / 2^16 >= 1, i.e. (exact
+        # integers) iff  f * 2^17 + (2 r + 1) * 2^nbits >= 2^(nbits + 17)
+        r_star = ((1 << (nbits + 17)) - f * (1 << 17) - (1 << nbits) + (1 << (nbits + 1)) - 1) >> (nbits + 1)
+        for r in (0, 1, r_star - 1, r_star, r_star + 1, 0xFFFF):
+            if r < 0 or r > 0xFFFF:
                 continue
-            w = (r << (9 + m)) | 0x1FF
+            w = r | 0xFFFF0000                  # the upper half (pruning variable) is not used
             val = O.decode(O.quantize_one(x, e, m, s, O.ROUND_STOCHASTIC, w), e, m, s)
-            up = f + r >= (1 << nbits)
+            up = f * (1 << 17) + (2 * r + 1) * (1 << nbits) >= (1 << (nbits + 17))
+            assert up == (r >= r_star)
             if up:
                 assert val == (hi_v if hi_v is not None else pos[-1])
             else:
                 assert val == lo_v
+        # the up-probability over all 2^16 values of r is the cut-off fraction rounded to the grid
+        ups = (1 << 16) - min(max(r_star, 0), 1 << 16)
+        assert abs(ups - f / 2 ** nbits * 2 ** 16) <= 0.5
         # exactly representable values never move
         assert O.decode(O.quantize_one(np.float32(lo_v), e, m, s, O.ROUND_STOCHASTIC, 0xFFFFFFFF),
                         e, m, s) == lo_v
@@ -445,3 +452,48 @@ def test_stochastic_underflow_keeps_the_mean_where_flushing_loses_it():
         keep = float(np.mean(y != 0))
         assert abs(keep - frac) < 5 * math.sqrt(frac * (1 - frac) / n) + 1e-6
         assert abs(float(y.mean()) - frac * floor) < 6 * floor * math.sqrt(frac * (1 - frac) / n) + 1e-12
+
+
+# --------------------------------------------------- random-variable grids, composition status
+@pytest.mark.parametrize("e,m", [(4, 1), (3, 2), (5, 0)])
+def test_stochastic_rounding_probability_is_exact_for_16_bit_inputs(e, m):
+    """A bf16 value has 7 - m cut-off bits: over all 2^16 values of the rounding variable the number
+    of round-ups is exactly (cut-off fraction) * 2^16 (brute force over the whole grid)."""
+    s = -3
+    for bits in (0x3E13, 0x3DFF, 0x3E80, 0x3D55, 0xBE2B):          # bf16 patterns inside the range
+        x = SI.bf16_bits_to_f32(np.array([bits], np.uint16))[0]
+        lo_code = O.quantize_one(x, e, m, s, O.ROUND_STOCHASTIC, 0)       # r = 0 never goes up ...
+        lo_v = O.decode(lo_code, e, m, s)
+        ups = sum(O.quantize_one(x, e, m, s, O.ROUND_STOCHASTIC, r) != lo_code for r in range(1 << 16))
+        spacing = 2.0 ** (math.floor(math.log2(abs(float(x)))) - m)
+        frac = (abs(float(x)) - abs(lo_v)) / spacing                      # exact in binary
+        assert ups == frac * 2 ** 16
+        if frac == 0:
+            assert O.quantize_one(x, e, m, s, O.ROUND_STOCHASTIC, 0xFFFF) == lo_code
+
+
+def test_pruning_and_rounding_use_disjoint_halves_of_the_word():
+    """The pruning decision depends on the upper half only, the rounding decision on the lower half."""
+    alpha, x = np.float32(0.8), np.float32(0.3)
+    for w in (0x00000000, 0x5A5A0000, 0x60000000, 0xFFFF0000):
+        assert all(O.prune_one(x, alpha, w | lo) == O.prune_one(x, alpha, w) for lo in (1, 0x8000, 0xFFFF))
+    for w in (0x0000, 0x1234, 0x8000, 0xFFFF):
+        assert all(O.quantize_one(0.3, 3, 2, 0, O.ROUND_STOCHASTIC, w | (hi << 16)) ==
+                   O.quantize_one(0.3, 3, 2, 0, O.ROUND_STOCHASTIC, w) for hi in (1, 0x8000, 0xFFFF))
+
+
+def test_alpha_below_fp_range_is_where_the_quantizer_flushes_alpha():
+    """Pruning turns every survivor at or below alpha into +-alpha; the flag must be set exactly when
+    the quantizer (pinned by enumeration above) sends alpha itself to code 0."""
+    for e, m, s in ((3, 2, -14), (2, 1, 0), (5, 2, -30), (4, 1, 7), (1, 6, -5), (7, 0, -60)):
+        edge = np.float32(2.0 ** (1 - 2 ** (e - 1) + s))           # smallest representable magnitude
+        below = np.nextafter(edge, np.float32(0))
+        above = np.nextafter(edge, np.float32(1e30))
+        assert O.alpha_below_fp_range(below, e, s) is True
+        assert O.alpha_below_fp_range(edge, e, s) is False
+        assert O.alpha_below_fp_range(above, e, s) is False
+        assert O.alpha_below_fp_range(0.0, e, s) is False          # no pruning: nothing to lose
+        for a in (below, edge, above, np.float32(edge * 0.01), np.float32(edge * 37.0)):
+            for rounding, w in ((O.ROUND_NEAREST_EVEN, 0), (O.ROUND_STOCHASTIC, 0xFFFFFFFF)):
+                flushed = O.quantize_one(a, e, m, s, rounding, w) == 0
+                assert flushed == O.alpha_below_fp_range(a, e, s)

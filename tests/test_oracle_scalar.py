@@ -32,23 +32,26 @@ def test_philox_known_answers(ctr, key, want):
 
 
 def test_random_word_layout():
-    """Word of element j = output[j & 3] of the block with counter (lo(j>>2), hi(j>>2), p, 0)."""
+    """Word of element j = output[j & 3] of the block with counter (lo(j>>2), hi(j>>2), 0, 0)."""
     seed = 0x0123456789ABCDEF
     for j in (0, 1, 2, 3, 4, 7, 12345, (1 << 34) + 5, (1 << 40) + 2):
-        for p in (0, 1):
-            q = j >> 2
-            blk = O.philox4x32_10([q & 0xFFFFFFFF, q >> 32, p, 0],
-                                  [seed & 0xFFFFFFFF, seed >> 32])
-            assert O.random_word(seed, j, p) == blk[j & 3]
+        q = j >> 2
+        blk = O.philox4x32_10([q & 0xFFFFFFFF, q >> 32, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        assert O.random_word(seed, j) == blk[j & 3]
 
 
 def test_random_words_look_uniform():
-    w = np.array([O.random_word(7, j, 0) for j in range(20000)], dtype=np.uint64)
-    u = (w >> 8).astype(np.float64) / 2 ** 24
-    assert abs(u.mean() - 0.5) < 5 * math.sqrt(1 / 12 / u.size)
-    assert sps.kstest(u, "uniform").pvalue > 1e-4
-    # the two purposes are different streams
-    w1 = np.array([O.random_word(7, j, 1) for j in range(2000)], dtype=np.uint64)
+    w = np.array([O.random_word(7, j) for j in range(20000)], dtype=np.uint64)
+    # the two halves of a word (pruning variable, rounding variable) are each uniform ...
+    for half in (w >> 16, w & 0xFFFF):
+        u = (half.astype(np.float64) + 0.5) / 2 ** 16
+        assert abs(u.mean() - 0.5) < 5 * math.sqrt(1 / 12 / u.size)
+        assert sps.kstest(u, "uniform").pvalue > 1e-4
+    # ... and uncorrelated with each other
+    a, b = (w >> 16).astype(np.float64), (w & 0xFFFF).astype(np.float64)
+    assert abs(np.corrcoef(a, b)[0, 1]) < 5 / math.sqrt(w.size)
+    # another seed is another stream
+    w1 = np.array([O.random_word(8, j) for j in range(2000)], dtype=np.uint64)
     assert (w1 != w[:2000]).mean() > 0.99
 
 
