@@ -35,10 +35,11 @@
  *     spread, nothing to prune, ...) cannot be reported synchronously and are written to the
  *     `status` bit field of the device structs.
  *   - Random words: Philox4x32-10 keyed by `seed`.  Global element j = elem_offset + i draws word
- *     (j & 3) of the block with counter (lo32(j>>2), hi32(j>>2), purpose, 0), purpose 0 for the
- *     pruning variable and 1 for stochastic rounding.  Because the counter is the global index,
- *     processing a tensor in several calls with the matching elem_offset gives the same bits as
- *     one call.
+ *     (j & 3) of the block with counter (lo32(j>>2), hi32(j>>2), 0, 0).  The upper 16 bits of that
+ *     word are the element's pruning variable, the lower 16 bits its rounding variable, so
+ *     lgn_prune followed by lgn_fp_quantize with the same seed and offset draws what
+ *     lgn_prune_quantize_fused draws.  Because the counter is the global index, processing a
+ *     tensor in several calls with the matching elem_offset gives the same bits as one call.
  */
 #ifndef LGN_H
 #define LGN_H
@@ -66,7 +67,7 @@ extern "C" {
 
 /* rounding of the mantissa */
 #define LGN_ROUND_NEAREST_EVEN 0 /* ties to the even FP-n code          */
-#define LGN_ROUND_STOCHASTIC 1   /* up with probability (cut-off part)/(spacing) */
+#define LGN_ROUND_STOCHASTIC 1   /* up with probability (cut-off part)/(spacing), on a 2^-16 grid */
 
 /* what a quantizing call writes */
 #define LGN_OUT_VALUE 0  /* n elements of the input dtype holding 2^s * q                     */
@@ -88,8 +89,16 @@ extern "C" {
 #define LGN_ST_SIGMA0 2u           /* all finite non-zero magnitudes are equal                 */
 #define LGN_ST_NOTHING_TO_PRUNE 4u /* existing zeros already reach the target: alpha = 0       */
 #define LGN_ST_NOT_CONVERGED 8u    /* the threshold solve hit its iteration limit              */
-#define LGN_ST_ALPHA_BELOW_FP_RANGE 16u /* reserved                                           */
-#define LGN_ST_HAS_NONFINITE 32u   /* Inf / NaN entries were seen (and skipped)                */
+#define LGN_ST_ALPHA_BELOW_FP_RANGE 16u /* pruning params only: 0 < alpha < 2^(E_min + s), the smallest
+                                           magnitude of the format the threshold is used with, so the
+                                           quantizer flushes every +-alpha pruning produces.  Set by
+                                           lgn_stats_solve (it computes both) and by
+                                           lgn_threshold_floor (which then raises alpha); lgn_threshold
+                                           alone does not know the format and never sets it          */
+#define LGN_ST_HAS_NONFINITE 32u   /* Inf / NaN entries were seen (and skipped by the statistics);
+                                      copied from the statistics into both parameter structs, so it
+                                      travels with the codes: a NaN has no code of its own and
+                                      comes out as the largest code of its sign                  */
 
 /* Result of lgn_stats (device memory, 72 bytes, 8-byte aligned). */
 typedef struct lgn_stats_t {
@@ -133,6 +142,29 @@ typedef struct lgn_fp_params_t {
  *   zero, decided before rounding.  Zero gives code 0; Inf and NaN give the largest code of their
  *   sign (with VALUE output NaN stays NaN).
  */
+
+/*
+ * Tuning knobs.  They change how the work is laid out on the device, never a result.  Process-wide;
+ * read at every launch; value < 0 restores the default.  Not part of the method: timing
+ * experiments and the tests of the cache-reuse boundary use them.
+ *   LGN_TUNE_STATS_KEEP_MB         how much of a tensor's tail the statistics pass reads with
+ *                                  ordinary (cache-allocating) loads, so that the pass that
+ *                                  follows finds it in the memory-side cache; 0 = all streaming
+ *                                  (default 224, range 0..4096)
+ *   LGN_TUNE_STATS_BLOCKS_PER_CU   workgroups per compute unit of the statistics pass; 0 = by
+ *                                  element type (2 for fp32, 6 for 16-bit types) (range 0..8)
+ *   LGN_TUNE_STREAM_PAIRS_PER_WAVE tile pairs (512 elements) a wave of a streaming kernel walks
+ *                                  (default 6, range 1..4096)
+ *   LGN_TUNE_STREAM_BLOCKS_PER_CU  upper limit of the streaming grid in workgroups per compute
+ *                                  unit (default 1024, range 1..1024)
+ * lgn_set_tuning returns LGN_ERR_INVALID_ARG for an unknown knob or a value out of range.
+ */
+#define LGN_TUNE_STATS_KEEP_MB 0
+#define LGN_TUNE_STATS_BLOCKS_PER_CU 1
+#define LGN_TUNE_STREAM_PAIRS_PER_WAVE 2
+#define LGN_TUNE_STREAM_BLOCKS_PER_CU 3
+int lgn_set_tuning(int knob, long value);
+long lgn_get_tuning(int knob); /* -1 for an unknown knob */
 
 /* Bytes of workspace lgn_stats and lgn_stats_solve need for n elements (a few tens of KiB,
  * independent of n).  Host function, no device work. */
@@ -186,7 +218,8 @@ int lgn_stats_masked(const void *g, const void *mask, int mask_kind, uint64_t n,
  * lgn_stats, lgn_threshold and lgn_fp_params in ONE launch (same passages as those three): the
  * workgroup that finishes last combines the per-block records and runs both solvers, so the two
  * parameter structs are ready when the statistics pass ends.  Results are identical to the three
- * separate calls.
+ * separate calls, except that this call also sets LGN_ST_ALPHA_BELOW_FP_RANGE in p_out->status
+ * when both a threshold and a format are asked for and the threshold lies below the format's range.
  *   target_sparsity  in [0, 1), or negative to skip the threshold (p_out may then be null)
  *   n_bits           in [2, 8], or 0 to skip the format (f_out may then be null)
  *   mask, mask_kind  as in lgn_stats_masked (null and LGN_MASK_NONE for a plain tensor)
@@ -246,7 +279,7 @@ int lgn_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
 
 /*
  * Stochastic pruning (Section 5): out_i = g_i if |g_i| > alpha; else sign(g_i) alpha if
- * |g_i| >= fl32(alpha * u_i); else 0, with u_i = ((word >> 9) + 1/2) / 2^23 in (0, 1).  Zeros stay
+ * |g_i| >= fl32(alpha * u_i); else 0, with u_i = ((word >> 16) + 1/2) / 2^16 in (0, 1).  Zeros stay
  * (+)zero; NaN and Inf pass through.  alpha is read from *p on the device (alpha = 0 keeps every
  * non-zero element).
  *   out   device, n elements of `dtype`; may equal g (in place)
@@ -257,7 +290,8 @@ int lgn_prune(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p,
 /*
  * FP(1,e,m) quantization with scale 2^s (Section 4.1; Alg. 1 last line).  (N, e, m, s) are read
  * from *f on the device; the caller sizes a PACKED output with the N it asked lgn_fp_params for.
- *   rounding  LGN_ROUND_*; stochastic rounding draws the purpose-1 word of each element
+ *   rounding  LGN_ROUND_*; stochastic rounding goes up iff the cut-off fraction of a spacing plus
+ *             (r + 1/2) / 2^16 reaches one, r the lower 16 bits of the element's word
  *   out       device; layout per out_kind (VALUE may be in place)
  */
 int lgn_fp_quantize(const void *g, uint64_t n, int dtype, const lgn_fp_params_t *f, int rounding,

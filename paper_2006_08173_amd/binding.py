@@ -28,6 +28,8 @@ LGN_PREFIX_CHUNK = 4096
 LGN_MASK_NONE, LGN_MASK_SAME_DTYPE, LGN_MASK_U8 = 0, 1, 2
 LGN_HIST_BINS = 2048
 LGN_ALLOC_LOWERED, LGN_ALLOC_CAPPED = 1, 2
+LGN_TUNE_STATS_KEEP_MB, LGN_TUNE_STATS_BLOCKS_PER_CU = 0, 1
+LGN_TUNE_STREAM_PAIRS_PER_WAVE, LGN_TUNE_STREAM_BLOCKS_PER_CU = 2, 3
 
 
 class LgnStats(C.Structure):
@@ -70,7 +72,7 @@ EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshol
            "lgn_fp_params", "lgn_prune", "lgn_fp_quantize", "lgn_prune_quantize_fused",
            "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_stats_masked", "lgn_prefix_encode",
            "lgn_prefix_decode", "lgn_log_histogram", "lgn_sparsity_allocate", "lgn_threshold_floor",
-           "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes",
+           "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes", "lgn_set_tuning", "lgn_get_tuning",
            "lgn_last_error", "lgn_version")
 
 
@@ -112,6 +114,10 @@ def load():
     L.lgn_log_histogram.argtypes = [vp, u64, i32, vp, vp]
     L.lgn_sparsity_allocate.argtypes = [vp, vp, i32, dbl, i32, vp, dbl, dbl, i32, vp, vp, vp]
     L.lgn_threshold_floor.argtypes = [vp, vp, vp, vp]
+    L.lgn_set_tuning.argtypes = [i32, C.c_long]
+    L.lgn_set_tuning.restype = i32
+    L.lgn_get_tuning.argtypes = [i32]
+    L.lgn_get_tuning.restype = C.c_long
     for name in EXPORTS[2:17]:
         getattr(L, name).restype = i32
     _lib = L
@@ -155,20 +161,33 @@ _ws_cache = {}
 
 
 def workspace(device) -> torch.Tensor:
-    """Per-device scratch tensor for lgn_stats / lgn_stats_solve (allocated once by torch and
-    prepared once with lgn_workspace_init)."""
-    key = torch.device(device).index if torch.device(device).index is not None else torch.cuda.current_device()
-    ws = _ws_cache.get(key)
-    if ws is None:
-        ws = torch.empty(lgn_workspace_bytes(0, LGN_F32), dtype=torch.uint8, device=f"cuda:{key}")
-        lgn_workspace_init(ws)
-        _ws_cache[key] = ws
+    """Scratch tensor for lgn_stats / lgn_stats_solve, one per (device, current stream): calls on
+    different streams may overlap in time and must not share the per-block records and the ticket.
+    Allocated by torch and prepared with lgn_workspace_init on that same stream, so the preparation
+    is ordered before the first use."""
+    dev = torch.device(device)
+    index = dev.index if dev.index is not None else torch.cuda.current_device()
+    with torch.cuda.device(index):
+        key = (index, torch.cuda.current_stream().cuda_stream)
+        ws = _ws_cache.get(key)
+        if ws is None:
+            ws = torch.empty(lgn_workspace_bytes(0, LGN_F32), dtype=torch.uint8, device=f"cuda:{index}")
+            lgn_workspace_init(ws)
+            _ws_cache[key] = ws
     return ws
 
 
 # ---- same names as the C interface ------------------------------------------------------------
 def lgn_version() -> int:
     return int(load().lgn_version())
+
+
+def lgn_set_tuning(knob: int, value: int) -> None:
+    _check(load().lgn_set_tuning(int(knob), int(value)))
+
+
+def lgn_get_tuning(knob: int) -> int:
+    return int(load().lgn_get_tuning(int(knob)))
 
 
 def lgn_workspace_bytes(n: int, dtype: int) -> int:
@@ -292,7 +311,6 @@ def _alloc_quant_out(g, out_kind, n_bits):
         return torch.empty(g.numel(), dtype=torch.uint8, device=g.device)
     if n_bits is None:
         raise ValueError("n_bits is needed to size a PACKED output")
-    # rounded up to whole dwords so the tensor start and size stay 4-byte friendly
     nbytes = lgn_packed_bytes(g.numel(), n_bits)
     return torch.empty(nbytes, dtype=torch.uint8, device=g.device)
 

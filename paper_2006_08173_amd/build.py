@@ -11,7 +11,7 @@ LIB = os.environ.get("LGN_LIB") or os.path.join(PKG, "liblgn.so")
 SOURCES = ["api.hip", "stats.hip", "solver.hip", "stream.hip", "stream_f32.hip", "stream_bf16.hip",
            "stream_f16.hip", "prefix.hip", "alloc.hip"]
 HEADERS = [os.path.join(CSRC, "lgn_device.hpp"), os.path.join(CSRC, "solver_device.hpp"),
-           os.path.join(CSRC, "fpcode_device.hpp"), os.path.join(CSRC, "stream_kernels.hpp"),
+           os.path.join(CSRC, "fpcode_device.hpp"), os.path.join(CSRC, "stream_kernels.hpp"), os.path.join(CSRC, "launch.hpp"),
            os.path.join(os.path.dirname(PKG), "include", "lgn.h")]
 
 

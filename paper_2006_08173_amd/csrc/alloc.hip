@@ -16,6 +16,7 @@
 //     xx = Phi((c - 2 s^2)/s)                                       E[x^2] = E[x T(x)]
 //     tt = e^{L - 3 s^2 / 2} Phi((min(L,c) - s^2)/s) + [xx - Phi((L - 2 s^2)/s)]_+      E[T(x)^2]
 //     cos = sqrt(xx / tt)
+#include "launch.hpp"
 #include "solver_device.hpp"
 
 namespace lgn {
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(kBlock) void hist_kernel(const void *__restrict__ g
     }
 }
 
-hipError_t launch_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, int max_blocks,
+hipError_t launch_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist,
                                 hipStream_t stream)
 {
     unsigned long long *h = reinterpret_cast<unsigned long long *>(hist);
@@ -97,7 +98,8 @@ hipError_t launch_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *
     const uint64_t epv = dtype == LGN_F32 ? 4 : 8;
     uint64_t blocks = (n / epv + kBlock - 1) / kBlock;
     if (blocks < 1) blocks = 1;
-    if (blocks > (uint64_t)max_blocks) blocks = max_blocks;
+    const uint64_t max_blocks = (uint64_t)device_cus() * 8;  // resident grid: eight workgroups per CU
+    if (blocks > max_blocks) blocks = max_blocks;
     if (dtype == LGN_F32) hist_kernel<LGN_F32><<<(int)blocks, kBlock, 0, stream>>>(g, n, h);
     else if (dtype == LGN_BF16) hist_kernel<LGN_BF16><<<(int)blocks, kBlock, 0, stream>>>(g, n, h);
     else hist_kernel<LGN_F16><<<(int)blocks, kBlock, 0, stream>>>(g, n, h);

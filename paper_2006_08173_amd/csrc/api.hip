@@ -4,50 +4,45 @@
 #include <stdio.h>
 #include <stdlib.h>
 
-#include "lgn_device.hpp"
+#include <atomic>
+
+#include "launch.hpp"
 
 namespace lgn {
-struct StreamArgs {
-    const void *g;
-    void *out;
-    uint64_t n;
-    uint64_t elem_offset;
-    const lgn_prune_params_t *p;
-    const lgn_fp_params_t *f;
-    uint32_t k0, k1;
-};
-hipError_t launch_stats(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
-                        lgn_stats_t *out, void *ws, int max_blocks, hipStream_t stream);
-size_t stats_workspace_bytes();
-hipError_t launch_workspace_init(void *ws, hipStream_t stream);
-hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
-                              double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
-                              int scale_mode, double scale_z, int sigma_units, lgn_stats_t *st,
-                              lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
-                              hipStream_t stream);
-hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
-                            lgn_prune_params_t *out, hipStream_t stream);
-hipError_t launch_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in,
-                                  lgn_prune_params_t *out, hipStream_t stream);
-hipError_t launch_fp_params(const lgn_stats_t *st, int n_bits, int e_bits, int scale_mode,
-                            double scale_z, int sigma_units, lgn_fp_params_t *out,
-                            hipStream_t stream);
-hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int out_kind,
-                         const StreamArgs &args, int max_blocks, hipStream_t stream);
-hipError_t launch_dequant(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f,
-                          int dtype, void *out, hipStream_t stream);
-hipError_t launch_prefix_encode(int width_class, int dtype, const void *in, uint64_t n,
-                                const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out,
-                                uint64_t capacity_words, uint64_t *table, hipStream_t stream);
-hipError_t launch_prefix_decode(int width_class, int dtype, const void *in, const uint64_t *table,
-                                uint64_t n, const lgn_prune_params_t *p, const lgn_fp_params_t *f,
-                                void *out, hipStream_t stream);
-hipError_t launch_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, int max_blocks,
-                                hipStream_t stream);
-hipError_t launch_sparsity_allocate(const lgn_stats_t *stats, const uint64_t *hists, int n_layers,
-                                    double overall, int n_deep, const double *min_cosine,
-                                    double max_sparsity, double quantile, int alpha_dtype,
-                                    lgn_prune_params_t *p_out, lgn_alloc_t *a_out, hipStream_t stream);
+
+// ---- tuning knobs: process-wide, lock-free ---------------------------------------------------
+namespace {
+constexpr int kKnobs = 4;
+constexpr long kKnobDefault[kKnobs] = {224, 0, 6, 1024};
+constexpr long kKnobMin[kKnobs] = {0, 0, 1, 1};
+constexpr long kKnobMax[kKnobs] = {4096, 8, 4096, 1024};
+std::atomic<long> g_knob[kKnobs] = {{224}, {0}, {6}, {1024}};
+std::atomic<int> g_cus[64];  // zero = not yet asked
+}  // namespace
+
+long tuning(int knob) { return knob >= 0 && knob < kKnobs ? g_knob[knob].load(std::memory_order_relaxed) : -1; }
+
+int set_tuning(int knob, long value)
+{
+    if (knob < 0 || knob >= kKnobs) return -1;
+    if (value < 0) value = kKnobDefault[knob];
+    if (value < kKnobMin[knob] || value > kKnobMax[knob]) return -1;
+    g_knob[knob].store(value, std::memory_order_relaxed);
+    return 0;
+}
+
+int device_cus()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int v = g_cus[dev].load(std::memory_order_relaxed);
+    if (v) return v;
+    int q = 0;
+    v = hipDeviceGetAttribute(&q, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && q > 0 ? q : 256;
+    g_cus[dev].store(v, std::memory_order_relaxed);  // every thread would store the same value
+    return v;
+}
+
 }  // namespace lgn
 
 namespace {
@@ -71,66 +66,6 @@ int device_fail(const char *what, hipError_t e)
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 bool dtype_ok(int d) { return d == LGN_F32 || d == LGN_BF16 || d == LGN_F16; }
-
-// Upper limit of the workgroups of a streaming launch (the launch itself sizes the grid by the
-// work per wave).
-int stream_blocks()
-{
-    static int cached = 0;
-    if (cached) return cached;
-    int per_cu = 1024;
-    if (const char *e = getenv("LGN_STREAM_BLOCKS_PER_CU")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= 1024) per_cu = v;
-    }
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-    }
-    cached = cus * per_cu;
-    return cached;
-}
-
-// Workgroups of a resident (grid-stride) launch: eight per CU.
-int resident_blocks()
-{
-    static int cached = 0;
-    if (cached) return cached;
-    int dev = 0, cus = 256, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-        cus = v;
-    cached = cus * 8;
-    return cached;
-}
-
-// Workgroups of the statistics pass.  Read-only streaming likes few, long-lived waves: for fp32
-// two workgroups per CU (each wave keeps 8 KiB in flight) measured best, 6.3 TB/s against 5.9 at
-// four; the 16-bit types have twice the arithmetic per byte and want six (10^9 bf16 elements:
-// 0.398 / 0.365 / 0.348 / 0.341 / 0.335 ms at 2 / 3 / 4 / 6 / 8).  Fewer workgroups also mean fewer
-// per-block records for the combine step.
-int stats_blocks_cap(int dtype)
-{
-    static int cus = 0;
-    static int env_per_cu = -1;
-    if (!cus) {
-        int dev = 0, v = 0;
-        cus = 256;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        env_per_cu = 0;
-        if (const char *e = getenv("LGN_STATS_BLOCKS_PER_CU")) {
-            const int w = atoi(e);
-            if (w >= 1 && w <= 8) env_per_cu = w;
-        }
-    }
-    const int per_cu = env_per_cu ? env_per_cu : (dtype == LGN_F32 ? 2 : 6);
-    const int blocks = cus * per_cu;
-    return blocks > 2048 ? 2048 : blocks;
-}
 
 int check_stats_args(const void *g, uint64_t n, int dtype, const lgn_stats_t *out, const void *ws,
                      size_t ws_bytes)
@@ -228,6 +163,15 @@ const char *lgn_last_error(void) { return g_err; }
 
 int lgn_version(void) { return LGN_VERSION; }
 
+int lgn_set_tuning(int knob, long value)
+{
+    if (lgn::set_tuning(knob, value) != 0)
+        return fail(LGN_ERR_INVALID_ARG, "tuning knob %d cannot take the value %ld", knob, value);
+    return LGN_OK;
+}
+
+long lgn_get_tuning(int knob) { return lgn::tuning(knob); }
+
 int lgn_workspace_init(void *ws, size_t ws_bytes, void *stream)
 {
     if (!ws || ws_bytes < lgn::stats_workspace_bytes())
@@ -243,7 +187,7 @@ int lgn_stats(const void *g, uint64_t n, int dtype, lgn_stats_t *out, void *ws, 
 {
     if (int rc = check_stats_args(g, n, dtype, out, ws, ws_bytes)) return rc;
     const hipError_t e = lgn::launch_stats(g, nullptr, LGN_MASK_NONE, n, dtype, out, ws,
-                                           stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
+                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats", e);
 }
 
@@ -253,7 +197,7 @@ int lgn_stats_masked(const void *g, const void *mask, int mask_kind, uint64_t n,
     if (int rc = check_stats_args(g, n, dtype, out, ws, ws_bytes)) return rc;
     if (int rc = check_mask_args(mask, mask_kind, n)) return rc;
     const hipError_t e = lgn::launch_stats(g, mask, mask_kind, n, dtype, out, ws,
-                                           stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
+                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_masked", e);
 }
 
@@ -279,7 +223,7 @@ int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, 
     const hipError_t e = lgn::launch_stats_solve(
         g, mask, mask_kind, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
         n_bits ? scale_rule_z(scale_mode, scale_arg) : 0.0, sigma_units, st_out, want_p ? p_out : nullptr, n_bits ? f_out : nullptr, ws,
-        stats_blocks_cap(dtype), static_cast<hipStream_t>(stream));
+        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_solve", e);
 }
 
@@ -322,7 +266,7 @@ int lgn_prune(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p,
     if (int rc = check_stream_common(g, n, dtype, out, LGN_OUT_VALUE)) return rc;
     if (!p) return fail(LGN_ERR_INVALID_ARG, "null prune params");
     lgn::StreamArgs a = {g, out, n, elem_offset, p, nullptr, (uint32_t)seed, (uint32_t)(seed >> 32)};
-    const hipError_t e = lgn::launch_stream(dtype, true, false, 0, LGN_OUT_VALUE, a, stream_blocks(),
+    const hipError_t e = lgn::launch_stream(dtype, true, false, 0, LGN_OUT_VALUE, a,
                                             static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_prune", e);
 }
@@ -336,7 +280,7 @@ int lgn_fp_quantize(const void *g, uint64_t n, int dtype, const lgn_fp_params_t 
         return fail(LGN_ERR_UNSUPPORTED, "unknown rounding %d", rounding);
     lgn::StreamArgs a = {g, out, n, elem_offset, nullptr, f, (uint32_t)seed, (uint32_t)(seed >> 32)};
     const hipError_t e = lgn::launch_stream(dtype, false, true, rounding, out_kind, a,
-                                            stream_blocks(), static_cast<hipStream_t>(stream));
+                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_fp_quantize", e);
 }
 
@@ -350,7 +294,7 @@ int lgn_prune_quantize_fused(const void *g, uint64_t n, int dtype, const lgn_pru
         return fail(LGN_ERR_UNSUPPORTED, "unknown rounding %d", rounding);
     lgn::StreamArgs a = {g, out, n, elem_offset, p, f, (uint32_t)seed, (uint32_t)(seed >> 32)};
     const hipError_t e = lgn::launch_stream(dtype, true, true, rounding, out_kind, a,
-                                            stream_blocks(), static_cast<hipStream_t>(stream));
+                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_prune_quantize_fused", e);
 }
 
@@ -425,7 +369,7 @@ int lgn_log_histogram(const void *g, uint64_t n, int dtype, uint64_t *hist, void
     if (!hist || !aligned(hist, 8)) return fail(LGN_ERR_INVALID_ARG, "histogram null or not 8-byte aligned");
     if (n && (!g || !aligned(g, 16))) return fail(LGN_ERR_INVALID_ARG, "input null or not 16-byte aligned");
     if (n > (1ull << 60)) return fail(LGN_ERR_INVALID_ARG, "n too large");
-    const hipError_t e = lgn::launch_log_histogram(g, n, dtype, hist, resident_blocks(),
+    const hipError_t e = lgn::launch_log_histogram(g, n, dtype, hist,
                                                    static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_log_histogram", e);
 }

@@ -47,7 +47,8 @@ __device__ __forceinline__ uint32_t quant_code(uint32_t bits, uint32_t w, const 
     const uint32_t rem = y & ((1u << cut) - 1u);
     bool up;
     if (ROUND == LGN_ROUND_STOCHASTIC) {
-        up = rem + (w >> (9 + q.m)) >= (1u << cut);
+        // cut-off fraction + (r + 1/2) / 2^16 >= 1, r the lower half of the element's word
+        up = rem + ((w & 0xffffu) << (cut - 16)) + (1u << (cut - 17)) >= (1u << cut);
     } else {
         const uint32_t half = 1u << (cut - 1);
         up = rem > half || (rem == half && (mag & 1u));

@@ -35,11 +35,10 @@ __device__ __forceinline__ void philox_round(uint32_t &c0, uint32_t &c1, uint32_
     c2 = n2;
 }
 
-// Words of the block with counter (lo32(q), hi32(q), purpose, 0).
-__device__ __forceinline__ void philox_block(uint64_t q, uint32_t purpose, PhiloxKey key,
-                                             uint32_t w[4])
+// Words of the block with counter (lo32(q), hi32(q), 0, 0): the words of elements 4q..4q+3.
+__device__ __forceinline__ void philox_block(uint64_t q, PhiloxKey key, uint32_t w[4])
 {
-    uint32_t c0 = (uint32_t)q, c1 = (uint32_t)(q >> 32), c2 = purpose, c3 = 0u;
+    uint32_t c0 = (uint32_t)q, c1 = (uint32_t)(q >> 32), c2 = 0u, c3 = 0u;
     uint32_t k0 = key.k0, k1 = key.k1;
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
@@ -62,20 +61,17 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
 constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
 constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
 
-// Rounds 1..10 for counter (q_lo, q_hi, PURPOSE, 0) when q_hi is wave-uniform and the round-1
-// product hi0:lo0 = M0 * q_lo is already known (it does not depend on the purpose, so one
-// product serves both streams).  In round 1 the second product has constant operands, in round 2
-// the first product has uniform operands: the compiler keeps those on the scalar unit, leaving
-// 17 vector multiplies instead of 20.
-template <uint32_t PURPOSE>
+// Rounds 1..10 for counter (q_lo, q_hi, 0, 0) when q_hi is wave-uniform and the round-1 product
+// hi0:lo0 = M0 * q_lo is already known.  In round 1 the second product is zero, in round 2 the
+// first product has uniform operands: the compiler keeps those on the scalar unit, leaving 17
+// vector multiplies instead of 20.
 __device__ __forceinline__ void philox_finish(uint32_t hi0, uint32_t lo0, uint32_t q_hi,
                                               PhiloxKey key, uint32_t w[4])
 {
     uint32_t k0 = key.k0, k1 = key.k1;
-    constexpr uint64_t p1c = (uint64_t)kPhiloxM1 * PURPOSE;
-    // round 1: (c0, c1, c2, c3) = (q_lo, q_hi, PURPOSE, 0)
-    uint32_t c0 = (uint32_t)(p1c >> 32) ^ q_hi ^ k0;  // uniform
-    uint32_t c1 = (uint32_t)p1c;                       // constant
+    // round 1: (c0, c1, c2, c3) = (q_lo, q_hi, 0, 0)
+    uint32_t c0 = q_hi ^ k0;  // uniform
+    uint32_t c1 = 0u;
     uint32_t c2 = hi0 ^ k1;
     uint32_t c3 = lo0;
     k0 += kPhiloxW0; k1 += kPhiloxW1;

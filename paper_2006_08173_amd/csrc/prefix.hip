@@ -17,6 +17,7 @@
 // and the chunk is assembled in a zero-initialised LDS image with atomic ORs -- only non-zero
 // elements write anything, the codeword "0" is the zero bit that is already there -- then copied
 // out coalesced while the image is cleared for the next chunk.
+#include "launch.hpp"
 #include "fpcode_device.hpp"
 
 namespace lgn {

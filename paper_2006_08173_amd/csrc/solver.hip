@@ -1,4 +1,5 @@
 // Kernels of lgn_threshold and lgn_fp_params: one wave each (see solver_device.hpp).
+#include "launch.hpp"
 #include "solver_device.hpp"
 
 namespace lgn {

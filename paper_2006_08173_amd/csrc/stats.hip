@@ -16,9 +16,9 @@
 // Inf, NaN or subnormal is re-done by a careful path (wave-uniform branch) that normalises
 // subnormals with integer operations.  Zeros contribute a zero deviation and are counted out
 // with a ballot / popcount on the scalar unit.
-#include <cstdlib>
 #include <type_traits>
 
+#include "launch.hpp"
 #include "lgn_device.hpp"
 #include "solver_device.hpp"
 
@@ -597,7 +597,19 @@ __global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restr
     } else if (wave == 1 && f_out && rq.n_bits != 0) {
         fp_params_body(&st_lds, rq.n_bits, rq.e_bits, rq.scale_mode, rq.scale_z, rq.sigma_units, f_out);
     }
-    if (threadIdx.x == 0) *ticket = 0u;  // ready for the next call on this workspace
+    __syncthreads();  // both parameter structs are written
+    if (threadIdx.x == 0) {
+        // Pruning followed by this format (Section 5's operator, then Section 4.1's underflow
+        // rule): every survivor at or below alpha comes out as +-alpha, and a magnitude below
+        // 2^(E_min + s), E_min = 1 - 2^(e-1), is flushed.  A threshold below that loses everything
+        // pruning touched; only this kernel holds both results, so it reports the condition.
+        if (p_out && f_out && rq.target_sparsity >= 0.0 && rq.n_bits != 0) {
+            const float alpha = p_out->alpha;
+            const int k = 1 - (1 << (f_out->e_bits - 1)) + f_out->scale_exp;
+            if (alpha > 0.0f && (double)alpha < ldexp(1.0, k)) p_out->status |= LGN_ST_ALPHA_BELOW_FP_RANGE;
+        }
+        *ticket = 0u;  // ready for the next call on this workspace
+    }
 }
 
 int stats_blocks(uint64_t n, int dtype)
@@ -626,17 +638,21 @@ hipError_t launch_workspace_init(void *ws, hipStream_t stream)
 }
 
 // How much of the tensor's tail the statistics pass leaves in the memory-side cache (256 MB on
-// this chip), in 16-byte vectors.  LGN_STATS_KEEP_MB overrides the default (read at every call, so
-// that a test can place the boundary inside a small tensor); 0 switches it off.  The result of
+// this chip), in 16-byte vectors (knob LGN_TUNE_STATS_KEEP_MB; 0 switches it off).  The result of
 // the pass does not depend on it: every wave still reduces its batches in the same order.
-static uint64_t kept_vectors()
+static uint64_t kept_vectors() { return (uint64_t)tuning(LGN_TUNE_STATS_KEEP_MB) * ((1u << 20) / 16); }
+
+// Workgroups of the statistics pass.  Read-only streaming likes few, long-lived waves: for fp32
+// two workgroups per CU (each wave keeps 8 KiB in flight) measured best, 6.3 TB/s against 5.9 at
+// four; the 16-bit types have twice the arithmetic per byte and want six (10^9 bf16 elements:
+// 0.398 / 0.365 / 0.348 / 0.341 / 0.335 ms at 2 / 3 / 4 / 6 / 8).  Fewer workgroups also mean fewer
+// per-block records for the combine step.
+static int stats_blocks_cap(int dtype)
 {
-    long mb = 224;
-    if (const char *e = getenv("LGN_STATS_KEEP_MB")) {
-        const long x = atol(e);
-        if (x >= 0 && x <= 4096) mb = x;
-    }
-    return (uint64_t)mb * ((1u << 20) / 16);
+    const long knob = tuning(LGN_TUNE_STATS_BLOCKS_PER_CU);
+    const int per_cu = knob > 0 ? (int)knob : (dtype == LGN_F32 ? 2 : 6);
+    const int blocks = device_cus() * per_cu;
+    return blocks > kMaxStatsBlocks ? kMaxStatsBlocks : blocks;
 }
 
 // Calls f.template operator()<DTYPE, MASK>() for the run-time pair (dtype, mask_kind).
@@ -691,10 +707,10 @@ struct SolveLaunch {
 };
 
 hipError_t launch_stats(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
-                        lgn_stats_t *out, void *ws, int max_blocks, hipStream_t stream)
+                        lgn_stats_t *out, void *ws, hipStream_t stream)
 {
     int blocks = stats_blocks(n, dtype);
-    if (blocks > max_blocks) blocks = max_blocks;
+    if (blocks > stats_blocks_cap(dtype)) blocks = stats_blocks_cap(dtype);
     Partial *partials = static_cast<Partial *>(ws);
     dispatch_dtype_mask(dtype, mask_kind, Stage1Launch{g, mask, n, partials, blocks, stream});
     hipError_t e = hipGetLastError();
@@ -706,11 +722,11 @@ hipError_t launch_stats(const void *g, const void *mask, int mask_kind, uint64_t
 hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
                               double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
                               int scale_mode, double scale_z, int sigma_units, lgn_stats_t *st,
-                              lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws, int max_blocks,
+                              lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws,
                               hipStream_t stream)
 {
     int blocks = stats_blocks(n, dtype);
-    if (blocks > max_blocks) blocks = max_blocks;
+    if (blocks > stats_blocks_cap(dtype)) blocks = stats_blocks_cap(dtype);
     Partial *partials = static_cast<Partial *>(ws);
     unsigned int *ticket = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset);
     const SolveRequest rq = {target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode, sigma_units, scale_z};

@@ -1,6 +1,4 @@
 // Launch side of the streaming operators (kernels: stream_kernels.hpp) and the dequantizer.
-#include <stdlib.h>
-
 #include "stream_kernels.hpp"
 
 namespace lgn {
@@ -30,7 +28,7 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(const uint8_t *__restri
 }
 
 hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int out_kind,
-                         const StreamArgs &args, int max_blocks, hipStream_t stream)
+                         const StreamArgs &args, hipStream_t stream)
 {
     if (args.n == 0) return hipSuccess;
     StreamKernel k;
@@ -43,18 +41,12 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
     // on the 205 M-element tensor, against 8 per CU with ~50 pairs each: -10 % on the fused
     // pass): workgroups then start staggered, so the waves' load and arithmetic phases do not
     // march in step.
-    static int per_wave = 0;
-    if (!per_wave) {
-        per_wave = 6;
-        if (const char *e = getenv("LGN_STREAM_PAIRS_PER_WAVE")) {
-            const int v = atoi(e);
-            if (v >= 1 && v <= 4096) per_wave = v;
-        }
-    }
+    const long per_wave = tuning(LGN_TUNE_STREAM_PAIRS_PER_WAVE);
     const uint64_t per_block = (uint64_t)per_wave * (kBlock / kWave);
     uint64_t blocks = (npairs + per_block - 1) / per_block;
     if (blocks < 1) blocks = 1;
-    if (blocks > (uint64_t)max_blocks) blocks = (uint64_t)max_blocks;
+    const uint64_t max_blocks = (uint64_t)device_cus() * (uint64_t)tuning(LGN_TUNE_STREAM_BLOCKS_PER_CU);
+    if (blocks > max_blocks) blocks = max_blocks;
     hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(kBlock), 0, stream, args);
     return hipGetLastError();
 }

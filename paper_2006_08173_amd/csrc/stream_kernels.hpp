@@ -3,7 +3,8 @@
 //
 // One kernel template covers prune-only, quantize-only and the fused pass.  A wave owns tiles of
 // 256 consecutive elements; lane l owns elements 4l..4l+3 of the tile, i.e. exactly one Philox
-// block per purpose, one 16-byte load (fp32) and one 16-byte / 4-byte store.  Everything is
+// block (one word per element: upper half prunes, lower half rounds), one 16-byte load (fp32) and
+// one 16-byte / 4-byte store.  Everything is
 // integer work on fp32 bit patterns (bf16 widens by a shift, fp16 by the exact conversion), except
 // the one single-precision product alpha * u that the pruning rule is defined with.
 //
@@ -23,34 +24,23 @@
 // instantiate it for one element type each (they compile in parallel), stream.hip launches.
 #pragma once
 
+#include "launch.hpp"
 #include "lgn_device.hpp"
 #include "fpcode_device.hpp"
 
 namespace lgn {
 
-
-struct StreamArgs {
-    const void *g;
-    void *out;
-    uint64_t n;
-    uint64_t elem_offset;
-    const lgn_prune_params_t *p;
-    const lgn_fp_params_t *f;
-    uint32_t k0, k1;
-};
-
-// Words of the four elements j0..j0+3 for a purpose; j0 need not be a multiple of four.
-__device__ __forceinline__ void quad_words(uint64_t j0, uint32_t purpose, PhiloxKey key,
-                                           uint32_t w[4])
+// Words of the four elements j0..j0+3; j0 need not be a multiple of four.
+__device__ __forceinline__ void quad_words(uint64_t j0, PhiloxKey key, uint32_t w[4])
 {
     const uint32_t r = (uint32_t)j0 & 3u;  // wave-uniform: tiles start at multiples of four
     uint32_t a[4];
-    philox_block(j0 >> 2, purpose, key, a);
+    philox_block(j0 >> 2, key, a);
     if (r == 0u) {
         w[0] = a[0]; w[1] = a[1]; w[2] = a[2]; w[3] = a[3];
     } else {
         uint32_t b[4];
-        philox_block((j0 >> 2) + 1, purpose, key, b);
+        philox_block((j0 >> 2) + 1, key, b);
         if (r == 1u) { w[0] = a[1]; w[1] = a[2]; w[2] = a[3]; w[3] = b[0]; }
         else if (r == 2u) { w[0] = a[2]; w[1] = a[3]; w[2] = b[0]; w[3] = b[1]; }
         else { w[0] = a[3]; w[1] = b[0]; w[2] = b[1]; w[3] = b[2]; }
@@ -58,13 +48,13 @@ __device__ __forceinline__ void quad_words(uint64_t j0, uint32_t purpose, Philox
 }
 
 // T_{alpha,u}: |x| > alpha keeps x; |x| < fl32(alpha u) gives 0; otherwise sign(x) alpha, with
-// u = ((w >> 9) + 1/2) / 2^23 in (0, 1).  Zero stays (+)zero whatever alpha u rounds to; NaN and
-// Inf compare above any finite alpha and pass.
+// u = ((w >> 16) + 1/2) / 2^16 in (0, 1): the upper half of the element's word.  Zero stays
+// (+)zero whatever alpha u rounds to; NaN and Inf compare above any finite alpha and pass.
 __device__ __forceinline__ uint32_t prune_bits(uint32_t bits, uint32_t w, uint32_t alpha_bits,
                                                float alpha)
 {
     const uint32_t a = bits & 0x7fffffffu;
-    const float u = (float)((w & 0xfffffe00u) | 0x100u) * 0x1p-32f;  // exact: 24 significant bits
+    const float u = (float)((w & 0xffff0000u) | 0x8000u) * 0x1p-32f;  // exact: 17 significant bits
     const uint32_t t = __float_as_uint(alpha * u);                    // one rounding
     const uint32_t small = (a < t || a == 0u) ? 0u : (alpha_bits | (bits & 0x80000000u));
     return a > alpha_bits ? bits : small;
@@ -129,8 +119,8 @@ __device__ __forceinline__ void pack_store_n(const PackLane &p, int lane, uint32
 // Wave-uniform constants of the fast path.
 struct FastConst {
     uint32_t alpha_bits;
-    float alpha23;     // alpha * 2^-23 and alpha * 2^-24 (exact for the alphas the fast path
-    float alpha24;     // accepts): fl32(alpha u) = fma(k, alpha23, alpha24) for u = (k + 1/2) / 2^23
+    float alpha16;     // alpha * 2^-16 and alpha * 2^-17 (exact for the alphas the fast path
+    float alpha17;     // accepts): fl32(alpha u) = fma(k, alpha16, alpha17) for u = (k + 1/2) / 2^16
     uint32_t sub;      // cbias << 23: subtracting it re-biases the exponent field
     uint32_t sub_hi;   // -(cbias << m) mod 2^32: the same subtraction applied to a magnitude code
     uint32_t lo_bits;  // smallest magnitude pattern that is not flushed
@@ -147,8 +137,9 @@ struct FastConst {
 // raises what pruning keeps to alpha, the upper clamp is the saturation rule (a magnitude clamped
 // to sat_bits has no remainder, so rounding cannot carry past the largest code; Inf and NaN
 // patterns lie above sat_bits).  `keep` is false where pruning zeroed the element.  Stochastic
-// rounding is one 64-bit multiply-add: the upper half of y * 2^(9+m) + w is
-// (y + (w >> (9+m))) >> (23-m).
+// rounding is one 64-bit multiply-add: with r the lower half of the element's word, the upper half
+// of y * 2^(9+m) + (r * 2^16 + 2^15) is (y + (r + 1/2) 2^(7-m)) >> (23-m), i.e. y goes up iff its
+// cut-off fraction plus (r + 1/2) / 2^16 reaches one.
 // CHECK_LO = false is used when every magnitude that reaches the quantizer is known to be at or
 // above the flush threshold (fused pass with alpha >= 2^(E_min+s)).
 template <int ROUND, bool CHECK_LO>
@@ -161,7 +152,7 @@ __device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool ke
         // its place in the code minus the re-biasing (cbias << m): sub * 2^(9+m) is a multiple of
         // 2^32, and the re-biased magnitude code stays below the sign bit, so nothing carries.
         // Written as asm so that the sum stays one v_mad_u64_u32 with a ready-made addend.
-        const uint64_t addend = ((uint64_t)(((bits >> 31) << c.sshift) + c.sub_hi) << 32) | w;
+        const uint64_t addend = ((uint64_t)(((bits >> 31) << c.sshift) + c.sub_hi) << 32) | ((w << 16) | 0x8000u);
         uint64_t r;
         asm("v_mad_u64_u32 %0, vcc, %1, %2, %3" : "=v"(r) : "v"(a), "s"(c.rmul), "v"(addend) : "vcc");
         code = (uint32_t)(r >> 32);
@@ -208,11 +199,12 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
     constexpr int QB = DTYPE == LGN_F32 ? 16 : 8;  // bytes per quad
     const uint32_t q_lo = (uint32_t)qbase + (uint32_t)lane;  // no carry: checked by the caller
     const uint32_t q_hi = (uint32_t)(qbase >> 32);
-    const uint64_t p0 = (uint64_t)kPhiloxM0 * q_lo;           // shared by both purposes
-    uint32_t w0[4] = {0u, 0u, 0u, 0u}, w1[4] = {0u, 0u, 0u, 0u};
-    if (DO_PRUNE) philox_finish<0u>((uint32_t)(p0 >> 32), (uint32_t)p0, q_hi, key, w0);
-    if (QUANT && ROUND == LGN_ROUND_STOCHASTIC)
-        philox_finish<1u>((uint32_t)(p0 >> 32), (uint32_t)p0, q_hi, key, w1);
+    // one word per element: upper half for pruning, lower half for stochastic rounding
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (DO_PRUNE || (QUANT && ROUND == LGN_ROUND_STOCHASTIC)) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * q_lo;
+        philox_finish((uint32_t)(p0 >> 32), (uint32_t)p0, q_hi, key, w);
+    }
 
     uint32_t mag_in[4];
     bool keep[4];
@@ -222,8 +214,8 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
         mag_in[t] = ab;
         keep[t] = true;
         if (DO_PRUNE) {
-            const float kf = (float)(w0[t] >> 9);
-            const uint32_t thr = __float_as_uint(__builtin_fmaf(kf, c.alpha23, c.alpha24));
+            const float kf = (float)(w[t] >> 16);
+            const uint32_t thr = __float_as_uint(__builtin_fmaf(kf, c.alpha16, c.alpha17));
             keep[t] = !(ab < thr);
             if (!QUANT) {
                 const uint32_t small = keep[t] ? (c.alpha_bits | (b[t] & 0x80000000u)) : 0u;
@@ -243,7 +235,7 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
     uint32_t code[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
-        code[t] = fast_code<ROUND, CHECK_LO>(b[t], mag_in[t], keep[t], w1[t], c);
+        code[t] = fast_code<ROUND, CHECK_LO>(b[t], mag_in[t], keep[t], w[t], c);
     if (OUT == LGN_OUT_VALUE) {
         uint32_t v[4];
 #pragma unroll
@@ -281,9 +273,9 @@ __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile,
         for (int t = 0; t < 4; ++t) b[t] = i0 + t < n ? load_elem<DTYPE>(a.g, i0 + t) : 0u;
     }
     const uint64_t j0 = a.elem_offset + i0;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if ((PRUNE && alpha_bits != 0u) || (QUANT && ROUND == LGN_ROUND_STOCHASTIC)) quad_words(j0, key, w);
     if (PRUNE && alpha_bits != 0u) {
-        uint32_t w[4];
-        quad_words(j0, 0u, key, w);
 #pragma unroll
         for (int t = 0; t < 4; ++t) b[t] = prune_bits(b[t], w[t], alpha_bits, alpha);
     } else if (PRUNE) {
@@ -300,8 +292,6 @@ __device__ __forceinline__ void general_tile(const StreamArgs &a, uint64_t tile,
         }
         return;
     }
-    uint32_t w[4] = {0u, 0u, 0u, 0u};
-    if (ROUND == LGN_ROUND_STOCHASTIC) quad_words(j0, 1u, key, w);
     uint32_t code[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) code[t] = quant_code<ROUND>(b[t], w[t], q);
@@ -468,8 +458,8 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
     const bool do_prune = PRUNE && alpha_bits != 0u;
     FastConst &c = s.c;
     c.alpha_bits = alpha_bits;
-    c.alpha23 = s.alpha * 0x1p-23f;
-    c.alpha24 = s.alpha * 0x1p-24f;
+    c.alpha16 = s.alpha * 0x1p-16f;
+    c.alpha17 = s.alpha * 0x1p-17f;
     c.sub = (uint32_t)max(q.cbias, 0) << 23;
     c.lo_bits = (uint32_t)min(max(q.cbias + 1, 0), 256) << 23;
     c.cut = 23u - (uint32_t)q.m;
@@ -487,7 +477,9 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
     // pruning raises every surviving magnitude to alpha: no flush test needed if alpha is in range
     const bool check_lo = !(do_prune && alpha_bits >= c.lo_bits);
     s.fast_ok = (a.elem_offset & 3ull) == 0ull &&
-                (!QUANT || (q.cbias >= 0 && q.cbias <= 254)) &&
+                // the saturation pattern must stay below the Inf pattern, so that the clamp also
+                // catches Inf and NaN
+                (!QUANT || (q.cbias >= 0 && q.cbias + q.cmax <= 254)) &&
                 (!do_prune || (alpha_bits >= 0x12000000u && alpha_bits < 0x7f800000u));
     s.qoff = a.elem_offset >> 2;
 

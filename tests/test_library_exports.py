@@ -46,6 +46,24 @@ def test_host_only_helpers():
     assert ctypes.sizeof(lgn.LgnFpParams) == 32
 
 
+def test_tuning_knobs_are_host_state_only():
+    for knob, default in ((lgn.LGN_TUNE_STATS_KEEP_MB, 224), (lgn.LGN_TUNE_STATS_BLOCKS_PER_CU, 0),
+                          (lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 6), (lgn.LGN_TUNE_STREAM_BLOCKS_PER_CU, 1024)):
+        assert lgn.lgn_get_tuning(knob) == default
+    lgn.lgn_set_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 12)
+    assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE) == 12
+    lgn.lgn_set_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, -1)
+    assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE) == 6
+    for knob, bad in ((lgn.LGN_TUNE_STATS_KEEP_MB, 5000), (lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 0), (9, 1)):
+        try:
+            lgn.lgn_set_tuning(knob, bad)
+        except lgn.LgnError as e:
+            assert e.code == lgn.LGN_ERR_INVALID_ARG
+        else:
+            raise AssertionError("accepted a bad knob/value")
+    assert lgn.lgn_get_tuning(9) == -1
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2006_08173_amd")
     for dirpath, _, files in os.walk(pkg):
