@@ -236,6 +236,24 @@ int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, 
                     void *stream);
 
 /*
+ * lgn_stats_solve for callers that cannot allocate device memory and so have no workspace to pass:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without ws) and the same results, bit for bit.  The per-block records and the ticket
+ * live in an array of lgn_static_scratch_bytes() = 81 984 bytes inside the library's device image
+ * (one copy per GPU, held until the process ends); it serves any n up to LGN_STATIC_MAX_ELEMENTS, a
+ * larger n is refused with LGN_ERR_INVALID_ARG.  The call allocates nothing and launches one
+ * 64-thread fill kernel (the ticket) and the statistics kernel on `stream`.  Every call on a GPU
+ * uses that GPU's one array: calls that overlap in time on one GPU (different streams, several host
+ * threads) race and must use lgn_stats_solve with workspaces of their own instead.
+ */
+#define LGN_STATIC_MAX_ELEMENTS (1ull << 40)
+int lgn_stats_solve_static(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                           double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
+                           int scale_mode, double scale_arg, int sigma_units, lgn_stats_t *st_out,
+                           lgn_prune_params_t *p_out, lgn_fp_params_t *f_out, void *stream);
+size_t lgn_static_scratch_bytes(void);
+
+/*
  * Threshold alpha such that stochastic pruning leaves a fraction `target_sparsity` of the WHOLE
  * tensor at zero (Section 5.1 poses the problem: the alpha that induces a given sparsity; closed
  * form of Section 5.2; existing zeros are credited as in Appendix "Algorithm for bi-Modal lognormal

@@ -73,6 +73,7 @@ EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshol
            "lgn_dequantize", "lgn_workspace_init", "lgn_stats_solve", "lgn_stats_masked", "lgn_prefix_encode",
            "lgn_prefix_decode", "lgn_log_histogram", "lgn_sparsity_allocate", "lgn_threshold_floor",
            "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes", "lgn_set_tuning", "lgn_get_tuning",
+           "lgn_stats_solve_static", "lgn_static_scratch_bytes",
            "lgn_last_error", "lgn_version")
 
 
@@ -103,6 +104,9 @@ def load():
     L.lgn_workspace_init.argtypes = [vp, sz, vp]
     L.lgn_stats_solve.argtypes = [vp, vp, i32, u64, i32, dbl, i32, i32, i32, i32, dbl, i32, vp, vp, vp, vp, sz, vp]
     L.lgn_stats_masked.argtypes = [vp, vp, i32, u64, i32, vp, vp, sz, vp]
+    L.lgn_stats_solve_static.argtypes = [vp, vp, i32, u64, i32, dbl, i32, i32, i32, i32, dbl, i32, vp, vp, vp, vp]
+    L.lgn_stats_solve_static.restype = i32
+    L.lgn_static_scratch_bytes.restype = sz
     L.lgn_last_error.restype = C.c_char_p
     L.lgn_version.restype = i32
     L.lgn_prefix_encode.argtypes = [vp, u64, i32, i32, vp, vp, vp, sz, vp, vp]
@@ -264,6 +268,31 @@ def lgn_stats_solve(g: torch.Tensor, target_sparsity: float = -1.0, alpha_dtype:
                                   p.data_ptr() if p is not None else None,
                                   f.data_ptr() if f is not None else None,
                                   ws.data_ptr(), ws.numel(), _stream()))
+    return st, p, f
+
+
+LGN_STATIC_MAX_ELEMENTS = 1 << 40
+
+
+def lgn_static_scratch_bytes() -> int:
+    return int(load().lgn_static_scratch_bytes())
+
+
+def lgn_stats_solve_static(g: torch.Tensor, st: torch.Tensor, p: torch.Tensor = None, f: torch.Tensor = None,
+                           target_sparsity: float = -1.0, alpha_dtype: int = LGN_F32, n_bits: int = 0,
+                           e_bits: int = -1, scale_mode: int = LGN_SCALE_QUANTILE, scale_arg: float = 0.997,
+                           sigma_units: int = LGN_SIGMA_PAPER_LITERAL, dtype=None, mask: torch.Tensor = None,
+                           n: int = None):
+    """lgn_stats_solve on the library's built-in scratch array.  The output structs are the
+    caller's (this wrapper allocates nothing either); `n` overrides the element count."""
+    g = _flat(g)
+    mp, mk = _mask_args(g, mask)
+    _check(load().lgn_stats_solve_static(g.data_ptr(), mp, mk, g.numel() if n is None else int(n),
+                                         _dtype_code(g, dtype), float(target_sparsity), int(alpha_dtype),
+                                         int(n_bits), int(e_bits), int(scale_mode), float(scale_arg),
+                                         int(sigma_units), st.data_ptr(),
+                                         p.data_ptr() if p is not None else None,
+                                         f.data_ptr() if f is not None else None, _stream()))
     return st, p, f
 
 

@@ -137,6 +137,26 @@ int check_fp_args(int n_bits, int e_bits, int scale_mode, double scale_arg, int 
     return LGN_OK;
 }
 
+// Arguments of the one-launch statistics + solvers form beyond those of lgn_stats.
+int check_solve_args(const void *mask, int mask_kind, uint64_t n, double target_sparsity, int alpha_dtype,
+                     int n_bits, int e_bits, int scale_mode, double scale_arg, int sigma_units,
+                     const lgn_prune_params_t *p_out, const lgn_fp_params_t *f_out, bool *want_p)
+{
+    if (int rc = check_mask_args(mask, mask_kind, n)) return rc;
+    *want_p = target_sparsity >= 0.0 || target_sparsity != target_sparsity;
+    if (*want_p) {
+        if (int rc = check_threshold_args(target_sparsity, alpha_dtype)) return rc;
+        if (!p_out || !aligned(p_out, 8))
+            return fail(LGN_ERR_INVALID_ARG, "prune params struct null or not 8-byte aligned");
+    }
+    if (n_bits != 0) {
+        if (int rc = check_fp_args(n_bits, e_bits, scale_mode, scale_arg, sigma_units)) return rc;
+        if (!f_out || !aligned(f_out, 8))
+            return fail(LGN_ERR_INVALID_ARG, "fp params struct null or not 8-byte aligned");
+    }
+    return LGN_OK;
+}
+
 int check_stream_common(const void *g, uint64_t n, int dtype, const void *out, int out_kind)
 {
     if (!dtype_ok(dtype)) return fail(LGN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
@@ -208,24 +228,40 @@ int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, 
                     void *stream)
 {
     if (int rc = check_stats_args(g, n, dtype, st_out, ws, ws_bytes)) return rc;
-    if (int rc = check_mask_args(mask, mask_kind, n)) return rc;
-    const bool want_p = target_sparsity >= 0.0 || target_sparsity != target_sparsity;
-    if (want_p) {
-        if (int rc = check_threshold_args(target_sparsity, alpha_dtype)) return rc;
-        if (!p_out || !aligned(p_out, 8))
-            return fail(LGN_ERR_INVALID_ARG, "prune params struct null or not 8-byte aligned");
-    }
-    if (n_bits != 0) {
-        if (int rc = check_fp_args(n_bits, e_bits, scale_mode, scale_arg, sigma_units)) return rc;
-        if (!f_out || !aligned(f_out, 8))
-            return fail(LGN_ERR_INVALID_ARG, "fp params struct null or not 8-byte aligned");
-    }
+    bool want_p = false;
+    if (int rc = check_solve_args(mask, mask_kind, n, target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode,
+                                  scale_arg, sigma_units, p_out, f_out, &want_p))
+        return rc;
     const hipError_t e = lgn::launch_stats_solve(
         g, mask, mask_kind, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
-        n_bits ? scale_rule_z(scale_mode, scale_arg) : 0.0, sigma_units, st_out, want_p ? p_out : nullptr, n_bits ? f_out : nullptr, ws,
-        static_cast<hipStream_t>(stream));
+        n_bits ? scale_rule_z(scale_mode, scale_arg) : 0.0, sigma_units, st_out, want_p ? p_out : nullptr,
+        n_bits ? f_out : nullptr, ws, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_solve", e);
 }
+
+int lgn_stats_solve_static(const void *g, const void *mask, int mask_kind, uint64_t n, int dtype,
+                           double target_sparsity, int alpha_dtype, int n_bits, int e_bits,
+                           int scale_mode, double scale_arg, int sigma_units, lgn_stats_t *st_out,
+                           lgn_prune_params_t *p_out, lgn_fp_params_t *f_out, void *stream)
+{
+    if (n > LGN_STATIC_MAX_ELEMENTS)
+        return fail(LGN_ERR_INVALID_ARG, "n = %llu exceeds LGN_STATIC_MAX_ELEMENTS = %llu of the built-in scratch array",
+                    (unsigned long long)n, (unsigned long long)LGN_STATIC_MAX_ELEMENTS);
+    // the workspace checks do not apply: any non-null aligned pointer passes them
+    alignas(16) static const char none[16] = {};
+    if (int rc = check_stats_args(g, n, dtype, st_out, none, lgn::stats_workspace_bytes())) return rc;
+    bool want_p = false;
+    if (int rc = check_solve_args(mask, mask_kind, n, target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode,
+                                  scale_arg, sigma_units, p_out, f_out, &want_p))
+        return rc;
+    const hipError_t e = lgn::launch_stats_solve_static(
+        g, mask, mask_kind, n, dtype, want_p ? target_sparsity : -1.0, alpha_dtype, n_bits, e_bits, scale_mode,
+        n_bits ? scale_rule_z(scale_mode, scale_arg) : 0.0, sigma_units, st_out, want_p ? p_out : nullptr,
+        n_bits ? f_out : nullptr, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_stats_solve_static", e);
+}
+
+size_t lgn_static_scratch_bytes(void) { return lgn::stats_scratch_bytes(); }
 
 int lgn_threshold(const lgn_stats_t *st, double target_sparsity, int alpha_dtype,
                   lgn_prune_params_t *out, void *stream)

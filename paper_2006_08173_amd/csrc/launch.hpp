@@ -37,6 +37,13 @@ hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, ui
                               int scale_mode, double scale_z, int sigma_units, lgn_stats_t *st,
                               lgn_prune_params_t *p, lgn_fp_params_t *f, void *ws,
                               hipStream_t stream);
+// The same launch on the library's own per-device scratch array (no workspace argument).
+hipError_t launch_stats_solve_static(const void *g, const void *mask, int mask_kind, uint64_t n,
+                                     int dtype, double target_sparsity, int alpha_dtype, int n_bits,
+                                     int e_bits, int scale_mode, double scale_z, int sigma_units,
+                                     lgn_stats_t *st, lgn_prune_params_t *p, lgn_fp_params_t *f,
+                                     hipStream_t stream);
+size_t stats_scratch_bytes();
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
                             lgn_prune_params_t *out, hipStream_t stream);
 hipError_t launch_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in,

@@ -16,6 +16,7 @@
 // Inf, NaN or subnormal is re-done by a careful path (wave-uniform branch) that normalises
 // subnormals with integer operations.  Zeros contribute a zero deviation and are counted out
 // with a ballot / popcount on the scalar unit.
+#include <mutex>
 #include <type_traits>
 
 #include "launch.hpp"
@@ -734,5 +735,54 @@ hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, ui
                         SolveLaunch{g, mask, n, partials, ticket, rq, st, p, f, blocks, stream});
     return hipGetLastError();
 }
+
+// ---- the same launch on a scratch array the library owns ------------------------------------
+// For callers that cannot provide a workspace because they cannot allocate one: the per-block
+// records and the ticket live in a file-scope device array (one copy per GPU the library runs
+// on, held until the process ends).  Host code never uses the array's name as an address: the
+// device address is asked for once per device and kept.
+constexpr size_t kScratchBytes = kTicketOffset + 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+static hipError_t scratch_address(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptr[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // this device's copy of the array
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
+
+hipError_t launch_stats_solve_static(const void *g, const void *mask, int mask_kind, uint64_t n,
+                                     int dtype, double target_sparsity, int alpha_dtype, int n_bits,
+                                     int e_bits, int scale_mode, double scale_z, int sigma_units,
+                                     lgn_stats_t *st, lgn_prune_params_t *p, lgn_fp_params_t *f,
+                                     hipStream_t stream)
+{
+    void *ws = nullptr;
+    hipError_t e = scratch_address(&ws);
+    if (e != hipSuccess) return e;
+    // The array keeps whatever the last call on this GPU left: the ticket must start at zero (a
+    // fill kernel, not a memset, so that the sequence can be captured in a graph); the records
+    // are overwritten before they are read.
+    e = launch_workspace_init(ws, stream);
+    if (e != hipSuccess) return e;
+    return launch_stats_solve(g, mask, mask_kind, n, dtype, target_sparsity, alpha_dtype, n_bits, e_bits,
+                              scale_mode, scale_z, sigma_units, st, p, f, ws, stream);
+}
+
+size_t stats_scratch_bytes() { return kScratchBytes; }
 
 }  // namespace lgn

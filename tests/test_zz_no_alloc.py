@@ -1,0 +1,77 @@
+"""The entry point that allocates nothing: lgn_stats_solve_static keeps its per-block records and
+ticket in an array inside the library's device image.  Its results must be the bytes of
+lgn_stats_solve, on calls in a row that share that array (the second smaller than the first)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import synth_inputs as SI
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lgn():
+    import paper_2006_08173_amd as m
+    m.load()
+    return m
+
+
+def _structs(device="cuda"):
+    return (torch.empty(72, dtype=torch.uint8, device=device), torch.empty(24, dtype=torch.uint8, device=device),
+            torch.empty(32, dtype=torch.uint8, device=device))
+
+
+def test_static_entry_point_matches_the_workspace_form_on_calls_in_a_row(lgn):
+    assert lgn.lgn_static_scratch_bytes() == 40 * 2048 + 64
+    big = SI.lognormal_tensor(3_000_001, seed=41, mu=-11.0, sigma=2.2, zero_frac=0.25)
+    big[[7, 1_000_000]] = [np.nan, np.inf]
+    small = SI.lognormal_tensor(70_001, seed=42, mu=-8.0, sigma=1.4, zero_frac=0.5)
+    tiny = SI.lognormal_tensor(5, seed=43, mu=-3.0, sigma=1.0)
+    bf = SI.lognormal_tensor(1_234_567, seed=44, mu=-15.0, sigma=3.0, zero_frac=0.1, dtype=SI.BF16)
+    cases = [(big, 0.9, lgn.LGN_F32, 6), (small, 0.8, lgn.LGN_F32, 5), (big, 0.7, lgn.LGN_F32, 8),
+             (tiny, 0.5, lgn.LGN_F32, 4), (bf, 0.85, lgn.LGN_BF16, 6), (small, 0.8, lgn.LGN_F32, 5)]
+    devs = {id(a): (torch.from_numpy(a.view(np.int16)) if a.dtype == np.uint16 else torch.from_numpy(a)).cuda()
+            for a in (big, small, tiny, bf)}
+    want = []
+    for a, s, adt, nb in cases:
+        st, p, f = lgn.lgn_stats_solve(devs[id(a)], s, adt, nb)
+        want.append((bytes(lgn.read_stats(st)), bytes(lgn.read_prune_params(p)), bytes(lgn.read_fp_params(f))))
+    torch.cuda.synchronize()
+    # the calls follow each other on one stream without host synchronisation in between
+    outs = [_structs() for _ in cases]
+    for (a, s, adt, nb), (st, p, f) in zip(cases, outs):
+        lgn.lgn_stats_solve_static(devs[id(a)], st, p, f, target_sparsity=s, alpha_dtype=adt, n_bits=nb)
+    torch.cuda.synchronize()
+    for (st, p, f), w, (a, s, adt, nb) in zip(outs, want, cases):
+        got = (bytes(lgn.read_stats(st)), bytes(lgn.read_prune_params(p)), bytes(lgn.read_fp_params(f)))
+        assert got == w, (a.size, s, nb)
+    # and against the oracle directly (statistics to 1e-6, counts exact)
+    hs, os_ = lgn.read_stats(outs[1][0]), O.stats(small)
+    assert (hs.n, hs.nnz) == (os_.n, os_.nnz)
+    assert abs(hs.mu - os_.mu) <= 1e-6 * abs(os_.mu) and abs(hs.sigma - os_.sigma) <= 1e-6 * os_.sigma
+    # either solve can be left out; a mask works as in the workspace form
+    st, p, f = _structs()
+    lgn.lgn_stats_solve_static(devs[id(small)], st, None, f, n_bits=6)
+    assert bytes(lgn.read_fp_params(f)) == bytes(lgn.read_fp_params(lgn.lgn_stats_solve(devs[id(small)], n_bits=6)[2]))
+    mask = (devs[id(small)] > 0).to(torch.uint8)
+    lgn.lgn_stats_solve_static(devs[id(small)], st, p, None, target_sparsity=0.9, mask=mask)
+    ref = lgn.lgn_stats_solve(devs[id(small)], 0.9, mask=mask)
+    assert bytes(lgn.read_stats(st)) == bytes(lgn.read_stats(ref[0]))
+    assert bytes(lgn.read_prune_params(p)) == bytes(lgn.read_prune_params(ref[1]))
+
+
+def test_static_entry_point_rejects_what_it_cannot_serve(lgn):
+    g = torch.zeros(1024, device="cuda")
+    st, p, f = _structs()
+    with pytest.raises(lgn.LgnError) as e:
+        lgn.lgn_stats_solve_static(g, st, p, f, target_sparsity=0.5, n_bits=6, n=lgn.LGN_STATIC_MAX_ELEMENTS + 1)
+    assert e.value.code == lgn.LGN_ERR_INVALID_ARG and "LGN_STATIC_MAX_ELEMENTS" in str(e.value)
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_stats_solve_static(g, st, None, f, target_sparsity=0.5, n_bits=6)   # threshold asked, no struct
+    with pytest.raises(lgn.LgnError):
+        lgn.lgn_stats_solve_static(g[1:], st, p, f, target_sparsity=0.5)           # misaligned tensor
+    # n = 0 is fine and reports an empty tensor
+    lgn.lgn_stats_solve_static(g, st, p, f, target_sparsity=0.5, n_bits=6, n=0)
+    assert lgn.read_stats(st).status & lgn.LGN_ST_EMPTY
