@@ -239,7 +239,7 @@ int lgn_stats_solve(const void *g, const void *mask, int mask_kind, uint64_t n, 
  * lgn_stats_solve for callers that cannot allocate device memory and so have no workspace to pass:
  * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments (without ws) and the same results, bit for bit.  The per-block records and the ticket
- * live in an array of lgn_static_scratch_bytes() = 81 984 bytes inside the library's device image
+ * live in an array of lgn_static_scratch_bytes() = 82 176 bytes inside the library's device image
  * (one copy per GPU, held until the process ends); it serves any n up to LGN_STATIC_MAX_ELEMENTS, a
  * larger n is refused with LGN_ERR_INVALID_ARG.  The call allocates nothing and launches one
  * 64-thread fill kernel (the ticket) and the statistics kernel on `stream`.  Every call on a GPU
@@ -320,6 +320,42 @@ int lgn_fp_quantize(const void *g, uint64_t n, int dtype, const lgn_fp_params_t 
 int lgn_prune_quantize_fused(const void *g, uint64_t n, int dtype, const lgn_prune_params_t *p,
                              const lgn_fp_params_t *f, int rounding, uint64_t seed,
                              uint64_t elem_offset, void *out, int out_kind, void *stream);
+
+/*
+ * Many tensors, two launches (per-layer thresholds and formats for all layers of a network:
+ * Section 5.2 last paragraph, appendix "Stochastic pruning complexity" -- the parameters are per
+ * layer, so a backward pass holds one small problem per layer; one pair of launches per layer
+ * leaves the device idle between them).  lgn_batch_stats_solve is lgn_stats_solve for every item,
+ * lgn_batch_prune_quantize_fused is lgn_prune_quantize_fused (elem_offset 0) for every item; the
+ * statistics may differ from the one-tensor call in the last bits (another summation order), the
+ * parameters follow from them as in the one-tensor call, and the codes are those of the one-tensor
+ * call for the same parameters.
+ *   items   HOST array of `count` descriptors (read during the call only); all device pointers in
+ *           it are the caller's, as in the one-tensor calls.  All tensors share `dtype`.
+ *   count   any number >= 0; the tables travel in the kernel arguments, 32 tensors per launch, so
+ *           up to 32 tensors take one launch per call and nothing is uploaded or allocated
+ *   ws      as for lgn_stats_solve (prepared with lgn_workspace_init)
+ * An item with n = 0 is allowed (its statistics report an empty tensor).  Errors: as the
+ * one-tensor calls, for the first offending item.
+ */
+typedef struct lgn_batch_item_t {
+    const void *g;          /* device, n elements, 16-byte aligned                                 */
+    void *out;              /* device, output of the fused pass (layout per out_kind)             */
+    uint64_t n;
+    uint64_t seed;          /* key of this tensor's random words                                  */
+    double target_sparsity; /* in [0, 1), or negative: no threshold (p not written)               */
+    int32_t n_bits;         /* in [2, 8], or 0: no format (f not written)                         */
+    int32_t e_bits;         /* in [1, n_bits - 1], or -1 for the minimiser                        */
+    lgn_stats_t *st;        /* device, written by lgn_batch_stats_solve                           */
+    lgn_prune_params_t *p;  /* device, written by lgn_batch_stats_solve, read by the fused pass   */
+    lgn_fp_params_t *f;     /* device, likewise                                                   */
+} lgn_batch_item_t;
+
+int lgn_batch_stats_solve(const lgn_batch_item_t *items, int count, int dtype, int alpha_dtype,
+                          int scale_mode, double scale_arg, int sigma_units, void *ws, size_t ws_bytes,
+                          void *stream);
+int lgn_batch_prune_quantize_fused(const lgn_batch_item_t *items, int count, int dtype, int rounding,
+                                   int out_kind, void *stream);
 
 /* Decode CODE8 or PACKED codes back to values 2^s * q of type `dtype`. */
 int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f, int dtype,

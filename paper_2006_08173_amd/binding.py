@@ -60,6 +60,15 @@ assert C.sizeof(LgnStats) == 72 and C.sizeof(LgnPruneParams) == 24 and C.sizeof(
 assert C.sizeof(LgnAlloc) == 32
 
 
+class LgnBatchItem(C.Structure):
+    _fields_ = [("g", C.c_void_p), ("out", C.c_void_p), ("n", C.c_uint64), ("seed", C.c_uint64),
+                ("target_sparsity", C.c_double), ("n_bits", C.c_int32), ("e_bits", C.c_int32),
+                ("st", C.c_void_p), ("p", C.c_void_p), ("f", C.c_void_p)]
+
+
+assert C.sizeof(LgnBatchItem) == 72
+
+
 class LgnError(RuntimeError):
     def __init__(self, code, text):
         super().__init__(f"lgn error {code}: {text}")
@@ -74,6 +83,7 @@ EXPORTS = ("lgn_workspace_bytes", "lgn_packed_bytes", "lgn_stats", "lgn_threshol
            "lgn_prefix_decode", "lgn_log_histogram", "lgn_sparsity_allocate", "lgn_threshold_floor",
            "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes", "lgn_set_tuning", "lgn_get_tuning",
            "lgn_stats_solve_static", "lgn_static_scratch_bytes",
+           "lgn_batch_stats_solve", "lgn_batch_prune_quantize_fused",
            "lgn_last_error", "lgn_version")
 
 
@@ -107,6 +117,10 @@ def load():
     L.lgn_stats_solve_static.argtypes = [vp, vp, i32, u64, i32, dbl, i32, i32, i32, i32, dbl, i32, vp, vp, vp, vp]
     L.lgn_stats_solve_static.restype = i32
     L.lgn_static_scratch_bytes.restype = sz
+    L.lgn_batch_stats_solve.argtypes = [vp, i32, i32, i32, i32, dbl, i32, vp, sz, vp]
+    L.lgn_batch_stats_solve.restype = i32
+    L.lgn_batch_prune_quantize_fused.argtypes = [vp, i32, i32, i32, i32, vp]
+    L.lgn_batch_prune_quantize_fused.restype = i32
     L.lgn_last_error.restype = C.c_char_p
     L.lgn_version.restype = i32
     L.lgn_prefix_encode.argtypes = [vp, u64, i32, i32, vp, vp, vp, sz, vp, vp]
@@ -294,6 +308,55 @@ def lgn_stats_solve_static(g: torch.Tensor, st: torch.Tensor, p: torch.Tensor = 
                                          p.data_ptr() if p is not None else None,
                                          f.data_ptr() if f is not None else None, _stream()))
     return st, p, f
+
+
+class Batch:
+    """A host array of lgn_batch_item_t plus the tensors it points to (kept alive with it)."""
+
+    def __init__(self, items, dtype, device):
+        self.count = len(items)
+        self.array = (LgnBatchItem * max(self.count, 1))()
+        self.tensors = items
+        self.dtype = dtype
+        self.device = device
+        for i, it in enumerate(items):
+            a = self.array[i]
+            a.g, a.out = it["g"].data_ptr(), it["out"].data_ptr() if it.get("out") is not None else None
+            a.n, a.seed = it["g"].numel(), int(it.get("seed", 0))
+            a.target_sparsity = float(it.get("target_sparsity", -1.0))
+            a.n_bits, a.e_bits = int(it.get("n_bits", 0)), int(it.get("e_bits", -1))
+            a.st = it["st"].data_ptr()
+            a.p = it["p"].data_ptr() if it.get("p") is not None else None
+            a.f = it["f"].data_ptr() if it.get("f") is not None else None
+
+
+def make_batch(items, dtype=None) -> Batch:
+    """items: dicts with g (tensor), st and optionally out, p, f (device buffers), target_sparsity,
+    n_bits, e_bits, seed.  Marshals them into the host descriptor array of the batched calls."""
+    if not items:
+        return Batch([], LGN_F32 if dtype is None else dtype, None)
+    for it in items:
+        _flat(it["g"])
+    dt = _dtype_code(items[0]["g"], dtype)
+    return Batch(items, dt, items[0]["g"].device)
+
+
+def lgn_batch_stats_solve(batch: Batch, alpha_dtype: int = None, scale_mode: int = LGN_SCALE_QUANTILE,
+                          scale_arg: float = 0.997, sigma_units: int = LGN_SIGMA_PAPER_LITERAL,
+                          ws: torch.Tensor = None) -> None:
+    if ws is None:
+        ws = workspace(batch.device if batch.device is not None else "cuda")
+    if alpha_dtype is None:
+        alpha_dtype = batch.dtype
+    _check(load().lgn_batch_stats_solve(C.addressof(batch.array), batch.count, int(batch.dtype), int(alpha_dtype),
+                                        int(scale_mode), float(scale_arg), int(sigma_units), ws.data_ptr(),
+                                        ws.numel(), _stream()))
+
+
+def lgn_batch_prune_quantize_fused(batch: Batch, rounding: int = LGN_ROUND_NEAREST_EVEN,
+                                   out_kind: int = LGN_OUT_CODE8) -> None:
+    _check(load().lgn_batch_prune_quantize_fused(C.addressof(batch.array), batch.count, int(batch.dtype),
+                                                 int(rounding), int(out_kind), _stream()))
 
 
 def lgn_threshold(st: torch.Tensor, target_sparsity: float, alpha_dtype: int = LGN_F32,

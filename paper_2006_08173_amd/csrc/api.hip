@@ -334,6 +334,57 @@ int lgn_prune_quantize_fused(const void *g, uint64_t n, int dtype, const lgn_pru
     return e == hipSuccess ? LGN_OK : device_fail("lgn_prune_quantize_fused", e);
 }
 
+int lgn_batch_stats_solve(const lgn_batch_item_t *items, int count, int dtype, int alpha_dtype,
+                          int scale_mode, double scale_arg, int sigma_units, void *ws, size_t ws_bytes,
+                          void *stream)
+{
+    if (count < 0) return fail(LGN_ERR_INVALID_ARG, "negative count");
+    if (count == 0) return LGN_OK;
+    if (!items) return fail(LGN_ERR_INVALID_ARG, "null item array");
+    bool any_format = false;
+    for (int i = 0; i < count; ++i) {
+        const lgn_batch_item_t &it = items[i];
+        int rc = check_stats_args(it.g, it.n, dtype, it.st, ws, ws_bytes);
+        bool want_p = false;
+        if (!rc)
+            rc = check_solve_args(nullptr, LGN_MASK_NONE, it.n, it.target_sparsity, alpha_dtype, it.n_bits, it.e_bits,
+                                  scale_mode, scale_arg, sigma_units, it.p, it.f, &want_p);
+        if (rc) {
+            char first[200];
+            snprintf(first, sizeof first, "%s", g_err);
+            return fail(rc, "item %d: %s", i, first);
+        }
+        any_format = any_format || it.n_bits != 0;
+    }
+    const hipError_t e = lgn::launch_batch_stats_solve(items, count, dtype, alpha_dtype, scale_mode,
+                                                       any_format ? scale_rule_z(scale_mode, scale_arg) : 0.0,
+                                                       sigma_units, ws, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_batch_stats_solve", e);
+}
+
+int lgn_batch_prune_quantize_fused(const lgn_batch_item_t *items, int count, int dtype, int rounding,
+                                   int out_kind, void *stream)
+{
+    if (count < 0) return fail(LGN_ERR_INVALID_ARG, "negative count");
+    if (count == 0) return LGN_OK;
+    if (!items) return fail(LGN_ERR_INVALID_ARG, "null item array");
+    if (rounding != LGN_ROUND_NEAREST_EVEN && rounding != LGN_ROUND_STOCHASTIC)
+        return fail(LGN_ERR_UNSUPPORTED, "unknown rounding %d", rounding);
+    for (int i = 0; i < count; ++i) {
+        const lgn_batch_item_t &it = items[i];
+        int rc = check_stream_common(it.g, it.n, dtype, it.out, out_kind);
+        if (!rc && (!it.p || !it.f)) rc = fail(LGN_ERR_INVALID_ARG, "null params");
+        if (rc) {
+            char first[200];
+            snprintf(first, sizeof first, "%s", g_err);
+            return fail(rc, "item %d: %s", i, first);
+        }
+    }
+    const hipError_t e = lgn::launch_batch_stream(items, count, dtype, rounding, out_kind,
+                                                  static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LGN_OK : device_fail("lgn_batch_prune_quantize_fused", e);
+}
+
 int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f, int dtype,
                    void *out, void *stream)
 {

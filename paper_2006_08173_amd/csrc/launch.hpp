@@ -44,6 +44,11 @@ hipError_t launch_stats_solve_static(const void *g, const void *mask, int mask_k
                                      lgn_stats_t *st, lgn_prune_params_t *p, lgn_fp_params_t *f,
                                      hipStream_t stream);
 size_t stats_scratch_bytes();
+hipError_t launch_batch_stats_solve(const lgn_batch_item_t *items, int count, int dtype, int alpha_dtype,
+                                    int scale_mode, double scale_z, int sigma_units, void *ws,
+                                    hipStream_t stream);
+hipError_t launch_batch_stream(const lgn_batch_item_t *items, int count, int dtype, int rounding,
+                               int out_kind, hipStream_t stream);
 hipError_t launch_threshold(const lgn_stats_t *st, double target, int alpha_dtype,
                             lgn_prune_params_t *out, hipStream_t stream);
 hipError_t launch_threshold_floor(const lgn_fp_params_t *f, const lgn_prune_params_t *in,

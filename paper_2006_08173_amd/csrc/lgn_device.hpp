@@ -12,6 +12,7 @@ namespace lgn {
 constexpr int kWave = 64;
 constexpr int kBlock = 256;            // threads per workgroup (4 waves, one per SIMD)
 constexpr int kMaxStatsBlocks = 2048;  // cap of stage-1 partials (fills 256 CUs x 8 waves/SIMD)
+constexpr int kBatchMax = 32;          // tensors per launch of the batched entry points
 
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11).  One block = four 32-bit words.  The multiplications are

@@ -319,18 +319,21 @@ __device__ __forceinline__ Row<DTYPE, MASK> load_row(const uint4 *gv, const void
     return r;
 }
 
+// `block` of `nblocks`: the workgroup's place among the workgroups that share the tensor (the whole
+// grid for a one-tensor launch, a slice of it for a batched one); partials[block] is written.
 template <int DTYPE, bool WRITE_THROUGH, int MASK>
 __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const void *__restrict__ mask,
-                                            uint64_t n, uint64_t keep_vecs, Partial *partials)
+                                            uint64_t n, uint64_t keep_vecs, Partial *partials,
+                                            uint32_t block, uint32_t nblocks)
 {
     constexpr int EPV = DTYPE == LGN_F32 ? 4 : 8;  // elements per 16-byte vector
     constexpr int kWavesPerBlock = kBlock / kWave;
     using R = Row<DTYPE, MASK>;
     const uint64_t nvec = n / EPV;
     const uint64_t nrows = nvec / kWave;  // full rows of 64 vectors (1 KiB)
-    const uint64_t nwaves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const uint64_t nwaves = (uint64_t)nblocks * kWavesPerBlock;
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock +
+    const uint64_t wave = (uint64_t)block * kWavesPerBlock +
                           (uint64_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint4 *__restrict__ gv = reinterpret_cast<const uint4 *>(g);
 
@@ -470,7 +473,7 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
         p.n = b.m.n; p.mean = b.m.mean; p.m2 = b.m.m2;
         p.nonfinite = (uint64_t)b.nonfinite;
         p.mx = b.mx; p.nmn = b.nmn;
-        store_partial(partials + blockIdx.x, p, WRITE_THROUGH);
+        store_partial(partials + block, p, WRITE_THROUGH);
     }
 }
 
@@ -480,7 +483,7 @@ __global__ __launch_bounds__(kBlock) void stats_stage1(const void *__restrict__ 
                                                        uint64_t keep_vecs,
                                                        Partial *__restrict__ partials)
 {
-    stage1_body<DTYPE, false, MASK>(g, mask, n, keep_vecs, partials);
+    stage1_body<DTYPE, false, MASK>(g, mask, n, keep_vecs, partials, blockIdx.x, gridDim.x);
 }
 
 // Merges `count` per-block records; thread 0 writes the result to *out and, if given, to *lds_out.
@@ -563,16 +566,13 @@ struct SolveRequest {
     double scale_z;  // standard normal quantile of the scale rule (evaluated by the host)
 };
 
-template <int DTYPE, int MASK>
-__global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restrict__ g,
-                                                             const void *__restrict__ mask, uint64_t n,
-                                                             uint64_t keep_vecs,
-                                                             Partial *partials, unsigned int *ticket,
-                                                             SolveRequest rq, lgn_stats_t *st_out,
-                                                             lgn_prune_params_t *p_out,
-                                                             lgn_fp_params_t *f_out)
+// What follows a workgroup's stage 1 in the one-launch form: publish, take a ticket, and if it was
+// the last one of the tensor's `nblocks` workgroups, combine their records and solve.
+__device__ __forceinline__ void finish_and_solve(const Partial *partials, uint32_t nblocks, uint64_t n,
+                                                 unsigned int *ticket, const SolveRequest &rq,
+                                                 lgn_stats_t *st_out, lgn_prune_params_t *p_out,
+                                                 lgn_fp_params_t *f_out)
 {
-    stage1_body<DTYPE, true, MASK>(g, mask, n, keep_vecs, partials);
     __shared__ bool is_last;
     __shared__ lgn_stats_t st_lds;
     if (threadIdx.x == 0) {
@@ -584,13 +584,13 @@ __global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restr
         __builtin_amdgcn_s_waitcnt(0);
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
         is_last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                  gridDim.x - 1;
+                  nblocks - 1;
     }
     __syncthreads();
     if (!is_last) return;
     // one workgroup only: drop what this XCD's caches hold, then read every record
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    stage2_body(partials, (int)gridDim.x, n, st_out, &st_lds);
+    stage2_body(partials, (int)nblocks, n, st_out, &st_lds);
     __syncthreads();
     const int wave = threadIdx.x / kWave;
     if (wave == 0 && p_out && rq.target_sparsity >= 0.0) {
@@ -613,6 +613,63 @@ __global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restr
     }
 }
 
+template <int DTYPE, int MASK>
+__global__ __launch_bounds__(kBlock) void stats_solve_kernel(const void *__restrict__ g,
+                                                             const void *__restrict__ mask, uint64_t n,
+                                                             uint64_t keep_vecs,
+                                                             Partial *partials, unsigned int *ticket,
+                                                             SolveRequest rq, lgn_stats_t *st_out,
+                                                             lgn_prune_params_t *p_out,
+                                                             lgn_fp_params_t *f_out)
+{
+    stage1_body<DTYPE, true, MASK>(g, mask, n, keep_vecs, partials, blockIdx.x, gridDim.x);
+    finish_and_solve(partials, gridDim.x, n, ticket, rq, st_out, p_out, f_out);
+}
+
+// ---- many tensors, one launch ----------------------------------------------------------------
+// The grid is cut into one slice of workgroups per tensor (slice sizes proportional to the element
+// counts, so that all slices finish together); a workgroup finds its tensor in a table of first
+// workgroup indices, runs stage 1 on its share of that tensor, and the last workgroup of each
+// slice combines and solves for its tensor, with a ticket of its own.  The tables travel in the
+// kernel argument, so nothing has to be uploaded or allocated.
+struct BatchStatsTensor {
+    const void *g;
+    uint64_t n;
+    uint64_t keep_vecs;
+    double target_sparsity;
+    lgn_stats_t *st;
+    lgn_prune_params_t *p;
+    lgn_fp_params_t *f;
+    uint32_t blocks;
+    int16_t n_bits, e_bits;
+};
+
+struct BatchStatsArgs {
+    Partial *partials;
+    unsigned int *tickets;
+    double scale_z;
+    int32_t alpha_dtype, scale_mode, sigma_units, count;
+    uint32_t first_block[kBatchMax];  // of tensor i; 0xffffffff past the last tensor
+    BatchStatsTensor t[kBatchMax];
+};
+static_assert(sizeof(BatchStatsArgs) <= 4096, "must fit the kernel argument segment");
+
+template <int DTYPE>
+__global__ __launch_bounds__(kBlock) void stats_solve_batch_kernel(BatchStatsArgs a)
+{
+    const uint32_t b = blockIdx.x;
+    int t = 0;
+#pragma unroll
+    for (int i = 1; i < kBatchMax; ++i) t += a.first_block[i] <= b ? 1 : 0;  // uniform: scalar unit
+    t = __builtin_amdgcn_readfirstlane(t);
+    const BatchStatsTensor &T = a.t[t];
+    const uint32_t first = a.first_block[t];
+    stage1_body<DTYPE, true, 0>(T.g, nullptr, T.n, T.keep_vecs, a.partials + first, b - first, T.blocks);
+    const SolveRequest rq = {T.target_sparsity, a.alpha_dtype, T.n_bits, T.e_bits, a.scale_mode, a.sigma_units,
+                             a.scale_z};
+    finish_and_solve(a.partials + first, T.blocks, T.n, a.tickets + t, rq, T.st, T.p, T.f);
+}
+
 int stats_blocks(uint64_t n, int dtype)
 {
     const uint64_t epv = dtype == LGN_F32 ? 4 : 8;
@@ -623,12 +680,14 @@ int stats_blocks(uint64_t n, int dtype)
 }
 
 constexpr size_t kTicketOffset = sizeof(Partial) * (size_t)kMaxStatsBlocks;  // 8-byte aligned
+constexpr size_t kTicketBytes = 256;  // 64 tickets: one per tensor of a batched launch
+static_assert(kBatchMax * sizeof(unsigned int) <= kTicketBytes, "a ticket per tensor");
 
-size_t stats_workspace_bytes() { return kTicketOffset + 64; }
+size_t stats_workspace_bytes() { return kTicketOffset + kTicketBytes; }
 
 __global__ void ticket_clear_kernel(unsigned int *ticket)
 {
-    if (threadIdx.x < 16) ticket[threadIdx.x] = 0u;
+    if (threadIdx.x < kTicketBytes / sizeof(unsigned int)) ticket[threadIdx.x] = 0u;
 }
 
 hipError_t launch_workspace_init(void *ws, hipStream_t stream)
@@ -736,12 +795,61 @@ hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, ui
     return hipGetLastError();
 }
 
+// Statistics + solvers for `count` tensors in as few launches as the argument tables allow
+// (kBatchMax tensors each).  Tensor t gets a share of the grid proportional to its size.
+hipError_t launch_batch_stats_solve(const lgn_batch_item_t *items, int count, int dtype, int alpha_dtype,
+                                    int scale_mode, double scale_z, int sigma_units, void *ws,
+                                    hipStream_t stream)
+{
+    const int cap = stats_blocks_cap(dtype);
+    const uint64_t keep_total = kept_vectors();
+    for (int c0 = 0; c0 < count; c0 += kBatchMax) {
+        const int m = count - c0 < kBatchMax ? count - c0 : kBatchMax;
+        BatchStatsArgs a;
+        a.partials = static_cast<Partial *>(ws);
+        a.tickets = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset);
+        a.scale_z = scale_z;
+        a.alpha_dtype = alpha_dtype; a.scale_mode = scale_mode; a.sigma_units = sigma_units; a.count = m;
+        long double total = 0.0L;
+        for (int i = 0; i < m; ++i) total += (long double)items[c0 + i].n;
+        // leave room for the one workgroup every tensor gets at least and for the rounding, so that
+        // the slices together never exceed the records the workspace holds
+        const int room = cap < kMaxStatsBlocks - 2 * kBatchMax ? cap : kMaxStatsBlocks - 2 * kBatchMax;
+        const int budget = room > m ? room - m : 1;
+        uint32_t next = 0;
+        for (int i = 0; i < kBatchMax; ++i) {
+            a.first_block[i] = 0xffffffffu;
+            if (i >= m) { a.t[i] = BatchStatsTensor{}; continue; }
+            const lgn_batch_item_t &it = items[c0 + i];
+            int blocks = total > 0.0L ? (int)((long double)budget * (long double)it.n / total + 0.5L) : 0;
+            if (blocks > stats_blocks(it.n, dtype)) blocks = stats_blocks(it.n, dtype);
+            if (blocks < 1) blocks = 1;
+            BatchStatsTensor &T = a.t[i];
+            T.g = it.g; T.n = it.n;
+            T.keep_vecs = total > 0.0L ? (uint64_t)((long double)keep_total * (long double)it.n / total) : 0;
+            T.target_sparsity = it.target_sparsity >= 0.0 ? it.target_sparsity : -1.0;
+            T.st = it.st; T.p = it.target_sparsity >= 0.0 ? it.p : nullptr; T.f = it.n_bits ? it.f : nullptr;
+            T.blocks = (uint32_t)blocks;
+            T.n_bits = (int16_t)it.n_bits; T.e_bits = (int16_t)it.e_bits;
+            a.first_block[i] = next;
+            next += (uint32_t)blocks;
+        }
+        if (next > (uint32_t)kMaxStatsBlocks) return hipErrorInvalidValue;  // cannot happen, see `room`
+        if (dtype == LGN_F32) stats_solve_batch_kernel<LGN_F32><<<next, kBlock, 0, stream>>>(a);
+        else if (dtype == LGN_BF16) stats_solve_batch_kernel<LGN_BF16><<<next, kBlock, 0, stream>>>(a);
+        else stats_solve_batch_kernel<LGN_F16><<<next, kBlock, 0, stream>>>(a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 // ---- the same launch on a scratch array the library owns ------------------------------------
 // For callers that cannot provide a workspace because they cannot allocate one: the per-block
 // records and the ticket live in a file-scope device array (one copy per GPU the library runs
 // on, held until the process ends).  Host code never uses the array's name as an address: the
 // device address is asked for once per device and kept.
-constexpr size_t kScratchBytes = kTicketOffset + 64;
+constexpr size_t kScratchBytes = kTicketOffset + kTicketBytes;
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 static hipError_t scratch_address(void **out)

@@ -27,6 +27,17 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(const uint8_t *__restri
     }
 }
 
+// Workgroups of one tensor's streaming grid: a wave gets about LGN_TUNE_STREAM_PAIRS_PER_WAVE pairs.
+static uint64_t stream_grid(uint64_t n)
+{
+    const uint64_t npairs = ((n + 255) / 256 + 1) / 2;
+    const uint64_t per_block = (uint64_t)tuning(LGN_TUNE_STREAM_PAIRS_PER_WAVE) * (kBlock / kWave);
+    uint64_t blocks = (npairs + per_block - 1) / per_block;
+    if (blocks < 1) blocks = 1;
+    const uint64_t max_blocks = (uint64_t)device_cus() * (uint64_t)tuning(LGN_TUNE_STREAM_BLOCKS_PER_CU);
+    return blocks > max_blocks ? max_blocks : blocks;
+}
+
 hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int out_kind,
                          const StreamArgs &args, hipStream_t stream)
 {
@@ -35,20 +46,54 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
     if (dtype == LGN_F32) k = pick_stream_kernel_f32(prune, quant, rounding, out_kind);
     else if (dtype == LGN_BF16) k = pick_stream_kernel_bf16(prune, quant, rounding, out_kind);
     else k = pick_stream_kernel_f16(prune, quant, rounding, out_kind);
-    const uint64_t npairs = ((args.n + 255) / 256 + 1) / 2;  // a wave step covers two tiles
-    // A wave gets about `per_wave` pairs.  Far more workgroups than the device holds at once
+    // A wave gets about six pairs of tiles.  Far more workgroups than the device holds at once
     // (measured best at four to eight pairs per wave for every variant, i.e. ~65 workgroups per CU
     // on the 205 M-element tensor, against 8 per CU with ~50 pairs each: -10 % on the fused
     // pass): workgroups then start staggered, so the waves' load and arithmetic phases do not
     // march in step.
-    const long per_wave = tuning(LGN_TUNE_STREAM_PAIRS_PER_WAVE);
-    const uint64_t per_block = (uint64_t)per_wave * (kBlock / kWave);
-    uint64_t blocks = (npairs + per_block - 1) / per_block;
-    if (blocks < 1) blocks = 1;
-    const uint64_t max_blocks = (uint64_t)device_cus() * (uint64_t)tuning(LGN_TUNE_STREAM_BLOCKS_PER_CU);
-    if (blocks > max_blocks) blocks = max_blocks;
+    const uint64_t blocks = stream_grid(args.n);
     hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(kBlock), 0, stream, args);
     return hipGetLastError();
+}
+
+// The fused pass over `count` tensors, kBatchMax tensors per launch.  Empty tensors get no
+// workgroups.
+hipError_t launch_batch_stream(const lgn_batch_item_t *items, int count, int dtype, int rounding,
+                               int out_kind, hipStream_t stream)
+{
+    StreamBatchKernel k;
+    if (dtype == LGN_F32) k = pick_stream_batch_kernel_f32(rounding, out_kind);
+    else if (dtype == LGN_BF16) k = pick_stream_batch_kernel_bf16(rounding, out_kind);
+    else k = pick_stream_batch_kernel_f16(rounding, out_kind);
+    int i = 0;
+    while (i < count) {
+        BatchStreamArgs a;
+        uint64_t next = 0;
+        int m = 0;
+        for (int j = 0; j < kBatchMax; ++j) {
+            a.first_block[j] = 0xffffffffu;
+            a.t[j] = BatchStreamTensor{};
+        }
+        // fill the table with the next non-empty tensors, as long as the grid index fits 31 bits
+        while (i < count && m < kBatchMax) {
+            const lgn_batch_item_t &it = items[i];
+            if (it.n == 0) { ++i; continue; }
+            const uint64_t blocks = stream_grid(it.n);
+            if (m > 0 && next + blocks > 0x7fffffffull) break;
+            BatchStreamTensor &T = a.t[m];
+            T.g = it.g; T.out = it.out; T.n = it.n; T.p = it.p; T.f = it.f;
+            T.k0 = (uint32_t)it.seed; T.k1 = (uint32_t)(it.seed >> 32);
+            T.blocks = (uint32_t)blocks;
+            a.first_block[m] = (uint32_t)next;
+            next += blocks;
+            ++m; ++i;
+        }
+        if (m == 0) break;
+        hipLaunchKernelGGL(k, dim3((unsigned)next), dim3(kBlock), 0, stream, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_dequant(const void *codes, uint64_t n, int in_kind, const lgn_fp_params_t *f,

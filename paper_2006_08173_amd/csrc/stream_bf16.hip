@@ -8,4 +8,9 @@ StreamKernel pick_stream_kernel_bf16(bool prune, bool quant, int rounding, int o
     return pick_kernel<LGN_BF16>(prune, quant, rounding, out_kind);
 }
 
+StreamBatchKernel pick_stream_batch_kernel_bf16(int rounding, int out_kind)
+{
+    return pick_batch_kernel<LGN_BF16>(rounding, out_kind);
+}
+
 }  // namespace lgn

@@ -8,4 +8,9 @@ StreamKernel pick_stream_kernel_f16(bool prune, bool quant, int rounding, int ou
     return pick_kernel<LGN_F16>(prune, quant, rounding, out_kind);
 }
 
+StreamBatchKernel pick_stream_batch_kernel_f16(int rounding, int out_kind)
+{
+    return pick_batch_kernel<LGN_F16>(rounding, out_kind);
+}
+
 }  // namespace lgn

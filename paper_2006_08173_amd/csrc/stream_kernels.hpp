@@ -434,8 +434,9 @@ __device__ __forceinline__ void walk_pairs(const WalkState &s)
     }
 }
 
+// One workgroup's share of a tensor: workgroup `block` of the `nblocks` that walk it.
 template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
-__global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT)) void stream_kernel(StreamArgs a)
+__device__ __forceinline__ void stream_body(const StreamArgs &a, uint32_t block, uint32_t nblocks)
 {
     WalkState s;
     s.a = a;
@@ -447,9 +448,9 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
     if (QUANT) load_quant_const(a.f, s.q);
     const QuantConst &q = s.q;
     s.ntiles = (a.n + 255) / 256;
-    s.nwaves = (uint64_t)gridDim.x * (kBlock / kWave);
+    s.nwaves = (uint64_t)nblocks * (kBlock / kWave);
     s.lane = threadIdx.x & (kWave - 1);
-    s.wave = (uint64_t)blockIdx.x * (kBlock / kWave) +
+    s.wave = (uint64_t)block * (kBlock / kWave) +
              (uint64_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     s.packed_total = (a.n * (uint64_t)q.n_bits + 7) / 8;
     s.pk = pack_lane(q.n_bits, s.lane);
@@ -491,6 +492,61 @@ __global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT))
         walk_pairs<DTYPE, PRUNE, false, QUANT, ROUND, OUT, true>(s);
 }
 
+
+template <int DTYPE, bool PRUNE, bool QUANT, int ROUND, int OUT>
+__global__ __launch_bounds__(kBlock, stream_min_waves(PRUNE, QUANT, ROUND, OUT)) void stream_kernel(StreamArgs a)
+{
+    stream_body<DTYPE, PRUNE, QUANT, ROUND, OUT>(a, blockIdx.x, gridDim.x);
+}
+
+// ---- many tensors, one launch: the fused pass ------------------------------------------------
+// The grid is the concatenation of the grids the one-tensor launches would use; a workgroup finds
+// its tensor in a table of first workgroup indices (kernel argument) and then does exactly what it
+// would do in that tensor's own launch, so the output is the same, bit for bit.
+struct BatchStreamTensor {
+    const void *g;
+    void *out;
+    uint64_t n;
+    const lgn_prune_params_t *p;
+    const lgn_fp_params_t *f;
+    uint32_t k0, k1;
+    uint32_t blocks, reserved;
+};
+
+struct BatchStreamArgs {
+    uint32_t first_block[kBatchMax];  // of tensor i; 0xffffffff past the last tensor
+    BatchStreamTensor t[kBatchMax];
+};
+static_assert(sizeof(BatchStreamArgs) <= 4096, "must fit the kernel argument segment");
+
+template <int DTYPE, int ROUND, int OUT>
+__global__ __launch_bounds__(kBlock, stream_min_waves(true, true, ROUND, OUT)) void stream_batch_kernel(BatchStreamArgs a)
+{
+    const uint32_t b = blockIdx.x;
+    int t = 0;
+#pragma unroll
+    for (int i = 1; i < kBatchMax; ++i) t += a.first_block[i] <= b ? 1 : 0;  // uniform: scalar unit
+    t = __builtin_amdgcn_readfirstlane(t);
+    const BatchStreamTensor &T = a.t[t];
+    const StreamArgs one = {T.g, T.out, T.n, 0ull, T.p, T.f, T.k0, T.k1};
+    stream_body<DTYPE, true, true, ROUND, OUT>(one, b - a.first_block[t], T.blocks);
+}
+
+using StreamBatchKernel = void (*)(BatchStreamArgs);
+
+template <int DTYPE>
+StreamBatchKernel pick_batch_kernel(int rounding, int out_kind)
+{
+    if (rounding == LGN_ROUND_STOCHASTIC) {
+        if (out_kind == LGN_OUT_VALUE) return stream_batch_kernel<DTYPE, LGN_ROUND_STOCHASTIC, LGN_OUT_VALUE>;
+        if (out_kind == LGN_OUT_CODE8) return stream_batch_kernel<DTYPE, LGN_ROUND_STOCHASTIC, LGN_OUT_CODE8>;
+        return stream_batch_kernel<DTYPE, LGN_ROUND_STOCHASTIC, LGN_OUT_PACKED>;
+    }
+    if (out_kind == LGN_OUT_VALUE) return stream_batch_kernel<DTYPE, LGN_ROUND_NEAREST_EVEN, LGN_OUT_VALUE>;
+    if (out_kind == LGN_OUT_CODE8) return stream_batch_kernel<DTYPE, LGN_ROUND_NEAREST_EVEN, LGN_OUT_CODE8>;
+    return stream_batch_kernel<DTYPE, LGN_ROUND_NEAREST_EVEN, LGN_OUT_PACKED>;
+}
+
 using StreamKernel = void (*)(StreamArgs);
 
 template <int DTYPE, bool PRUNE, bool QUANT>
@@ -520,5 +576,8 @@ StreamKernel pick_kernel(bool prune, bool quant, int rounding, int out_kind)
 StreamKernel pick_stream_kernel_f32(bool prune, bool quant, int rounding, int out_kind);
 StreamKernel pick_stream_kernel_bf16(bool prune, bool quant, int rounding, int out_kind);
 StreamKernel pick_stream_kernel_f16(bool prune, bool quant, int rounding, int out_kind);
+StreamBatchKernel pick_stream_batch_kernel_f32(int rounding, int out_kind);
+StreamBatchKernel pick_stream_batch_kernel_bf16(int rounding, int out_kind);
+StreamBatchKernel pick_stream_batch_kernel_f16(int rounding, int out_kind);
 
 }  // namespace lgn

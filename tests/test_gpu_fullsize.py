@@ -264,3 +264,37 @@ def test_config3_twenty_tensors_on_three_streams(lgn):
                                 c["rng_seed"], 0, O.OUT_CODE8)
         assert np.array_equal(it["out"].cpu().numpy(), want), c["name"]
         it["g"] = None
+
+
+def test_config3_batched_on_one_stream(lgn):
+    """Configuration 3 as written: twenty tensors back to back on ONE stream, here as one batched
+    statistics+solve launch and one batched fused launch (issued twice without a host synchronisation
+    in between).  Per tensor: statistics agree with the oracle, parameters are the oracle's for those
+    statistics, every code is the oracle's."""
+    tensors = SI.config_c3()
+    items = []
+    for cfg in tensors:
+        g, d = upload(cfg)
+        items.append(dict(cfg=cfg, host=g, g=d, out=torch.empty(cfg["n"], dtype=torch.uint8, device="cuda"),
+                          st=torch.empty(72, dtype=torch.uint8, device="cuda"),
+                          p=torch.empty(24, dtype=torch.uint8, device="cuda"),
+                          f=torch.empty(32, dtype=torch.uint8, device="cuda"),
+                          target_sparsity=cfg["sparsity"], n_bits=cfg["n_bits"], seed=cfg["rng_seed"]))
+    batch = lgn.make_batch(items)
+    torch.cuda.synchronize()
+    for _ in range(2):
+        lgn.lgn_batch_stats_solve(batch)
+        lgn.lgn_batch_prune_quantize_fused(batch, O.ROUND_STOCHASTIC, out_kind=O.OUT_CODE8)
+    torch.cuda.synchronize()
+    for it in items:
+        c, g = it["cfg"], it["host"]
+        hs, hp, hf = lgn.read_stats(it["st"]), lgn.read_prune_params(it["p"]), lgn.read_fp_params(it["f"])
+        stats_close(hs, O.stats(g))
+        same_in = oracle_stats_like(hs)
+        op, of = O.threshold(same_in, c["sparsity"]), O.fp_params(same_in, c["n_bits"])
+        assert np.float32(hp.alpha) == np.float32(op.alpha), c["name"]
+        assert (hf.e_bits, hf.m_bits, hf.scale_exp) == (of.e_bits, of.m_bits, of.scale_exp), c["name"]
+        want = O.prune_quantize(g, hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp, O.ROUND_STOCHASTIC,
+                                c["rng_seed"], 0, O.OUT_CODE8)
+        assert np.array_equal(it["out"].cpu().numpy(), want), c["name"]
+        it["host"] = None

@@ -24,7 +24,7 @@ def _structs(device="cuda"):
 
 
 def test_static_entry_point_matches_the_workspace_form_on_calls_in_a_row(lgn):
-    assert lgn.lgn_static_scratch_bytes() == 40 * 2048 + 64
+    assert lgn.lgn_static_scratch_bytes() == 40 * 2048 + 256
     big = SI.lognormal_tensor(3_000_001, seed=41, mu=-11.0, sigma=2.2, zero_frac=0.25)
     big[[7, 1_000_000]] = [np.nan, np.inf]
     small = SI.lognormal_tensor(70_001, seed=42, mu=-8.0, sigma=1.4, zero_frac=0.5)
