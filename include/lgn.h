@@ -153,8 +153,9 @@ typedef struct lgn_fp_params_t {
  *                                  (default 224, range 0..4096)
  *   LGN_TUNE_STATS_BLOCKS_PER_CU   workgroups per compute unit of the statistics pass; 0 = by
  *                                  element type (2 for fp32, 6 for 16-bit types) (range 0..8)
- *   LGN_TUNE_STREAM_PAIRS_PER_WAVE tile pairs (512 elements) a wave of a streaming kernel walks
- *                                  (default 6, range 1..4096)
+ *   LGN_TUNE_STREAM_PAIRS_PER_WAVE tile pairs (512 elements) a wave of a streaming kernel walks;
+ *                                  0 = by element type (6 for fp32, 24 for 16-bit types)
+ *                                  (default 0, range 0..4096)
  *   LGN_TUNE_STREAM_BLOCKS_PER_CU  upper limit of the streaming grid in workgroups per compute
  *                                  unit (default 1024, range 1..1024)
  * lgn_set_tuning returns LGN_ERR_INVALID_ARG for an unknown knob or a value out of range.

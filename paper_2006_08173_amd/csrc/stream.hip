@@ -27,11 +27,21 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(const uint8_t *__restri
     }
 }
 
-// Workgroups of one tensor's streaming grid: a wave gets about LGN_TUNE_STREAM_PAIRS_PER_WAVE pairs.
-static uint64_t stream_grid(uint64_t n)
+// Workgroups of one tensor's streaming grid.  A wave gets a few pairs of tiles, so that there are
+// far more workgroups than the device holds at once: they start staggered, and the waves' load
+// and arithmetic phases do not march in step (fp32, fused pass of 205 M elements: 8 workgroups per
+// CU with ~50 pairs per wave 0.200 ms, ~65 per CU with 6 pairs 0.180 ms).  The passes over fp32
+// tensors are bound by memory and like 3 to 6 pairs (fused pass after a statistics pass: 282.6 /
+// 283.7 / 284.5 / 288 / 291 / 298 us per step at 3 / 4 / 6 / 8 / 12 / 16).  The 16-bit types carry
+// twice the elements per byte and are bound by instruction issue; there the per-wave set-up
+// weighs more than the staggering (10^9 bf16 elements to packed 6-bit codes: 752 / 687 / 669 / 660 /
+// 655 / 651 / 651 / 653 us at 3 / 6 / 8 / 12 / 16 / 24 / 32 / 48).
+static uint64_t stream_grid(uint64_t n, int dtype)
 {
     const uint64_t npairs = ((n + 255) / 256 + 1) / 2;
-    const uint64_t per_block = (uint64_t)tuning(LGN_TUNE_STREAM_PAIRS_PER_WAVE) * (kBlock / kWave);
+    const long knob = tuning(LGN_TUNE_STREAM_PAIRS_PER_WAVE);
+    const uint64_t per_wave = knob > 0 ? (uint64_t)knob : (dtype == LGN_F32 ? 6 : 24);
+    const uint64_t per_block = per_wave * (kBlock / kWave);
     uint64_t blocks = (npairs + per_block - 1) / per_block;
     if (blocks < 1) blocks = 1;
     const uint64_t max_blocks = (uint64_t)device_cus() * (uint64_t)tuning(LGN_TUNE_STREAM_BLOCKS_PER_CU);
@@ -46,12 +56,7 @@ hipError_t launch_stream(int dtype, bool prune, bool quant, int rounding, int ou
     if (dtype == LGN_F32) k = pick_stream_kernel_f32(prune, quant, rounding, out_kind);
     else if (dtype == LGN_BF16) k = pick_stream_kernel_bf16(prune, quant, rounding, out_kind);
     else k = pick_stream_kernel_f16(prune, quant, rounding, out_kind);
-    // A wave gets about six pairs of tiles.  Far more workgroups than the device holds at once
-    // (measured best at four to eight pairs per wave for every variant, i.e. ~65 workgroups per CU
-    // on the 205 M-element tensor, against 8 per CU with ~50 pairs each: -10 % on the fused
-    // pass): workgroups then start staggered, so the waves' load and arithmetic phases do not
-    // march in step.
-    const uint64_t blocks = stream_grid(args.n);
+    const uint64_t blocks = stream_grid(args.n, dtype);
     hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(kBlock), 0, stream, args);
     return hipGetLastError();
 }
@@ -78,7 +83,7 @@ hipError_t launch_batch_stream(const lgn_batch_item_t *items, int count, int dty
         while (i < count && m < kBatchMax) {
             const lgn_batch_item_t &it = items[i];
             if (it.n == 0) { ++i; continue; }
-            const uint64_t blocks = stream_grid(it.n);
+            const uint64_t blocks = stream_grid(it.n, dtype);
             if (m > 0 && next + blocks > 0x7fffffffull) break;
             BatchStreamTensor &T = a.t[m];
             T.g = it.g; T.out = it.out; T.n = it.n; T.p = it.p; T.f = it.f;

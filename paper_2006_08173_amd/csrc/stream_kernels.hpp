@@ -100,8 +100,10 @@ __device__ __forceinline__ void pack_store_n(const PackLane &p, int lane, uint32
                                              uint8_t *tile_out, uint64_t bytes_valid)
 {
     uint32_t dword = chunk >> p.o;
-    // 64-bit shifts: a shift of 32 or more leaves nothing in the low word
-    if (p.neighbours >= 1) dword |= (uint32_t)((uint64_t)from_lane_above<1>(chunk) << p.s1);
+    // 64-bit shifts: a shift of 32 or more leaves nothing in the low word.  The first neighbour is
+    // merged unconditionally (for N = 8, where no dword spans two lanes, its shift is 32): the
+    // common formats then run without a branch here.
+    dword |= (uint32_t)((uint64_t)from_lane_above<1>(chunk) << p.s1);
     if (p.neighbours >= 2) dword |= (uint32_t)((uint64_t)from_lane_above<2>(chunk) << p.s2);
     if (p.neighbours >= 3) dword |= (uint32_t)((uint64_t)from_lane_above<3>(chunk) << p.s3);
     if (p.owns) {
@@ -153,8 +155,8 @@ __device__ __forceinline__ uint32_t fast_code(uint32_t bits, uint32_t a, bool ke
         // 2^32, and the re-biased magnitude code stays below the sign bit, so nothing carries.
         // Written as asm so that the sum stays one v_mad_u64_u32 with a ready-made addend.
         const uint64_t addend = ((uint64_t)(((bits >> 31) << c.sshift) + c.sub_hi) << 32) | ((w << 16) | 0x8000u);
-        uint64_t r;
-        asm("v_mad_u64_u32 %0, vcc, %1, %2, %3" : "=v"(r) : "v"(a), "s"(c.rmul), "v"(addend) : "vcc");
+        uint64_t r, carry;  // the carry-out goes to a scalar pair of the allocator's choice, not vcc
+        asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(r), "=s"(carry) : "v"(a), "s"(c.rmul), "v"(addend));
         code = (uint32_t)(r >> 32);
     } else {
         const uint32_t y = a - c.sub;
@@ -204,6 +206,11 @@ __device__ __forceinline__ void fast_tile(const StreamArgs &a, uint64_t tile, ui
     if (DO_PRUNE || (QUANT && ROUND == LGN_ROUND_STOCHASTIC)) {
         const uint64_t p0 = (uint64_t)kPhiloxM0 * q_lo;
         philox_finish((uint32_t)(p0 >> 32), (uint32_t)p0, q_hi, key, w);
+        // Two of the four words are low halves of products; without this the compiler turns their
+        // later shift by 16 into a second multiply by M << 16 plus an or (two instructions where
+        // one shift-or does).
+#pragma unroll
+        for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(w[t]));
     }
 
     uint32_t mag_in[4];
