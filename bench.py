@@ -74,13 +74,19 @@ def parse():
                          "for all tensors, or one chain per tensor dealt to --streams streams")
     ap.add_argument("--streams", type=int, default=1, help="workload c3, --c3-mode streams: number of HIP streams")
     ap.add_argument("--evict", action="store_true",
-                    help="cache-evicting variant: a 512 MB buffer is rewritten before every timed step (outside "
-                         "the events), so nothing of the tensor is left in the memory-side cache; per-step "
-                         "times then come from the events alone")
+                    help="cache-evicting variant: a 512 MB buffer is read before every timed step (outside the "
+                         "events), so nothing of the tensor is left in the memory-side cache from the step before; "
+                         "per-step times then come from the events alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-beyond", action="store_true", help="skip the timings of the rows beyond the hot path")
     ap.add_argument("--no-keep0", action="store_true", help="skip the extra loop with the statistics pass all streaming")
     ap.add_argument("--table-out", default=None, help="--workload all: also write the table as text to this file")
+    ap.add_argument("--cold-trace", default=None, metavar="FILE",
+                    help="one-tensor workloads: instead of the plain cold pass, run 300 steps straight after the idle "
+                         "period with events on every step and write the per-step kernel times to FILE")
+    ap.add_argument("--touch-outputs", action="store_true",
+                    help="write the output and struct buffers once before anything is timed (to tell first-touch "
+                         "effects from clock effects in a cold trace)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one plain elementwise copy of the tensor before the timed region "
                          "(known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -112,7 +118,7 @@ class Runner:
         self.torch, self.args, self.step, self.n_marks = torch, args, step, n_marks
         self.evict_buf = None
         if args.evict:
-            self.evict_buf = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda")
+            self.evict_buf = torch.zeros(128 << 20, dtype=torch.int32, device="cuda")   # 512 MB
 
     def _wall(self, warmup, steps):
         t = self.torch
@@ -149,7 +155,8 @@ class Runner:
         t0 = time.perf_counter()
         for k in range(args.steps):
             if self.evict_buf is not None:
-                self.evict_buf.add_(1)   # ordinary loads and stores over 512 MB: replaces the cache's contents
+                self.evict_buf.sum()     # ordinary loads over 512 MB replace what the 256 MB cache held and
+                                         # leave nothing dirty behind that the next kernel would have to wait for
             self.step(marks[k])
         t.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / args.steps
@@ -178,10 +185,45 @@ def summarize(spans):
             "per_launch_median_ms": [round(statistics.median(c), 4) for c in cols]}
 
 
+def cold_trace(torch, args, step, path):
+    """300 steps from cold with events around every launch; writes a table, returns the mean of the
+    first warmup + steps step spans (what a cold pass of the requested size would have seen)."""
+    k = 300
+    marks = [[] for _ in range(k)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for m in marks:
+        step(m)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / k
+    spans = [[m[i].elapsed_time(m[i + 1]) * 1e3 for i in range(len(m) - 1)] for m in marks]
+    tot = [sum(s) for s in spans]
+    with open(path, "w") as f:
+        f.write("python3 bench.py " + " ".join(sys.argv[1:]) + "\n")
+        f.write(f"{k} steps straight after the idle period of data generation, HIP events around every launch "
+                f"(wall clock {wall * 1e3:.1f} us per step including the event records)\n")
+        f.write("step | " + " | ".join(f"launch {i + 1} us" for i in range(len(spans[0]))) + " | step us\n")
+        for i in list(range(40)) + list(range(40, k, 10)):
+            f.write(f"{i} | " + " | ".join(f"{x:.1f}" for x in spans[i]) + f" | {tot[i]:.1f}\n")
+        for lo, hi in ((0, 5), (5, 25), (25, 100), (100, 200), (200, 300)):
+            seg = tot[lo:hi]
+            cols = list(zip(*spans[lo:hi]))
+            f.write(f"steps [{lo},{hi}): mean step {statistics.fmean(seg):.1f} us, median {statistics.median(seg):.1f}, "
+                    f"min {min(seg):.1f}; per launch mean " + ", ".join(f"{statistics.fmean(c):.1f}" for c in cols) + "\n")
+    w, s_ = args.warmup, args.steps
+    seg = tot[min(w, k - 1):min(w + s_, k)]
+    return statistics.fmean(seg) * 1e-3
+
+
 def protocol(torch, args, step, n_marks):
     r = Runner(torch, args, step, n_marks)
     out = {}
-    if args.precondition_ms > 0:
+    if args.cold_trace:
+        out["cold_ms_per_step"] = round(cold_trace(torch, args, step, args.cold_trace), 4)
+        pms, psteps = r.precondition()
+        out["preconditioning_ms"] = round(pms, 1)
+        out["preconditioning_steps"] = psteps
+    elif args.precondition_ms > 0:
         out["cold_ms_per_step"] = round(r.cold(), 4)
         pms, psteps = r.precondition()
         out["preconditioning_ms"] = round(pms, 1)
@@ -386,6 +428,11 @@ def bench_one(args, name, lgn, SI, torch, np):
         fused_bytes = n * (in_bytes + out_bytes_per_elem)
         what = (f"stats+threshold(S={sparsity})+FP{n_bits} format+fused prune/quantize, {args.rounding} rounding, "
                 f"{ok_name} output, " + ("2 launches (stats+solvers merged, fused)" if merged else "4 launches"))
+
+    if args.touch_outputs:
+        for buf in (out, st, pp, fp):
+            buf.zero_()
+        torch.cuda.synchronize()
 
     if args.copy_probe and cfg["dtype"] == SI.F32:
         probe = torch.empty_like(d)
