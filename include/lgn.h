@@ -158,12 +158,19 @@ typedef struct lgn_fp_params_t {
  *                                  (default 0, range 0..4096)
  *   LGN_TUNE_STREAM_BLOCKS_PER_CU  upper limit of the streaming grid in workgroups per compute
  *                                  unit (default 1024, range 1..1024)
+ *   LGN_TUNE_STATS_STRICT_PUBLISH  1 (default): in the one-launch statistics forms a workgroup issues
+ *                                  a device-scope release fence between writing its record and
+ *                                  taking its ticket, as the memory model asks (4 us on an 822 MB
+ *                                  tensor).  0: it only waits for its write-through stores to
+ *                                  complete, which makes them visible device-wide on this hardware
+ *                                  but is no promise of the memory model.  Results are identical.
  * lgn_set_tuning returns LGN_ERR_INVALID_ARG for an unknown knob or a value out of range.
  */
 #define LGN_TUNE_STATS_KEEP_MB 0
 #define LGN_TUNE_STATS_BLOCKS_PER_CU 1
 #define LGN_TUNE_STREAM_PAIRS_PER_WAVE 2
 #define LGN_TUNE_STREAM_BLOCKS_PER_CU 3
+#define LGN_TUNE_STATS_STRICT_PUBLISH 4
 int lgn_set_tuning(int knob, long value);
 long lgn_get_tuning(int knob); /* -1 for an unknown knob */
 

@@ -30,6 +30,7 @@ LGN_HIST_BINS = 2048
 LGN_ALLOC_LOWERED, LGN_ALLOC_CAPPED = 1, 2
 LGN_TUNE_STATS_KEEP_MB, LGN_TUNE_STATS_BLOCKS_PER_CU = 0, 1
 LGN_TUNE_STREAM_PAIRS_PER_WAVE, LGN_TUNE_STREAM_BLOCKS_PER_CU = 2, 3
+LGN_TUNE_STATS_STRICT_PUBLISH = 4
 
 
 class LgnStats(C.Structure):

@@ -560,7 +560,7 @@ __global__ __launch_bounds__(kBlock) void stats_stage2(const Partial *__restrict
 // lives at the end of the workspace, must be zero on entry and is reset to zero on exit.
 struct SolveRequest {
     double target_sparsity;  // < 0: no threshold asked for
-    int alpha_dtype;
+    int alpha_dtype;         // bit 8: publish the per-block record with a release fence
     int n_bits;              // 0: no format asked for
     int e_bits, scale_mode, sigma_units;
     double scale_z;  // standard normal quantile of the scale rule (evaluated by the host)
@@ -583,6 +583,11 @@ __device__ __forceinline__ void finish_and_solve(const Partial *partials, uint32
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
         __builtin_amdgcn_s_waitcnt(0);
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        // The release fence the memory model asks for between the record and the ticket (one
+        // wave per workgroup issues it: +4 us on an 822 MB tensor).  With the knob
+        // LGN_TUNE_STATS_STRICT_PUBLISH at 0 it is left out: completed write-through stores are
+        // visible device-wide on this hardware, but that is behaviour, not a promise.
+        if (rq.alpha_dtype & 0x100) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         is_last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   nblocks - 1;
     }
@@ -594,7 +599,7 @@ __device__ __forceinline__ void finish_and_solve(const Partial *partials, uint32
     __syncthreads();
     const int wave = threadIdx.x / kWave;
     if (wave == 0 && p_out && rq.target_sparsity >= 0.0) {
-        threshold_body<true>(&st_lds, rq.target_sparsity, rq.alpha_dtype, p_out);
+        threshold_body<true>(&st_lds, rq.target_sparsity, rq.alpha_dtype & 0xff, p_out);
     } else if (wave == 1 && f_out && rq.n_bits != 0) {
         fp_params_body(&st_lds, rq.n_bits, rq.e_bits, rq.scale_mode, rq.scale_z, rq.sigma_units, f_out);
     }
@@ -789,7 +794,8 @@ hipError_t launch_stats_solve(const void *g, const void *mask, int mask_kind, ui
     if (blocks > stats_blocks_cap(dtype)) blocks = stats_blocks_cap(dtype);
     Partial *partials = static_cast<Partial *>(ws);
     unsigned int *ticket = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset);
-    const SolveRequest rq = {target_sparsity, alpha_dtype, n_bits, e_bits, scale_mode, sigma_units, scale_z};
+    const int strict = tuning(LGN_TUNE_STATS_STRICT_PUBLISH) ? 0x100 : 0;
+    const SolveRequest rq = {target_sparsity, alpha_dtype | strict, n_bits, e_bits, scale_mode, sigma_units, scale_z};
     dispatch_dtype_mask(dtype, mask_kind,
                         SolveLaunch{g, mask, n, partials, ticket, rq, st, p, f, blocks, stream});
     return hipGetLastError();
@@ -809,7 +815,7 @@ hipError_t launch_batch_stats_solve(const lgn_batch_item_t *items, int count, in
         a.partials = static_cast<Partial *>(ws);
         a.tickets = reinterpret_cast<unsigned int *>(static_cast<char *>(ws) + kTicketOffset);
         a.scale_z = scale_z;
-        a.alpha_dtype = alpha_dtype; a.scale_mode = scale_mode; a.sigma_units = sigma_units; a.count = m;
+        a.alpha_dtype = alpha_dtype | (tuning(LGN_TUNE_STATS_STRICT_PUBLISH) ? 0x100 : 0); a.scale_mode = scale_mode; a.sigma_units = sigma_units; a.count = m;
         long double total = 0.0L;
         for (int i = 0; i < m; ++i) total += (long double)items[c0 + i].n;
         // leave room for the one workgroup every tensor gets at least and for the rounding, so that

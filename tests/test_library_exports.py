@@ -48,13 +48,15 @@ def test_host_only_helpers():
 
 def test_tuning_knobs_are_host_state_only():
     for knob, default in ((lgn.LGN_TUNE_STATS_KEEP_MB, 224), (lgn.LGN_TUNE_STATS_BLOCKS_PER_CU, 0),
-                          (lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 0), (lgn.LGN_TUNE_STREAM_BLOCKS_PER_CU, 1024)):
+                          (lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 0), (lgn.LGN_TUNE_STREAM_BLOCKS_PER_CU, 1024),
+                          (lgn.LGN_TUNE_STATS_STRICT_PUBLISH, 1)):
         assert lgn.lgn_get_tuning(knob) == default
     lgn.lgn_set_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 12)
     assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE) == 12
     lgn.lgn_set_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, -1)
     assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE) == 0
-    for knob, bad in ((lgn.LGN_TUNE_STATS_KEEP_MB, 5000), (lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 5000), (9, 1)):
+    for knob, bad in ((lgn.LGN_TUNE_STATS_KEEP_MB, 5000), (lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 5000),
+                      (lgn.LGN_TUNE_STATS_STRICT_PUBLISH, 2), (9, 1)):
         try:
             lgn.lgn_set_tuning(knob, bad)
         except lgn.LgnError as e:
