@@ -32,7 +32,8 @@
  *   - the prefix code of the appendix "Encoding" is laid out as a bit stream in which stream bit
  *     k is bit (k & 7) of byte k >> 3, codewords are written first symbol first, the value that
  *     follows "11" is the element's own bit pattern (32, 16 or N bits) least significant bit
- *     first, and every chunk of 4096 elements starts on a 32-bit boundary listed in a table.
+ *     first, every chunk of 4096 elements starts on a 32-bit boundary listed in a table, and the
+ *     bit lengths of a chunk's 16 sub-blocks of 256 elements are listed beside it.
  *
  * Pins (tests/test_oracle_*.py): Philox known-answer vectors; Table 2 of the paper for the
  * format choice; quadrature of the sparsity definition (the expectation over the uniform
@@ -646,8 +647,13 @@ float orc_prune_one(float x, float alpha, uint32_t w) { return prune_one(x, alph
  * Container (this build's choice, the paper gives the codewords only): chunks of 4096 elements,
  * each starting on a 32-bit boundary; table[c] = index of the first 32-bit word of chunk c,
  * table[nchunks] = total number of words, table[nchunks + 1] = 0 (status, no overflow here).
+ * A chunk is further divided into 16 sub-blocks of 256 elements whose lengths in bits are listed
+ * (sub[16 c + j], 16-bit numbers; 0 for a sub-block past the end of the tensor), so that decoding
+ * can start at any multiple of 256 elements: sub-block j of chunk c begins at stream bit
+ * 32 table[c] + sub[16 c] + ... + sub[16 c + j - 1].
  * ------------------------------------------------------------------------------------------ */
 #define ORC_PREFIX_CHUNK 4096u
+#define ORC_PREFIX_SUB 256u
 
 static uint32_t raw_pattern(const void *in, uint64_t i, int width)
 {
@@ -678,10 +684,10 @@ uint64_t orc_prefix_bound_bytes(uint64_t n, int width)
     return orc_prefix_chunks(n) * words_per_chunk * 4u;
 }
 
-/* Fills table (nchunks + 2 entries) and, if out is not NULL, the zero-initialised stream.
- * Returns the number of bytes of the stream. */
+/* Fills table (nchunks + 2 entries), sub (16 nchunks entries, if not NULL) and, if out is not
+ * NULL, the zero-initialised stream.  Returns the number of bytes of the stream. */
 uint64_t orc_prefix_encode(const void *in, uint64_t n, int width, uint32_t special, uint8_t *out,
-                           uint64_t *table)
+                           uint64_t *table, uint16_t *sub)
 {
     const uint64_t nchunks = orc_prefix_chunks(n);
     int64_t c;
@@ -689,7 +695,13 @@ uint64_t orc_prefix_encode(const void *in, uint64_t n, int width, uint32_t speci
     for (c = 0; c < (int64_t)nchunks; ++c) {
         uint64_t bits = 0, i = (uint64_t)c * ORC_PREFIX_CHUNK;
         const uint64_t end = i + ORC_PREFIX_CHUNK < n ? i + ORC_PREFIX_CHUNK : n;
-        for (; i < end; ++i) bits += symbol_bits(raw_pattern(in, i, width), width, special);
+        unsigned j;
+        if (sub) for (j = 0; j < 16u; ++j) sub[16 * c + j] = 0;
+        for (; i < end; ++i) {
+            const unsigned len = symbol_bits(raw_pattern(in, i, width), width, special);
+            bits += len;
+            if (sub) sub[16 * c + (i - (uint64_t)c * ORC_PREFIX_CHUNK) / ORC_PREFIX_SUB] += (uint16_t)len;
+        }
         table[c + 1] = (bits + 31u) / 32u; /* words of this chunk, turned into offsets below */
     }
     table[0] = 0;
@@ -737,6 +749,36 @@ void orc_prefix_decode(const uint8_t *stream, const uint64_t *table, uint64_t n,
                 if (get_bit(stream, k++)) {
                     int b;
                     for (b = 0; b < width; ++b) v |= (uint32_t)get_bit(stream, k++) << b;
+                } else {
+                    v = special | ((uint32_t)get_bit(stream, k++) << (width - 1));
+                }
+            }
+            if (width == 32) ((uint32_t *)out)[i] = v;
+            else if (width == 16) ((uint16_t *)out)[i] = (uint16_t)v;
+            else ((uint8_t *)out)[i] = (uint8_t)v;
+        }
+    }
+}
+
+/* Decodes every sub-block of 256 elements on its own, from the bit position the container gives
+ * for it: what the list of sub-block lengths is for. */
+void orc_prefix_decode_sub(const uint8_t *stream, const uint64_t *table, const uint16_t *sub,
+                           uint64_t n, int width, uint32_t special, void *out)
+{
+    const uint64_t nsub = (n + ORC_PREFIX_SUB - 1u) / ORC_PREFIX_SUB;
+    int64_t b;
+#pragma omp parallel for num_threads(g_threads)
+    for (b = 0; b < (int64_t)nsub; ++b) {
+        const uint64_t c = (uint64_t)b / 16u, j = (uint64_t)b % 16u;
+        uint64_t k = table[c] * 32u, i = (uint64_t)b * ORC_PREFIX_SUB, t;
+        const uint64_t end = i + ORC_PREFIX_SUB < n ? i + ORC_PREFIX_SUB : n;
+        for (t = 0; t < j; ++t) k += sub[16 * c + t];
+        for (; i < end; ++i) {
+            uint32_t v = 0;
+            if (get_bit(stream, k++)) {
+                if (get_bit(stream, k++)) {
+                    int q;
+                    for (q = 0; q < width; ++q) v |= (uint32_t)get_bit(stream, k++) << q;
                 } else {
                     v = special | ((uint32_t)get_bit(stream, k++) << (width - 1));
                 }

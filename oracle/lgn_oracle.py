@@ -110,9 +110,10 @@ def lib():
         L.orc_prefix_chunks.restype = u64
         L.orc_prefix_bound_bytes.argtypes = [u64, i32]
         L.orc_prefix_bound_bytes.restype = u64
-        L.orc_prefix_encode.argtypes = [vp, u64, i32, u32, vp, vp]
+        L.orc_prefix_encode.argtypes = [vp, u64, i32, u32, vp, vp, vp]
         L.orc_prefix_encode.restype = u64
         L.orc_prefix_decode.argtypes = [vp, vp, u64, i32, u32, vp]
+        L.orc_prefix_decode_sub.argtypes = [vp, vp, vp, u64, i32, u32, vp]
         _lib = L
     return _lib
 
@@ -321,16 +322,31 @@ def prefix_bound_bytes(n: int, width: int) -> int:
     return int(lib().orc_prefix_bound_bytes(int(n), int(width)))
 
 
-def prefix_encode(a: np.ndarray, special: int, n_bits: int = None):
-    """Returns (stream bytes, table) for the prefix code; see orc_prefix_encode."""
+def prefix_encode(a: np.ndarray, special: int, n_bits: int = None, with_sub: bool = False):
+    """Returns (stream bytes, table) for the prefix code, with with_sub also the bit lengths of the
+    sub-blocks of 256 elements (16 per chunk); see orc_prefix_encode."""
     width = prefix_width(a, n_bits)
     raw = _raw_view(a, width)
     nchunks = int(lib().orc_prefix_chunks(raw.size))
     table = np.zeros(nchunks + 2, dtype=np.uint64)
-    nbytes = int(lib().orc_prefix_encode(_ptr(raw), raw.size, width, int(special), None, _ptr(table)))
+    sub = np.zeros(16 * nchunks, dtype=np.uint16)
+    nbytes = int(lib().orc_prefix_encode(_ptr(raw), raw.size, width, int(special), None, _ptr(table), None))
     stream = np.zeros(nbytes, dtype=np.uint8)
-    lib().orc_prefix_encode(_ptr(raw), raw.size, width, int(special), _ptr(stream), _ptr(table))
-    return stream, table
+    lib().orc_prefix_encode(_ptr(raw), raw.size, width, int(special), _ptr(stream), _ptr(table),
+                            _ptr(sub) if nchunks else None)
+    return (stream, table, sub) if with_sub else (stream, table)
+
+
+def prefix_decode_sub(stream: np.ndarray, table: np.ndarray, sub: np.ndarray, n: int, width: int,
+                      special: int) -> np.ndarray:
+    """Decodes sub-block by sub-block, each from the position the sub-block lengths give."""
+    stream = np.ascontiguousarray(stream, dtype=np.uint8)
+    table = np.ascontiguousarray(table, dtype=np.uint64)
+    sub = np.ascontiguousarray(sub, dtype=np.uint16)
+    out = np.empty(n, dtype={32: np.uint32, 16: np.uint16}.get(width, np.uint8))
+    lib().orc_prefix_decode_sub(_ptr(stream), _ptr(table), _ptr(sub) if sub.size else None, int(n), int(width),
+                                int(special), _ptr(out))
+    return out
 
 
 def prefix_decode(stream: np.ndarray, table: np.ndarray, n: int, width: int, special: int) -> np.ndarray:

@@ -116,7 +116,9 @@ def test_matches_string_coder_and_round_trips(width, n_bits):
         arr[rng.random(n) < 0.6] = 0
         special = 3 if n_bits > 2 else 1
     raw = arr.view({32: np.uint32, 16: np.uint16}.get(width, np.uint8))
-    stream, table = O.prefix_encode(arr, special, n_bits)
+    stream, table, sub = O.prefix_encode(arr, special, n_bits, with_sub=True)
+    s2, t2 = O.prefix_encode(arr, special, n_bits)
+    assert np.array_equal(s2, stream) and np.array_equal(t2, table)
     nchunks = 3
     assert table.size == nchunks + 2 and table[0] == 0 and table[-1] == 0
     assert stream.size == int(table[nchunks]) * 4
@@ -131,9 +133,25 @@ def test_matches_string_coder_and_round_trips(width, n_bits):
         vals_c, used = string_decode(got, part.size, width, special, words)
         assert used == len(want)
         decoded += vals_c
+        # sub-blocks of 256 elements: the listed lengths are those of the string coder, and decoding
+        # can start at each listed position (string decoder from that character on)
+        start = 0
+        for j in range(16):
+            blk = part[j * 256:(j + 1) * 256]
+            assert int(sub[16 * c + j]) == len(string_encode(blk, width, special, words))
+            vals_b, used_b = string_decode(got[start:], blk.size, width, special, words)
+            assert np.array_equal(np.array(vals_b, dtype=raw.dtype), blk) and used_b == int(sub[16 * c + j])
+            start += int(sub[16 * c + j])
+        assert start == len(want)
+    assert sub.size == 16 * nchunks and sub.dtype == np.uint16
     assert np.array_equal(np.array(decoded, dtype=raw.dtype), raw)
     back = O.prefix_decode(stream, table, n, width, special)
     assert np.array_equal(back, raw)
+    assert np.array_equal(O.prefix_decode_sub(stream, table, sub, n, width, special), raw)
+    # a wrong length anywhere but at the very end derails the sub-block decoder
+    bad = sub.copy()
+    bad[3] += 1
+    assert not np.array_equal(O.prefix_decode_sub(stream, table, bad, n, width, special), raw)
 
 
 def test_length_identity_and_bound():
