@@ -384,17 +384,22 @@ int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_para
  *   out       device, the bit stream: stream bit k is bit (k & 7) of byte k >> 3; codewords first
  *             symbol first, the value after "11" least significant bit first.  Only the all-zero
  *             pattern takes the codeword "0", so decoding returns the input exactly.
- *   table     device, lgn_prefix_table_bytes(n) bytes: ceil(n / 4096) + 2 entries of 64 bits
- *             (followed by LGN_PREFIX_MAX_BLOCKS entries of scratch for the encoder):
- *             elements are coded in chunks of LGN_PREFIX_CHUNK, every chunk starts on a 32-bit
- *             boundary (padding bits are zero); table[c] = index of the first 32-bit word of chunk
- *             c, table[nchunks] = number of words of the whole stream, table[nchunks + 1] = 0, or
- *             1 if out_capacity was too small (the chunks that did not fit are then not written).
+ *   table     device, lgn_prefix_table_bytes(n) bytes: ceil(n / 4096) + 2 entries of 64 bits,
+ *             then LGN_PREFIX_MAX_BLOCKS entries of scratch for the encoder, then 16 numbers of
+ *             16 bits per chunk.  Elements are coded in chunks of LGN_PREFIX_CHUNK, every chunk
+ *             starts on a 32-bit boundary (padding bits are zero); table[c] = index of the first
+ *             32-bit word of chunk c, table[nchunks] = number of words of the whole stream,
+ *             table[nchunks + 1] = 0, or 1 if out_capacity was too small (the chunks that did not
+ *             fit are then not written).  The 16-bit numbers are the lengths in bits of each
+ *             chunk's sixteen sub-blocks of LGN_PREFIX_SUB elements (0 past the end of the tensor):
+ *             sub-block j of chunk c begins at stream bit 32 table[c] + the lengths of the
+ *             sub-blocks before it, which is where the decoder starts its parsers.
  *   out_capacity  bytes available at out; lgn_prefix_bound_bytes(n, width) always suffices
  *             (width = 32, 16 or N)
  * Three launches (words per chunk, scan of per-workgroup sums, emit); `in` is read twice.
  */
 #define LGN_PREFIX_CHUNK 4096
+#define LGN_PREFIX_SUB 256
 #define LGN_PREFIX_MAX_BLOCKS 2048 /* entries of scratch the encoder keeps behind the table */
 size_t lgn_prefix_table_bytes(uint64_t n);
 size_t lgn_prefix_bound_bytes(uint64_t n, int width);
@@ -403,11 +408,12 @@ int lgn_prefix_encode(const void *in, uint64_t n, int in_kind, int dtype, const 
                       void *stream);
 
 /* Inverse of lgn_prefix_encode: writes n elements (values of `dtype`, or one code per byte) to
- * out.  in_kind, dtype, *p and *f must be those of the encoding call.  One thread per chunk.
- * `in` must hold at least table[nchunks] words and `table` must be the table of that stream
- * (entries ascending, table[c + 1] <= table[nchunks]): the call has no size of `in` to check the
- * entries against, and reads the words [table[c], table[c + 1]) of every chunk.  Bits of the
- * stream itself are not trusted: whatever they are, exactly n elements are written. */
+ * out.  in_kind, dtype, *p and *f must be those of the encoding call.  One thread per sub-block of
+ * LGN_PREFIX_SUB elements.  `in` must hold at least table[nchunks] words and `table` must be the
+ * whole table of that stream as the encoder left it (entries ascending, table[c + 1] <=
+ * table[nchunks], sub-block lengths behind it): the call has no size of `in` to check the entries
+ * against, and reads words of [table[c], table[c + 1]) only for every chunk.  Bits of the stream
+ * itself are not trusted: whatever they are, exactly n elements are written. */
 int lgn_prefix_decode(const void *in, const uint64_t *table, uint64_t n, int in_kind, int dtype,
                       const lgn_prune_params_t *p, const lgn_fp_params_t *f, void *out, void *stream);
 

@@ -25,6 +25,8 @@ LGN_SIGMA_PAPER_LITERAL, LGN_SIGMA_BASE2 = 0, 1
 LGN_ST_EMPTY, LGN_ST_SIGMA0, LGN_ST_NOTHING_TO_PRUNE, LGN_ST_NOT_CONVERGED = 1, 2, 4, 8
 LGN_ST_ALPHA_BELOW_FP_RANGE, LGN_ST_HAS_NONFINITE = 16, 32
 LGN_PREFIX_CHUNK = 4096
+LGN_PREFIX_SUB = 256
+LGN_PREFIX_MAX_BLOCKS = 2048
 LGN_MASK_NONE, LGN_MASK_SAME_DTYPE, LGN_MASK_U8 = 0, 1, 2
 LGN_HIST_BINS = 2048
 LGN_ALLOC_LOWERED, LGN_ALLOC_CAPPED = 1, 2
@@ -470,6 +472,13 @@ def lgn_prefix_encode(x: torch.Tensor, in_kind: int, p: torch.Tensor = None, f: 
                                     f.data_ptr() if f is not None else None,
                                     out.data_ptr(), out.numel(), table.data_ptr(), _stream()))
     return out, table
+
+
+def prefix_sub_lengths(table: torch.Tensor, n: int) -> torch.Tensor:
+    """The 16-bit sub-block lengths (16 per chunk) stored behind the chunk table, as an int16 view."""
+    nchunks = (int(n) + LGN_PREFIX_CHUNK - 1) // LGN_PREFIX_CHUNK
+    first = (nchunks + 2 + LGN_PREFIX_MAX_BLOCKS) * 4          # in 16-bit units
+    return table.view(torch.int16)[first:first + 16 * nchunks]
 
 
 def lgn_prefix_decode(stream_buf: torch.Tensor, table: torch.Tensor, n: int, in_kind: int,

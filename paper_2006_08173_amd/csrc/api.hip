@@ -400,7 +400,9 @@ int lgn_dequantize(const void *codes, uint64_t n, int in_kind, const lgn_fp_para
 
 size_t lgn_prefix_table_bytes(uint64_t n)
 {
-    return (size_t)(((n + LGN_PREFIX_CHUNK - 1) / LGN_PREFIX_CHUNK + 2 + LGN_PREFIX_MAX_BLOCKS) * 8);
+    const uint64_t nchunks = (n + LGN_PREFIX_CHUNK - 1) / LGN_PREFIX_CHUNK;
+    // chunk table, the encoder's scratch entries, sixteen 16-bit sub-block lengths per chunk
+    return (size_t)((nchunks + 2 + LGN_PREFIX_MAX_BLOCKS) * 8 + nchunks * 32);
 }
 
 size_t lgn_prefix_bound_bytes(uint64_t n, int width)

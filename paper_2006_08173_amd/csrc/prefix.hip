@@ -8,7 +8,9 @@
 // codewords are written first symbol first, the value after "11" least significant bit first.
 //
 // Container: chunks of 4096 elements, each starting on a 32-bit boundary listed in a table
-// (table[c] = first word of chunk c, table[nchunks] = total words, table[nchunks+1] = status).
+// (table[c] = first word of chunk c, table[nchunks] = total words, table[nchunks+1] = status),
+// and behind the table the bit lengths of every chunk's 16 sub-blocks of 256 elements (16-bit
+// numbers), so that the decoder can start a parser at every 256th element.
 // Variable-length output needs the chunk sizes before anything can be placed, hence three
 // launches.  Count: words per chunk, one wave per chunk, and their sum per workgroup.  Scan: one
 // small workgroup turns the per-workgroup sums into first-word offsets.  Emit: a workgroup walks
@@ -25,6 +27,17 @@ namespace lgn {
 constexpr int kChunk = LGN_PREFIX_CHUNK;          // elements per chunk
 constexpr int kPerThread = kChunk / kBlock;       // 16 consecutive elements per thread
 constexpr int kChunkWordsMax = (kChunk * 34 + 31) / 32;  // fp32: 2 + 32 bits per element
+constexpr int kSub = 256;                         // elements per sub-block
+constexpr int kSubsPerChunk = kChunk / kSub;      // 16
+
+static_assert(kSub == kPerThread * 16, "a sub-block is the elements of 16 consecutive threads of the emit pass");
+static_assert(kSub * 34 < 65536, "a sub-block's length fits 16 bits");
+
+// The sub-block lengths live behind the chunk table and the encoder's scratch entries.
+__host__ __device__ __forceinline__ uint16_t *sub_lengths(uint64_t *table, uint64_t nchunks)
+{
+    return reinterpret_cast<uint16_t *>(table + nchunks + 2 + LGN_PREFIX_MAX_BLOCKS);
+}
 
 static_assert(kPerThread == 16, "a thread reads its elements as 16-byte vectors");
 
@@ -298,6 +311,13 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
         }
         const uint32_t incl = wave_inclusive_scan(bits);
         if (lane == kWave - 1) wave_sum[wave] = incl;
+        {
+            // length of each sub-block: 16 consecutive threads, four sub-blocks per wave
+            const uint32_t start = __shfl(incl - bits, lane & ~15);
+            if ((lane & 15) == 15)
+                sub_lengths(a.table, nchunks)[c * kSubsPerChunk + (uint64_t)(wave * 4 + (lane >> 4))] =
+                    (uint16_t)(incl - start);
+        }
         __syncthreads();
         uint32_t pos = incl - bits, total = 0;
 #pragma unroll
@@ -350,7 +370,8 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
     if (overflow && threadIdx.x == 0) a.table[nchunks + 1] = 1;  // stream buffer too small
 }
 
-// ---- decode: one thread per chunk (a chunk is sequential by nature; not on the hot path) ------
+// ---- decode: one thread per sub-block of 256 elements (a prefix code is sequential by nature; the
+// listed sub-block lengths give sixteen starting points per chunk) --------------------------------
 template <int WC>
 __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
 {
@@ -363,10 +384,24 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
     const uint32_t *in = reinterpret_cast<const uint32_t *>(a.in);
     T *out = reinterpret_cast<T *>(a.out);
     const uint32_t tid = threadIdx.x;
-    const uint64_t c = (uint64_t)blockIdx.x * kBlock + tid;
-    // a thread without a chunk reads nothing and decodes zeros; it still helps to copy out
-    const uint64_t wend = c < nchunks ? a.table[c + 1] : 0;
-    uint64_t w = c < nchunks ? a.table[c] : 0;  // next word to request
+    const uint64_t nsub = (a.n + kSub - 1) / kSub;
+    const uint64_t sb = (uint64_t)blockIdx.x * kBlock + tid;  // this thread's sub-block
+    const uint64_t c = sb / kSubsPerChunk;
+    const uint32_t j = (uint32_t)(sb % kSubsPerChunk);
+    // a thread without a sub-block reads nothing and decodes zeros; it still helps to copy out
+    const uint64_t wend = sb < nsub ? a.table[c + 1] : 0;
+    uint32_t skip = 0;  // bits of the chunk before this sub-block
+    if (sb < nsub) {
+        const uint2 *lp = reinterpret_cast<const uint2 *>(sub_lengths(a.table, nchunks) + c * kSubsPerChunk);
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint2 x = lp[k];
+            const uint32_t len[4] = {x.x & 0xffffu, x.x >> 16, x.y & 0xffffu, x.y >> 16};
+#pragma unroll
+            for (uint32_t t = 0; t < 4; ++t) skip += 4 * k + t < j ? len[t] : 0u;
+        }
+    }
+    uint64_t w = sb < nsub ? a.table[c] + (skip >> 5) : 0;  // next word to request
 
     // The threads of a wave sit in different symbols of different chunks, and a wait for memory
     // holds the whole wave, so nothing that waits may sit in a branch only some threads take.
@@ -420,15 +455,21 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
         return v;
     };
 
-    // Output: a thread produces 16 bytes per step, 4 KiB-of-elements apart from its neighbours'.
+    // the sub-block starts inside its first word
+    refill();
+    acc >>= (skip & 31u);
+    have -= (skip & 31u);
+
+    // Output: a thread produces 16 bytes per step, 256 elements apart from its neighbours'.
     // Eight steps are collected in LDS (128 bytes per thread, slots rotated by the thread index
     // to spread the banks) and then written by the wave as whole 128-byte lines: lane l writes
     // piece l % 8 of the thread l / 8 + 8 k, k = 0..7.  Only wave-level ordering is needed.
     __shared__ uint4 stage[kBlock * 8];
     const int lane = (int)tid & (kWave - 1);
     const int wave_first = (int)tid - lane;                      // first thread of this wave
-    const uint64_t wave_chunk = (uint64_t)blockIdx.x * kBlock + (uint64_t)wave_first;
-    constexpr int kSteps = kChunk / EPV;
+    const uint64_t wave_sub = (uint64_t)blockIdx.x * kBlock + (uint64_t)wave_first;
+    constexpr int kSteps = kSub / EPV;
+    static_assert(kSteps % 8 == 0, "eight steps make a 128-byte line");
     for (int step = 0; step < kSteps; ++step) {
         const uint32_t fresh = min(kRing - (wr - rd), kTop);  // free slots of the ring
         uint32_t top[kTop];
@@ -456,10 +497,10 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int t = wave_first + k * 8 + (lane >> 3);  // thread whose line this lane writes
-            const uint64_t chunk = wave_chunk + (uint64_t)(k * 8 + (lane >> 3));
+            const uint64_t block = wave_sub + (uint64_t)(k * 8 + (lane >> 3));
             const uint4 x = stage[t * 8 + ((pstep + t) & 7)];
-            if (chunk >= nchunks) continue;
-            const uint64_t e0 = chunk * kChunk + (uint64_t)pstep * EPV;  // first element of the piece
+            if (block >= nsub) continue;
+            const uint64_t e0 = block * kSub + (uint64_t)pstep * EPV;  // first element of the piece
             if (e0 + EPV <= a.n) {
                 *reinterpret_cast<uint4 *>(out + e0) = x;
             } else if (e0 < a.n) {  // the ragged end of the tensor, element by element
@@ -517,7 +558,8 @@ hipError_t launch_prefix_decode(int width_class, int dtype, const void *in, cons
     const uint64_t nchunks = (n + kChunk - 1) / kChunk;
     if (!nchunks) return hipSuccess;
     const PrefixArgs a = {in, out, n, 0, const_cast<uint64_t *>(table), p, f, dtype};
-    const int blocks = (int)((nchunks + kBlock - 1) / kBlock);
+    const uint64_t nsub = (n + kSub - 1) / kSub;
+    const int blocks = (int)((nsub + kBlock - 1) / kBlock);
     if (width_class == 2) prefix_decode_kernel<2><<<blocks, kBlock, 0, stream>>>(a);
     else if (width_class == 1) prefix_decode_kernel<1><<<blocks, kBlock, 0, stream>>>(a);
     else prefix_decode_kernel<0><<<blocks, kBlock, 0, stream>>>(a);

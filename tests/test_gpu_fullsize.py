@@ -202,9 +202,10 @@ def test_prefix_code_at_full_size(lgn):
     buf, table = lgn.lgn_prefix_encode(y, lgn.LGN_OUT_VALUE, p)
     t = table.cpu().numpy().view(np.uint64)[: (g.size + 4095) // 4096 + 2]
     hy = y.cpu().numpy()
-    want, wt = O.prefix_encode(hy, O.prefix_special_of_alpha(hp.alpha, 32))
+    want, wt, wsub = O.prefix_encode(hy, O.prefix_special_of_alpha(hp.alpha, 32), with_sub=True)
     assert np.array_equal(t, wt)
     assert np.array_equal(buf[: int(t[-2]) * 4].cpu().numpy(), want)
+    assert np.array_equal(lgn.prefix_sub_lengths(table, g.size).cpu().numpy().view(np.uint16), wsub)
     back = lgn.lgn_prefix_decode(buf, table, g.size, lgn.LGN_OUT_VALUE, p)
     assert torch.equal(back.view(torch.int32), y.view(torch.int32))
     # 40 % of the elements were zero before pruning, so fewer are +-alpha than in the paper's example
@@ -215,9 +216,10 @@ def test_prefix_code_at_full_size(lgn):
     t = table.cpu().numpy().view(np.uint64)[: (g.size + 4095) // 4096 + 2]
     hc = codes.cpu().numpy()
     special = O.prefix_special_of_code(hp.alpha, hf.e_bits, hf.m_bits, hf.scale_exp)
-    want, wt = O.prefix_encode(hc, special, 6)
+    want, wt, wsub = O.prefix_encode(hc, special, 6, with_sub=True)
     assert np.array_equal(t, wt)
     assert np.array_equal(buf[: int(t[-2]) * 4].cpu().numpy(), want)
+    assert np.array_equal(lgn.prefix_sub_lengths(table, g.size).cpu().numpy().view(np.uint16), wsub)
     assert torch.equal(lgn.lgn_prefix_decode(buf, table, g.size, lgn.LGN_OUT_CODE8, p, f), codes)
     assert want.size * 8 / g.size < 2.2                   # against 6 bits per value packed
 

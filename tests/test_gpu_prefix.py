@@ -65,9 +65,10 @@ def test_value_streams_match_oracle(lgn, dtype):
         d = to_dev(a)
         buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_VALUE, p)
         got, t = host_stream(buf, table, n)
-        want, wt = O.prefix_encode(a, special)
+        want, wt, wsub = O.prefix_encode(a, special, with_sub=True)
         assert np.array_equal(t, wt), n
         assert np.array_equal(got, want), n
+        assert np.array_equal(lgn.prefix_sub_lengths(table, n).cpu().numpy().view(np.uint16), wsub), n
         back = lgn.lgn_prefix_decode(buf, table, n, lgn.LGN_OUT_VALUE, p,
                                      dtype=lgn.LGN_F32 if dtype == SI.F32 else lgn.LGN_BF16)
         raw = back.view(torch.int32 if dtype == SI.F32 else torch.int16).cpu().numpy()
@@ -92,9 +93,10 @@ def test_code_streams_match_oracle(lgn, n_bits, e):
         d = to_dev(codes)
         buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_CODE8, p, f)
         got, t = host_stream(buf, table, n)
-        want, wt = O.prefix_encode(codes, special, n_bits)
+        want, wt, wsub = O.prefix_encode(codes, special, n_bits, with_sub=True)
         assert np.array_equal(t, wt), n
         assert np.array_equal(got, want), n
+        assert np.array_equal(lgn.prefix_sub_lengths(table, n).cpu().numpy().view(np.uint16), wsub), n
         back = lgn.lgn_prefix_decode(buf, table, n, lgn.LGN_OUT_CODE8, p, f)
         assert np.array_equal(back.cpu().numpy(), codes), n
 
