@@ -741,3 +741,59 @@ def test_path_replays_from_a_hip_graph(lgn):
             assert bytes(lgn.read_stats(st)) == want[0], rep
             assert bytes(lgn.read_prune_params(p)) == want[1], rep
             assert torch.equal(out, want[2]), rep
+
+
+def test_static_and_batched_forms_replay_from_a_hip_graph(lgn):
+    """What the entry point without a workspace is for: under graph capture nothing may be allocated.
+    lgn_stats_solve_static + the fused pass, and the two batched calls (their per-tensor tables are
+    kernel arguments, frozen into the graph), are captured and replayed on fresh data; every replay
+    gives the bits of the eager calls."""
+    n = 1_200_003
+    tensors = [mixed_tensor(n, 880 + i, SI.F32, mu=-10.0 - i, sigma=1.8 + 0.2 * i) for i in range(3)]
+    d = torch.empty(n, dtype=torch.float32, device="cuda")
+    d2 = torch.empty(n // 3, dtype=torch.float32, device="cuda")
+    mk = lambda size: torch.empty(size, dtype=torch.uint8, device="cuda")
+    st, p, f, out = mk(72), mk(24), mk(32), mk(n)
+    items = [dict(g=d, out=mk(n), target_sparsity=0.8, n_bits=6, seed=5, st=mk(72), p=mk(24), f=mk(32)),
+             dict(g=d2, out=mk(n // 3), target_sparsity=0.6, n_bits=5, seed=6, st=mk(72), p=mk(24), f=mk(32))]
+    batch = lgn.make_batch(items)
+    ws = torch.empty(lgn.lgn_workspace_bytes(0, lgn.LGN_F32), dtype=torch.uint8, device="cuda")
+    lgn.lgn_workspace_init(ws)
+
+    def chain():
+        lgn.lgn_stats_solve_static(d, st, p, f, target_sparsity=0.85, n_bits=6)
+        lgn.lgn_prune_quantize_fused(d, p, f, O.ROUND_STOCHASTIC, 3, 0, out=out, out_kind=O.OUT_CODE8)
+        lgn.lgn_batch_stats_solve(batch, ws=ws)
+        lgn.lgn_batch_prune_quantize_fused(batch, O.ROUND_STOCHASTIC, out_kind=O.OUT_CODE8)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return ([bytes(lgn.read_stats(st)), bytes(lgn.read_prune_params(p)), bytes(lgn.read_fp_params(f))] +
+                [bytes(lgn.read_stats(it["st"])) + bytes(lgn.read_prune_params(it["p"])) for it in items],
+                [out.clone()] + [it["out"].clone() for it in items])
+
+    eager = []
+    for t in tensors:
+        d.copy_(torch.from_numpy(t))
+        d2.copy_(torch.from_numpy(t[: n // 3]))
+        chain()
+        eager.append(snapshot())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()                                            # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    for rep in range(2):
+        for t, (want_structs, want_outs) in zip(tensors, eager):
+            d.copy_(torch.from_numpy(t))                   # eager work between the replays
+            d2.copy_(torch.from_numpy(t[: n // 3]))
+            for o in [out] + [it["out"] for it in items]:
+                o.zero_()
+            graph.replay()
+            got_structs, got_outs = snapshot()
+            assert got_structs == want_structs, rep
+            assert all(torch.equal(a, b) for a, b in zip(got_outs, want_outs)), rep
