@@ -13,10 +13,10 @@ namespace lgn {
 // ---- tuning knobs: process-wide, lock-free ---------------------------------------------------
 namespace {
 constexpr int kKnobs = 5;
-constexpr long kKnobDefault[kKnobs] = {224, 0, 0, 1024, 1};
+constexpr long kKnobDefault[kKnobs] = {224, 0, 0, 1024, 0};
 constexpr long kKnobMin[kKnobs] = {0, 0, 0, 1, 0};
 constexpr long kKnobMax[kKnobs] = {4096, 8, 4096, 1024, 1};
-std::atomic<long> g_knob[kKnobs] = {{224}, {0}, {0}, {1024}, {1}};
+std::atomic<long> g_knob[kKnobs] = {{224}, {0}, {0}, {1024}, {0}};
 std::atomic<int> g_cus[64];  // zero = not yet asked
 }  // namespace
 

@@ -583,10 +583,12 @@ __device__ __forceinline__ void finish_and_solve(const Partial *partials, uint32
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
         __builtin_amdgcn_s_waitcnt(0);
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        // The release fence the memory model asks for between the record and the ticket (one
-        // wave per workgroup issues it: +4 us on an 822 MB tensor).  With the knob
-        // LGN_TUNE_STATS_STRICT_PUBLISH at 0 it is left out: completed write-through stores are
-        // visible device-wide on this hardware, but that is behaviour, not a promise.
+        // That completed write-through stores are visible device-wide is how this hardware
+        // behaves, not a promise of the memory model.  With the knob LGN_TUNE_STATS_STRICT_PUBLISH
+        // the release fence the model asks for is added; it writes back this XCD's whole L2,
+        // the dirty lines of the pass before included (+11 us on an 822 MB tensor behind a fused
+        // pass, +55 us on 10^9 bf16 elements), so it is off by default and there to rule out a
+        // suspected stale read.
         if (rq.alpha_dtype & 0x100) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         is_last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   nblocks - 1;

@@ -491,17 +491,17 @@ def test_stats_solve_equals_three_calls(lgn, dtype):
 
 
 def test_both_ways_of_publishing_records_give_the_same_bytes(lgn):
-    """The one-launch form publishes a workgroup's record with a release fence before the ticket
-    (default), or, with the knob LGN_TUNE_STATS_STRICT_PUBLISH at 0, by waiting for its write-through
-    stores only.  Both give the bytes of the two-launch form."""
+    """The one-launch form publishes a workgroup's record by waiting for its write-through stores
+    (default), or, with the knob LGN_TUNE_STATS_STRICT_PUBLISH at 1, with the release fence the memory
+    model asks for as well.  Both give the bytes of the two-launch form."""
     g = mixed_tensor(5_000_003, 61, SI.F32)
     d = to_dev(g)
     st = lgn.lgn_stats(d)
     want = [bytes(lgn.read_stats(st)), bytes(lgn.read_prune_params(lgn.lgn_threshold(st, 0.9))),
             bytes(lgn.read_fp_params(lgn.lgn_fp_params(st, 6)))]
-    assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STATS_STRICT_PUBLISH) == 1
+    assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STATS_STRICT_PUBLISH) == 0
     try:
-        for strict in (1, 0, 1):
+        for strict in (0, 1, 0):
             lgn.lgn_set_tuning(lgn.LGN_TUNE_STATS_STRICT_PUBLISH, strict)
             for _ in range(3):
                 got = lgn.lgn_stats_solve(d, 0.9, lgn.LGN_F32, 6)
@@ -509,7 +509,7 @@ def test_both_ways_of_publishing_records_give_the_same_bytes(lgn):
                         bytes(lgn.read_fp_params(got[2]))] == want, strict
     finally:
         lgn.lgn_set_tuning(lgn.LGN_TUNE_STATS_STRICT_PUBLISH, -1)
-    assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STATS_STRICT_PUBLISH) == 1
+    assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STATS_STRICT_PUBLISH) == 0
 
 
 def test_stats_solve_flags_a_threshold_below_the_formats_range(lgn):

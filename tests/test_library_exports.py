@@ -49,7 +49,7 @@ def test_host_only_helpers():
 def test_tuning_knobs_are_host_state_only():
     for knob, default in ((lgn.LGN_TUNE_STATS_KEEP_MB, 224), (lgn.LGN_TUNE_STATS_BLOCKS_PER_CU, 0),
                           (lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 0), (lgn.LGN_TUNE_STREAM_BLOCKS_PER_CU, 1024),
-                          (lgn.LGN_TUNE_STATS_STRICT_PUBLISH, 1)):
+                          (lgn.LGN_TUNE_STATS_STRICT_PUBLISH, 0)):
         assert lgn.lgn_get_tuning(knob) == default
     lgn.lgn_set_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE, 12)
     assert lgn.lgn_get_tuning(lgn.LGN_TUNE_STREAM_PAIRS_PER_WAVE) == 12
