@@ -139,8 +139,13 @@ def load():
     L.lgn_set_tuning.restype = i32
     L.lgn_get_tuning.argtypes = [i32]
     L.lgn_get_tuning.restype = C.c_long
-    for name in EXPORTS[2:17]:
-        getattr(L, name).restype = i32
+    # every entry point that can fail returns an LGN_* code; the sizes, the error text, the version and
+    # the knob getter are set above
+    not_status = {"lgn_workspace_bytes", "lgn_packed_bytes", "lgn_prefix_table_bytes", "lgn_prefix_bound_bytes",
+                  "lgn_static_scratch_bytes", "lgn_last_error", "lgn_version", "lgn_get_tuning"}
+    for name in EXPORTS:
+        if name not in not_status:
+            getattr(L, name).restype = i32
     _lib = L
     return L
 
