@@ -431,9 +431,11 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
         next = ring[(rd & (kRing - 1u)) * kBlock + tid];
     };
     const uint32_t payload_mask = width == 32 ? 0xffffffffu : (1u << width) - 1u;
-    // A symbol is classified from its first two bits, again with selects.
-    auto symbol = [&]() {
-        refill();
+    // A symbol is classified from its first two bits, again with selects.  A top-up leaves at
+    // least 32 bits, and a byte code takes at most 2 + 8 of them, so for byte codes only every
+    // third symbol needs one.
+    auto symbol = [&](bool top_up) {
+        if (top_up) refill();
         const uint32_t lo = (uint32_t)acc;
         const bool nonzero = (lo & 1u) != 0u, value = (lo & 3u) == 3u;
         uint32_t v = nonzero ? special | (((lo >> 2) & 1u) << (width - 1)) : 0u;
@@ -461,15 +463,18 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
     have -= (skip & 31u);
 
     // Output: a thread produces 16 bytes per step, 256 elements apart from its neighbours'.
-    // Eight steps are collected in LDS (128 bytes per thread, slots rotated by the thread index
-    // to spread the banks) and then written by the wave as whole 128-byte lines: lane l writes
-    // piece l % 8 of the thread l / 8 + 8 k, k = 0..7.  Only wave-level ordering is needed.
-    __shared__ uint4 stage[kBlock * 8];
+    // kLine steps are collected in LDS (16 * kLine bytes per thread, slots rotated by the thread
+    // index to spread the banks) and then written by the wave as whole lines: lane l writes piece
+    // l % kLine of the thread l / kLine + (64 / kLine) k.  Only wave-level ordering is needed.
+    // Four steps (64-byte lines) rather than eight: the smaller buffer lets a fourth workgroup
+    // fit a compute unit, and the parsers are bound by latency, not by the stores.
+    constexpr int kLine = 4, kRows = kWave / kLine;
+    __shared__ uint4 stage[kBlock * kLine];
     const int lane = (int)tid & (kWave - 1);
     const int wave_first = (int)tid - lane;                      // first thread of this wave
     const uint64_t wave_sub = (uint64_t)blockIdx.x * kBlock + (uint64_t)wave_first;
     constexpr int kSteps = kSub / EPV;
-    static_assert(kSteps % 8 == 0, "eight steps make a 128-byte line");
+    static_assert(kSteps % kLine == 0, "whole lines");
     for (int step = 0; step < kSteps; ++step) {
         const uint32_t fresh = min(kRing - (wr - rd), kTop);  // free slots of the ring
         uint32_t top[kTop];
@@ -478,7 +483,7 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
         uint32_t q[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int j = 0; j < EPV; ++j) {
-            const uint32_t v = symbol();
+            const uint32_t v = symbol(WC != 0 || j % 3 == 0);
             if (WC == 2) q[j] = v;
             else if (WC == 1) q[j / 2] |= v << (16 * (j % 2));
             else q[j / 4] |= v << (8 * (j % 4));
@@ -488,17 +493,17 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
             if (j < fresh) ring[((wr + j) & (kRing - 1u)) * kBlock + tid] = top[j];
         wr += fresh;
         w += fresh;
-        stage[tid * 8 + ((step + (int)tid) & 7)] = make_uint4(q[0], q[1], q[2], q[3]);
-        if ((step & 7) != 7) continue;
+        stage[tid * kLine + ((step + (int)tid) & (kLine - 1))] = make_uint4(q[0], q[1], q[2], q[3]);
+        if ((step & (kLine - 1)) != kLine - 1) continue;
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        const int piece = lane & 7;                       // 16-byte piece of the 128-byte line
-        const int pstep = (step & ~7) + piece;            // the step that produced it
+        const int piece = lane & (kLine - 1);             // 16-byte piece of the line
+        const int pstep = (step & ~(kLine - 1)) + piece;  // the step that produced it
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int t = wave_first + k * 8 + (lane >> 3);  // thread whose line this lane writes
-            const uint64_t block = wave_sub + (uint64_t)(k * 8 + (lane >> 3));
-            const uint4 x = stage[t * 8 + ((pstep + t) & 7)];
+        for (int k = 0; k < kLine; ++k) {
+            const int t = wave_first + k * kRows + lane / kLine;  // thread whose line this lane writes
+            const uint64_t block = wave_sub + (uint64_t)(k * kRows + lane / kLine);
+            const uint4 x = stage[t * kLine + ((pstep + t) & (kLine - 1))];
             if (block >= nsub) continue;
             const uint64_t e0 = block * kSub + (uint64_t)pstep * EPV;  // first element of the piece
             if (e0 + EPV <= a.n) {
