@@ -15,6 +15,9 @@
  *   lgn_fp_quantize  FP(1,e,m) quantization with scale 2^s               (Section 4.1, Alg. 1)
  *   lgn_prune_quantize_fused   the two operators in one pass
  *   lgn_stats_solve            the first three steps in one launch
+ *   lgn_batch_stats_solve, lgn_batch_prune_quantize_fused
+ *                              those two launches for many tensors at once (all layers of a network)
+ *   lgn_stats_solve_static     lgn_stats_solve for callers that cannot allocate a workspace
  *
  * Beyond that path: the prefix code of a pruned tensor (lgn_prefix_encode / lgn_prefix_decode,
  * appendix "Encoding"), statistics of one mode of a bi-modal gradient (lgn_stats_masked), the
