@@ -497,3 +497,15 @@ def test_alpha_below_fp_range_is_where_the_quantizer_flushes_alpha():
             for rounding, w in ((O.ROUND_NEAREST_EVEN, 0), (O.ROUND_STOCHASTIC, 0xFFFFFFFF)):
                 flushed = O.quantize_one(a, e, m, s, rounding, w) == 0
                 assert flushed == O.alpha_below_fp_range(a, e, s)
+
+
+def test_pruning_bias_of_the_16_bit_grid_is_bounded():
+    """Averaged over ALL 2^16 values of the pruning variable, T(x) differs from x by at most
+    alpha * 2^-17 (half a grid step), except below alpha * 2^-17 where an element is always dropped
+    and the bias is the element itself -- the bound the design quotes for this reading."""
+    alpha = np.float32(0.8)
+    for x in (0.3, -0.3, 0.799, 1e-3, 0.123456, 0.5 * 0.8, 0.8 * 2.0 ** -16, 0.8 * 2.0 ** -18):
+        x = np.float32(x)
+        total = sum(float(O.prune_one(x, alpha, k << 16)) for k in range(1 << 16))
+        mean = total / 2 ** 16
+        assert abs(mean - float(x)) <= float(alpha) * 2.0 ** -17 * (1 + 1e-6), (x, mean)
