@@ -14,11 +14,12 @@
 // Variable-length output needs the chunk sizes before anything can be placed, hence three
 // launches.  Count: words per chunk, one wave per chunk, and their sum per workgroup.  Scan: one
 // small workgroup turns the per-workgroup sums into first-word offsets.  Emit: a workgroup walks
-// its contiguous run of chunks with a running offset; thread t owns elements 16t .. 16t+15 of the
-// chunk, a block-wide exclusive scan of the threads' bit counts gives each thread its position,
-// and the chunk is assembled in a zero-initialised LDS image with atomic ORs -- only non-zero
-// elements write anything, the codeword "0" is the zero bit that is already there -- then copied
-// out coalesced while the image is cleared for the next chunk.
+// its contiguous run of chunks; an exclusive scan of the bit counts gives every thread (16-bit
+// and 32-bit patterns: 16 elements per thread, a workgroup per chunk) or lane (byte codes: 64 per
+// lane, a wave per chunk) its position, and the chunk is assembled in a zero-initialised LDS
+// image with atomic ORs -- only non-zero elements write anything, the codeword "0" is the zero
+// bit that is already there -- then copied out coalesced while the image is cleared for the next
+// chunk.
 #include "launch.hpp"
 #include "fpcode_device.hpp"
 
@@ -260,9 +261,11 @@ __device__ __forceinline__ void lds_put(uint32_t *buf, uint32_t pos, uint32_t bi
     if (hi) atomicOr(buf + (pos >> 5) + 1, hi);
 }
 
+// 16-bit and 32-bit patterns: a workgroup per chunk, 16 elements per thread.
 template <int WC>
 __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const uint64_t *scratch)
 {
+    static_assert(WC == 1 || WC == 2, "byte codes have a kernel of their own");
     __shared__ uint32_t buf[kChunkWordsMax + 1];  // + 1: the word after the last bit may be ORed with 0
     __shared__ uint32_t wave_sum[kBlock / kWave];
     int width;
@@ -279,36 +282,12 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
     __syncthreads();
     for (uint64_t c = run.first; c < run.last; ++c) {
         const uint64_t first = c * kChunk + (uint64_t)threadIdx.x * kPerThread;
-        // Byte codes, the usual case (most of them zero after pruning): the thread's sixteen codes
-        // stay packed in four words; which bytes are non-zero and which are the special magnitude
-        // is found for four bytes at a time, and only the non-zero ones are visited below.
-        const bool packed = WC == 0 && c * kChunk + kChunk <= a.n;  // workgroup-uniform
         uint32_t v[kPerThread];
-        uint32_t d[4] = {0u, 0u, 0u, 0u}, nonzero = 0u, is_special16 = 0u;
-        int count = kPerThread;
         uint32_t bits = 0;
-        if (packed) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(static_cast<const uint8_t *>(a.in) + first);
-            d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
-            const uint32_t mag = (((1u << (width - 1)) - 1u) & 0xffu) * 0x01010101u, sp4 = special * 0x01010101u;
+        const int count = load_thread_elems<WC>(a.in, first, a.n, v);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                // bit 7 of a byte of t: that byte of y is non-zero
-                auto byte_nonzero = [](uint32_t y) { return (((y & 0x7f7f7f7fu) + 0x7f7f7f7fu) | y) & 0x80808080u; };
-                const uint32_t nz = byte_nonzero(d[k]);
-                const uint32_t sp = special ? ~byte_nonzero((d[k] & mag) ^ sp4) & 0x80808080u : 0u;
-                // bits 7, 15, 23, 31 gathered into bits 0..3
-                nonzero |= (((nz >> 7) * 0x00204081u) >> 21 & 0xfu) << (4 * k);
-                is_special16 |= (((sp >> 7) * 0x00204081u) >> 21 & 0xfu) << (4 * k);
-            }
-            const uint32_t n_nz = (uint32_t)__popc(nonzero), n_sp = (uint32_t)__popc(is_special16);
-            bits = (uint32_t)kPerThread + n_nz * (1u + (uint32_t)width) - n_sp * ((uint32_t)width - 1u);
-        } else {
-            count = load_thread_elems<WC>(a.in, first, a.n, v);
-#pragma unroll
-            for (int j = 0; j < kPerThread; ++j)
-                if (j < count) bits += (uint32_t)symbol_len(v[j], width, special);
-        }
+        for (int j = 0; j < kPerThread; ++j)
+            if (j < count) bits += (uint32_t)symbol_len(v[j], width, special);
         const uint32_t incl = wave_inclusive_scan(bits);
         if (lane == kWave - 1) wave_sum[wave] = incl;
         {
@@ -326,22 +305,9 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
             total += wave_sum[w];
         }
         // zero symbols are the zero bits the image already holds: only the others are written
-        if (packed) {
-            uint32_t extra = 0;  // bits beyond one per element, of the elements before the current one
-            while (nonzero) {
-                const uint32_t j = (uint32_t)__ffs((int)nonzero) - 1u;
-                nonzero &= nonzero - 1u;
-                const uint32_t w = j < 8u ? (j < 4u ? d[0] : d[1]) : (j < 12u ? d[2] : d[3]);
-                const uint32_t x = (w >> (8u * (j & 3u))) & 0xffu;
-                const bool sp = ((is_special16 >> j) & 1u) != 0u;
-                const uint32_t word = sp ? (1u | (((x >> (width - 1)) & 1u) << 2)) : (3u | ((x & payload_mask) << 2));
-                lds_put(buf, pos + j + extra, word);
-                extra += sp ? 2u : 1u + (uint32_t)width;
-            }
-        }
 #pragma unroll
         for (int j = 0; j < kPerThread; ++j) {
-            if (!packed && j < count) {
+            if (j < count) {
                 const uint32_t x = v[j];
                 const bool is_special = special != 0u && (x & ((1u << (width - 1)) - 1u)) == special;
                 const uint32_t head = is_special ? (1u | (((x >> (width - 1)) & 1u) << 2)) : 3u;
@@ -368,6 +334,153 @@ __global__ __launch_bounds__(kBlock) void prefix_emit_kernel(PrefixArgs a, const
         __syncthreads();  // the image and wave_sum are reused by the next chunk
     }
     if (overflow && threadIdx.x == 0) a.table[nchunks + 1] = 1;  // stream buffer too small
+}
+
+// ---- launch 3 for byte codes: one wave per chunk ----------------------------------------------
+// After pruning some 85 % of the codes are zero and cost nothing, so the emit pass is bound by the
+// loop over the non-zero ones, which runs as often as the busiest lane of a wave needs.  With 64
+// consecutive codes per lane instead of 16 the busiest lane is much closer to the average one
+// (binomial counts: about 16 of 64 against 7 of 16 at 15 % non-zero), and a chunk is one wave's
+// work: no workgroup barrier, one scan, one LDS image per wave.  A wave walks every fourth chunk
+// of its workgroup's run; the chunks' first words come from the table, which wave 0 first turns
+// from words per chunk into running ends for the whole run.
+constexpr int kLaneCodes = kChunk / kWave;                // 64 consecutive codes per lane
+constexpr int kByteImageWords = (kChunk * 10 + 31) / 32;  // at most 2 + 8 bits per code
+static_assert(kSub % kLaneCodes == 0, "a sub-block is the codes of whole lanes");
+
+// The 64 codes of a lane as sixteen words; codes at or beyond n read as zero.
+__device__ __forceinline__ void load_lane_codes(const uint8_t *src, uint64_t first, uint64_t n, uint4 x[4])
+{
+    if (first + kLaneCodes <= n) {
+        const uint4 *vp = reinterpret_cast<const uint4 *>(src + first);  // first % 64 == 0
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = vp[k];
+        return;
+    }
+    uint32_t w[16];
+    for (int k = 0; k < 16; ++k) {
+        w[k] = 0u;
+        for (int t = 0; t < 4; ++t) {
+            const uint64_t i = first + (uint64_t)(4 * k + t);
+            if (i < n) w[k] |= (uint32_t)src[i] << (8 * t);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) x[k] = make_uint4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+}
+
+__global__ __launch_bounds__(kBlock) void prefix_emit_bytes_kernel(PrefixArgs a, const uint64_t *scratch)
+{
+    constexpr int kWaves = kBlock / kWave;
+    __shared__ uint32_t image[kWaves][kByteImageWords + 1];  // + 1: the word after the last bit may be ORed with 0
+    // a lane's codes, for the loop over the non-zero ones: word k of lane l at [k * 64 + l], so
+    // that a lane only ever touches its own column and no two lanes share a bank
+    __shared__ uint32_t codes[kWaves][(kLaneCodes / 4) * kWave];
+    int width;
+    uint32_t special;
+    prefix_consts<0>(a, width, special);
+    const uint32_t payload_mask = (1u << width) - 1u;
+    const uint32_t mag_mask = (1u << (width - 1)) - 1u;  // <= 0x7f: the per-byte sums below cannot carry
+    const uint32_t mag4 = mag_mask * 0x01010101u, sp4 = special * 0x01010101u;
+    const uint32_t special_or_none = special ? special : 0x100u;  // 0x100: no masked byte equals it
+    const uint64_t nchunks = (a.n + kChunk - 1) / kChunk;
+    const ChunkRun run = chunk_run(nchunks);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    const uint8_t *src = static_cast<const uint8_t *>(a.in);
+    uint32_t *out = reinterpret_cast<uint32_t *>(a.out);
+    uint32_t *img = image[wave];
+    uint32_t *mine = codes[wave] + lane;
+    for (int i = lane; i < kByteImageWords + 1; i += kWave) img[i] = 0u;
+
+    uint64_t c = run.first + (uint64_t)wave;
+    uint4 x[4] = {make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u),
+                  make_uint4(0u, 0u, 0u, 0u)};
+    if (c < run.last) load_lane_codes(src, c * kChunk + (uint64_t)lane * kLaneCodes, a.n, x);  // in flight during the scan
+
+    if (wave == 0) {  // words per chunk -> end of each chunk, for this workgroup's run
+        uint64_t carry = scratch[blockIdx.x];
+        for (uint64_t base = run.first; base < run.last; base += kWave) {
+            const uint64_t idx = base + (uint64_t)lane;
+            const uint64_t words = idx < run.last ? a.table[idx + 1] : 0;
+            const uint64_t incl = wave_inclusive_scan(words);
+            if (idx < run.last) a.table[idx + 1] = carry + incl;
+            carry += __shfl(incl, kWave - 1);
+        }
+    }
+    __syncthreads();
+
+    bool overflow = false;
+    for (; c < run.last; c += kWaves) {
+        const uint32_t d[16] = {x[0].x, x[0].y, x[0].z, x[0].w, x[1].x, x[1].y, x[1].z, x[1].w,
+                                x[2].x, x[2].y, x[2].z, x[2].w, x[3].x, x[3].y, x[3].z, x[3].w};
+        const uint64_t lane_first = c * kChunk + (uint64_t)lane * kLaneCodes;
+        if (c + kWaves < run.last)  // the next chunk of this wave, in flight while this one is assembled
+            load_lane_codes(src, lane_first + (uint64_t)kWaves * kChunk, a.n, x);
+        const uint64_t w0 = c == run.first ? scratch[blockIdx.x] : a.table[c];
+
+        // which codes are non-zero (a 64-bit mask in element order) and how many are +-alpha
+        uint32_t nz_lo = 0u, nz_hi = 0u, n_sp = 0u;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            mine[k * kWave] = d[k];
+            // bit 7 of a byte: that byte of d is non-zero
+            const uint32_t nz = (((d[k] & 0x7f7f7f7fu) + 0x7f7f7f7fu) | d[k]) & 0x80808080u;
+            // a zero byte of t: that code's magnitude is alpha's
+            const uint32_t t = (d[k] & mag4) ^ sp4;
+            n_sp += (uint32_t)__popc(~(t + 0x7f7f7f7fu) & 0x80808080u);
+            // bits 7, 15, 23, 31 gathered into a nibble
+            const uint32_t nib = (((nz >> 7) * 0x00204081u) >> 21) & 0xfu;
+            if (k < 8) nz_lo |= nib << (4 * k);
+            else nz_hi |= nib << (4 * (k - 8));
+        }
+        if (special == 0u) n_sp = 0u;
+        const uint32_t n_nz = (uint32_t)__popc(nz_lo) + (uint32_t)__popc(nz_hi);
+        const uint32_t present =
+            lane_first + kLaneCodes <= a.n ? (uint32_t)kLaneCodes : (lane_first < a.n ? (uint32_t)(a.n - lane_first) : 0u);
+        const uint32_t bits = present + n_nz * (1u + (uint32_t)width) - n_sp * ((uint32_t)width - 1u);
+        const uint32_t incl = wave_inclusive_scan(bits);
+        const uint32_t total = __shfl(incl, kWave - 1);
+        const uint32_t pos = incl - bits;
+        {
+            // length of each sub-block: the codes of four consecutive lanes
+            const uint32_t start = __shfl(pos, lane & ~3);
+            if ((lane & 3) == 3)
+                sub_lengths(a.table, nchunks)[c * kSubsPerChunk + (uint64_t)(lane >> 2)] = (uint16_t)(incl - start);
+        }
+
+        // zero symbols are the zero bits the image already holds: only the others are written
+        uint64_t todo = ((uint64_t)nz_hi << 32) | nz_lo;
+        uint32_t extra = 0;  // bits beyond one per code, of the codes before the current one
+        const uint8_t *bytes = reinterpret_cast<const uint8_t *>(mine);
+        while (todo) {
+            const uint32_t j = (uint32_t)__ffsll((unsigned long long)todo) - 1u;
+            todo &= todo - 1ull;
+            const uint32_t v = bytes[(j >> 2) * (kWave * 4u) + (j & 3u)];
+            const bool sp = (v & mag_mask) == special_or_none;
+            // "1", then "0" and the sign (+-alpha) or "1" and the code
+            const uint32_t rest = sp ? ((v >> (width - 1)) & 1u) << 1 : ((v & payload_mask) << 1) | 1u;
+            const uint32_t p = pos + j + extra;
+            const uint64_t w = (uint64_t)((rest << 1) | 1u) << (p & 31u);
+            atomicOr(img + (p >> 5), (uint32_t)w);
+            atomicOr(img + (p >> 5) + 1, (uint32_t)(w >> 32));  // often zero: cheaper than asking
+            extra += sp ? 2u : 1u + (uint32_t)width;
+        }
+
+        // the image is complete once every lane's ORs are done: LDS serves a wave's requests in order
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        const uint32_t nwords = (total + 31u) / 32u;  // = what the count pass found for this chunk
+        const bool fits = w0 + nwords <= a.capacity_words;
+        for (uint32_t i = (uint32_t)lane; i < nwords; i += kWave) {
+            if (fits) out[w0 + i] = img[i];
+            img[i] = 0u;
+        }
+        overflow |= !fits;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (overflow && lane == 0) a.table[nchunks + 1] = 1;  // stream buffer too small
 }
 
 // ---- decode: one thread per sub-block of 256 elements (a prefix code is sequential by nature; the
@@ -542,7 +655,8 @@ static hipError_t encode_launches(const PrefixArgs &a, hipStream_t stream)
     prefix_scan_kernel<<<1, kScanThreads, 0, stream>>>(a.table, nchunks, scratch, nchunks ? blocks : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !nchunks) return e;
-    prefix_emit_kernel<WC><<<blocks, kBlock, 0, stream>>>(a, scratch);
+    if constexpr (WC == 0) prefix_emit_bytes_kernel<<<blocks, kBlock, 0, stream>>>(a, scratch);
+    else prefix_emit_kernel<WC><<<blocks, kBlock, 0, stream>>>(a, scratch);
     return hipGetLastError();
 }
 

@@ -224,6 +224,35 @@ def test_prefix_code_at_full_size(lgn):
     assert want.size * 8 / g.size < 2.2                   # against 6 bits per value packed
 
 
+def test_prefix_byte_codes_with_long_runs_of_chunks(lgn):
+    """More chunks than 64 per workgroup of the emit pass (its table of chunk ends is then built in
+    several steps): 545 M sparse byte codes, the whole stream, table and sub-block lengths against
+    the oracle, and the way back."""
+    n_bits, e, m, s = 6, 3, 2, -14
+    f = lgn.upload_struct(lgn.LgnFpParams(n_bits, e, m, s, 0.0, 0, 0))
+    alpha = 3.1e-4
+    p = lgn.upload_struct(lgn.LgnPruneParams(alpha, 0, 0.0, 0.0))
+    special = O.prefix_special_of_code(alpha, e, m, s)
+    n = 2048 * 65 * 4096 + 3 * 4096 + 777
+    rng = np.random.default_rng(99)
+    codes = np.zeros(n, np.uint8)
+    step = 1 << 26
+    for lo in range(0, n, step):
+        k = min(step, n - lo)
+        r = rng.random(k, dtype=np.float32)
+        v = rng.integers(1, 1 << n_bits, k, dtype=np.uint8)
+        v[r < 0.015] = special
+        codes[lo:lo + k] = np.where(r < 0.03, v, 0)
+    d = torch.from_numpy(codes).cuda()
+    buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_CODE8, p, f)
+    t = table.cpu().numpy().view(np.uint64)[: (n + 4095) // 4096 + 2]
+    want, wt, wsub = O.prefix_encode(codes, special, n_bits, with_sub=True)
+    assert np.array_equal(t, wt)
+    assert np.array_equal(buf[: int(t[-2]) * 4].cpu().numpy(), want)
+    assert np.array_equal(lgn.prefix_sub_lengths(table, n).cpu().numpy().view(np.uint16), wsub)
+    assert torch.equal(lgn.lgn_prefix_decode(buf, table, n, lgn.LGN_OUT_CODE8, p, f), d)
+
+
 def test_config3_twenty_tensors_on_three_streams(lgn):
     """Configuration 3 as the benchmark runs it: twenty tensors (6.4 M to 205.5 M elements, 2.5 GB in
     all), each with its own statistics, threshold and format, dealt round-robin to three streams with

@@ -148,6 +148,31 @@ def test_no_special_class_and_small_capacity(lgn):
         lgn.lgn_prefix_encode(d.view(torch.uint8), lgn.LGN_OUT_CODE8, None, None)
 
 
+def test_byte_codes_small_capacity(lgn):
+    """Byte codes into a buffer that ends inside the stream: the chunks that fit are written whole,
+    nothing is written past the buffer, the table is complete and the status entry is set."""
+    n_bits, e, m, s = 6, 3, 2, -14
+    f = lgn.upload_struct(lgn.LgnFpParams(n_bits, e, m, s, 0.0, 0, 0))
+    alpha = 3.1e-4
+    p = lgn.upload_struct(lgn.LgnPruneParams(alpha, 0, 0.0, 0.0))
+    special = O.prefix_special_of_code(alpha, e, m, s)
+    rng = np.random.default_rng(5)
+    n = 11 * 4096 + 100
+    codes = np.where(rng.random(n) < 0.2, rng.integers(1, 1 << n_bits, n), 0).astype(np.uint8)
+    want, wt = O.prefix_encode(codes, special, n_bits)
+    d = to_dev(codes)
+    cap = int(wt[7]) * 4 + 8                               # chunks 0..6 fit, chunk 7 does not
+    small = torch.full((cap + 4096,), 0xEE, dtype=torch.uint8, device="cuda")
+    _, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_CODE8, p, f, out=small[:cap])
+    t = host_table(table, n)
+    assert t[-1] == 1 and np.array_equal(t[:-1], wt[:-1])
+    hs = small.cpu().numpy()
+    assert np.array_equal(hs[: int(wt[7]) * 4], want[: int(wt[7]) * 4])
+    assert np.all(hs[cap:] == 0xEE)
+    # chunks behind the one that did not fit are skipped too (they start beyond the buffer)
+    assert np.all(hs[int(wt[7]) * 4 : cap] == 0xEE)
+
+
 def test_chain_prune_quantize_encode_config1(lgn):
     """stats+solvers -> fused prune/quantize -> prefix code, parameters never leaving the device."""
     cfg = SI.config_c1()
