@@ -588,25 +588,63 @@ __global__ __launch_bounds__(kBlock) void prefix_decode_kernel(PrefixArgs a)
     const uint64_t wave_sub = (uint64_t)blockIdx.x * kBlock + (uint64_t)wave_first;
     constexpr int kSteps = kSub / EPV;
     static_assert(kSteps % kLine == 0, "whole lines");
+    bool dense = false;  // byte codes: which of the two forms of a step this wave takes next (wave-uniform)
     for (int step = 0; step < kSteps; ++step) {
         const uint32_t fresh = min(kRing - (wr - rd), kTop);  // free slots of the ring
         uint32_t top[kTop];
 #pragma unroll
         for (uint32_t j = 0; j < kTop; ++j) top[j] = (j < fresh && w + j < wend) ? in[w + j] : 0u;
-        uint32_t q[4] = {0u, 0u, 0u, 0u};
+        uint4 *slot = stage + tid * kLine + ((step + (int)tid) & (kLine - 1));
+        if (WC == 0 && !dense) {
+            // Byte codes, most of them zero: the step's sixteen bytes start as zeros in LDS, a run
+            // of "0" codewords is skipped in one go (count of trailing zero bits, at most up to
+            // the end of the step) and only the non-zero codes are parsed and stored.  The loop
+            // runs once per non-zero code of the busiest lane (and ends after at most sixteen
+            // rounds whatever the bits are); a top-up at every round keeps at least 32 bits,
+            // enough for sixteen zeros and one codeword of at most ten.
+            *slot = make_uint4(0u, 0u, 0u, 0u);
+            uint8_t *bytes = reinterpret_cast<uint8_t *>(slot);
+            uint32_t pos = 0, busy = 0;
+            while (pos < (uint32_t)EPV) {
+                refill();
+                const uint32_t lo = (uint32_t)acc;
+                const uint32_t room = (uint32_t)EPV - pos;
+                uint32_t first_one;  // index of the lowest set bit; 0xffffffff if there is none
+                asm("v_ffbl_b32 %0, %1" : "=v"(first_one) : "v"(lo));
+                const uint32_t z = min(first_one, room);
+                const bool more = z < room;  // then bit z is a "1"
+                const uint32_t sym = lo >> z;
+                const bool value = (sym & 2u) != 0u;
+                const uint32_t v = value ? (sym >> 2) & payload_mask : special | (((sym >> 2) & 1u) << (width - 1));
+                const uint32_t used = z + (more ? (value ? 2u + (uint32_t)width : 3u) : 0u);
+                acc >>= used;
+                have -= used;
+                if (more) bytes[pos + z] = (uint8_t)v;
+                pos += z + 1u;
+                ++busy;
+            }
+            // a round costs about twice a symbol of the other form: that one is the better
+            // choice from about ten non-zero codes among sixteen in the busiest lane
+            dense = __builtin_amdgcn_ballot_w64(busy > 10u) != 0ull;
+        } else {
+            uint32_t q[4] = {0u, 0u, 0u, 0u};
+            uint32_t busy = 0;
 #pragma unroll
-        for (int j = 0; j < EPV; ++j) {
-            const uint32_t v = symbol(WC != 0 || j % 3 == 0);
-            if (WC == 2) q[j] = v;
-            else if (WC == 1) q[j / 2] |= v << (16 * (j % 2));
-            else q[j / 4] |= v << (8 * (j % 4));
+            for (int j = 0; j < EPV; ++j) {
+                const uint32_t v = symbol(WC != 0 || j % 3 == 0);
+                if (WC == 2) q[j] = v;
+                else if (WC == 1) q[j / 2] |= v << (16 * (j % 2));
+                else q[j / 4] |= v << (8 * (j % 4));
+                if (WC == 0) busy += v != 0u ? 1u : 0u;
+            }
+            *slot = make_uint4(q[0], q[1], q[2], q[3]);
+            if (WC == 0) dense = __builtin_amdgcn_ballot_w64(busy > 8u) != 0ull;
         }
 #pragma unroll
         for (uint32_t j = 0; j < kTop; ++j)
             if (j < fresh) ring[((wr + j) & (kRing - 1u)) * kBlock + tid] = top[j];
         wr += fresh;
         w += fresh;
-        stage[tid * kLine + ((step + (int)tid) & (kLine - 1))] = make_uint4(q[0], q[1], q[2], q[3]);
         if ((step & (kLine - 1)) != kLine - 1) continue;
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

@@ -148,6 +148,37 @@ def test_no_special_class_and_small_capacity(lgn):
         lgn.lgn_prefix_encode(d.view(torch.uint8), lgn.LGN_OUT_CODE8, None, None)
 
 
+def test_byte_codes_with_dense_and_sparse_stretches(lgn):
+    """The decoder takes a step of sixteen byte codes in one of two forms and picks the form for the
+    next step from how many non-zero codes the last one held: stretches of dense and of sparse codes
+    of many lengths, so that the switch happens at every position of a sub-block, in both
+    directions, and differently in the lanes of a wave."""
+    n_bits, e, m, s = 6, 3, 2, -14
+    f = lgn.upload_struct(lgn.LgnFpParams(n_bits, e, m, s, 0.0, 0, 0))
+    alpha = 3.1e-4
+    p = lgn.upload_struct(lgn.LgnPruneParams(alpha, 0, 0.0, 0.0))
+    special = O.prefix_special_of_code(alpha, e, m, s)
+    rng = np.random.default_rng(2024)
+    n = 37 * 4096 + 301
+    dens = np.empty(n)
+    i = 0
+    while i < n:
+        k = int(rng.choice([5, 16, 17, 48, 100, 256, 700, 5000]))
+        dens[i:i + k] = rng.choice([0.0, 0.05, 0.15, 0.4, 0.6, 0.9, 1.0])
+        i += k
+    codes = rng.integers(1, 1 << n_bits, n, dtype=np.uint8)
+    codes[rng.random(n) < 0.4] = special
+    codes[rng.random(n) >= dens] = 0
+    d = to_dev(codes)
+    buf, table = lgn.lgn_prefix_encode(d, lgn.LGN_OUT_CODE8, p, f)
+    got, t = host_stream(buf, table, n)
+    want, wt, wsub = O.prefix_encode(codes, special, n_bits, with_sub=True)
+    assert np.array_equal(t, wt) and np.array_equal(got, want)
+    assert np.array_equal(lgn.prefix_sub_lengths(table, n).cpu().numpy().view(np.uint16), wsub)
+    back = lgn.lgn_prefix_decode(buf, table, n, lgn.LGN_OUT_CODE8, p, f)
+    assert np.array_equal(back.cpu().numpy(), codes)
+
+
 def test_byte_codes_small_capacity(lgn):
     """Byte codes into a buffer that ends inside the stream: the chunks that fit are written whole,
     nothing is written past the buffer, the table is complete and the status entry is set."""
