@@ -5,7 +5,7 @@
 // consecutive 1 KiB rows per wave, the next batch requested before the current one is reduced.
 // Per element: l = v_log_f32(|g|) (one hardware instruction, relative error about 1e-7, i.e. well
 // inside the 1e-6 budget on mu even if every rounding went the same way), minus a wave-uniform
-// pivot taken from the wave's first row, widened to fp64 and accumulated as sum and sum of
+// pivot (the mean log2 of the wave's first row), widened to fp64 and accumulated as sum and sum of
 // squares in fp64.  Subtracting the pivot before squaring keeps the squares small, so nothing
 // cancels when the moments are formed.  Waves and workgroups are merged pairwise as
 // (count, mean, M2) with the exact parallel update  M2 = M2a + M2b + d^2 na nb / n,
@@ -342,25 +342,38 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
     t.mx = 0u; t.nmn = 0u; t.slow_cnt = 0u; t.nonfinite = 0u;
     uint32_t cnt = 0;  // wave-uniform; one wave sees far fewer than 2^32 elements
 
-    // Pivot: the largest normal magnitude in the wave's first row (1.0 if there is none) and its
-    // log2 as the hardware instruction returns it.
+    // Pivot: 2^(mean log2 of the normal magnitudes in the wave's first row), 1.0 if there is none,
+    // and its log2 as the hardware instruction returns it.  The mean, not an extreme: one huge or
+    // tiny value in that row must not move the pivot away from the bulk, or the squares of the
+    // deviations grow and their low bits (summed in fp32 for the 16-bit types) start to matter.
     uint32_t pivot_bits = 0x3f800000u;
     if (wave < nrows) {
         const R r = load_row<DTYPE, MASK>(gv, mask, wave * kWave + lane);
         const uint4 v = apply_mask<DTYPE, MASK>(r.g, r.m);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-        uint32_t cand = 0u;
+        float sum = 0.0f;
+        uint32_t count = 0u;
+        auto take = [&](uint32_t a) {
+            const bool normal = a >= 0x00800000u && a < 0x7f800000u;
+            sum += normal ? __builtin_amdgcn_logf(__uint_as_float(a)) : 0.0f;
+            count += normal ? 1u : 0u;
+        };
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             uint32_t lo = w[i], hi = 0u;
             if (DTYPE != LGN_F32) widen_pair<DTYPE>(w[i], lo, hi);
-            lo &= 0x7fffffffu;
-            hi &= 0x7fffffffu;
-            if (lo < 0x7f800000u) cand = max(cand, lo);
-            if (hi < 0x7f800000u) cand = max(cand, hi);
+            take(lo & 0x7fffffffu);
+            if (DTYPE != LGN_F32) take(hi & 0x7fffffffu);
         }
-        cand = wave_max(cand);
-        if (cand >= 0x00800000u) pivot_bits = cand;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            sum += __shfl_xor(sum, off);
+            count += __shfl_xor(count, off);
+        }
+        if (count != 0u) {
+            const float mean = fminf(fmaxf(sum / (float)count, -125.0f), 127.0f);  // 2^mean is a normal number
+            pivot_bits = __float_as_uint(__builtin_amdgcn_exp2f(mean));
+        }
         pivot_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)pivot_bits);
     }
     const float pivot = __builtin_amdgcn_logf(__uint_as_float(pivot_bits));

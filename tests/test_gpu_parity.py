@@ -112,6 +112,24 @@ def test_stats_parity_special_values(lgn, dtype):
     assert got.sigma == 0.0 and got.status & lgn.LGN_ST_SIGMA0
 
 
+@pytest.mark.parametrize("dtype", [SI.F32, SI.BF16, SI.F16])
+def test_stats_with_an_extreme_value_in_a_waves_first_row(lgn, dtype):
+    """A narrow distribution (sigma = 0.3) with the largest finite value of the type, and a tiny one,
+    among the first elements a wave reads: the wave's reference point for its sums must stay with
+    the bulk, or mu and sigma lose digits to cancellation (the 16-bit types add their squares in fp32
+    first).  Small tensors, so that single waves carry a large share of the result."""
+    big = {SI.F32: 3.0e38, SI.BF16: 3.0e38, SI.F16: 60000.0}[dtype]
+    small = {SI.F32: 1.0e-37, SI.BF16: 1.0e-37, SI.F16: 7.0e-5}[dtype]
+    mu = -4.0 if dtype == SI.F16 else -12.0
+    for n, places in ((2177, (3,)), (2177, (0, 1500)), (40_000, (5, 513, 20_000)), (300_000, (100, 2048 * 64 + 7))):
+        g32 = SI.lognormal_tensor(n, seed=n + len(places), mu=mu, sigma=0.3, zero_frac=0.3, dtype=SI.F32)
+        for k, i in enumerate(places):
+            g32[i] = big if k % 2 == 0 else small
+        g = g32 if dtype == SI.F32 else (SI.f32_to_bf16_bits(g32) if dtype == SI.BF16 else g32.astype(np.float16))
+        d = to_dev(g) if dtype != SI.F16 else torch.from_numpy(g).cuda()
+        assert_stats_match(lgn.read_stats(lgn.lgn_stats(d)), O.stats(g))
+
+
 def test_stats_config_c1_and_reproducible(lgn):
     cfg = SI.config_c1()
     g = SI.make(cfg)
