@@ -3,11 +3,11 @@
 //
 // Two-stage grid reduction.  Stage 1 streams the tensor once with 16-byte loads, a batch of four
 // consecutive 1 KiB rows per wave, the next batch requested before the current one is reduced.
-// Per element: l = v_log_f32(|g|) (one hardware instruction, relative error about 1e-7, i.e. well
-// inside the 1e-6 budget on mu even if every rounding went the same way), minus a wave-uniform
-// pivot (the mean log2 of the wave's first row), widened to fp64 and accumulated as sum and sum of
-// squares in fp64.  Subtracting the pivot before squaring keeps the squares small, so nothing
-// cancels when the moments are formed.  Waves and workgroups are merged pairwise as
+// Per element: d = v_log_f32(2^-k |g|) (one hardware instruction, at most 1 ulp of its result),
+// where 2^k is a wave-uniform reference point (k = the rounded mean log2 of the wave's first
+// row): the deviation from the reference point directly, widened to fp64 and accumulated as sum
+// and sum of squares in fp64.  Deviations are small, so the squares are, and nothing cancels
+// when the moments are formed.  Waves and workgroups are merged pairwise as
 // (count, mean, M2) with the exact parallel update  M2 = M2a + M2b + d^2 na nb / n,
 // d = mean_b - mean_a.  Stage 2 merges the per-block records in a fixed order, so results are
 // reproducible for a given launch shape.
@@ -92,8 +92,23 @@ __device__ __forceinline__ void accumulate_careful(uint32_t bits, float pivot, L
     t.nmn = max(t.nmn, 0u - a);
 }
 
+// The wave's reference point: a power of two near the bulk of its values (wave-uniform).
+struct Pivot {
+    uint32_t bits;        // 2^k as an fp32 pattern
+    float scale;          // 2^-k
+    float log2;           // k
+    uint32_t hi_lim;      // magnitudes at or above this pattern leave the fast path (Inf, NaN, or 2^-k |g| overflows)
+    uint32_t neg_lo_lim;  // minus the smallest pattern the fast path takes (below: subnormal, or 2^-k |g| is)
+};
+
 // Four elements per lane.  Returns the number of valid elements the fast path counted for the
 // whole wave (wave-uniform), 0 if the careful path was taken.
+// The logarithm is taken of 2^-k |g| (an exact product): its result is the deviation itself, a
+// small number, so the instruction's error (it truncates: -0.5 ulp of the RESULT on average, up
+// to 1 ulp) is small too and is spread evenly around the reference point.  Taken of |g| itself
+// the result sits near -20 for typical gradients, the error is 1e-6 absolute, and its mean
+// jumps where |log2| crosses a power of two -- at 2^-16, in the middle of typical gradients --
+// which a narrow distribution (sigma below 0.2) sees as an error of 1e-6 and more in sigma.
 // SUM4_F32: the four deviations and their squares are first summed in fp32 and enter the fp64
 // accumulators as two numbers instead of eight.  Used for the 16-bit element types, where the
 // pass is bound by arithmetic (twice the elements per byte): the three extra fp32 roundings per
@@ -101,28 +116,28 @@ __device__ __forceinline__ void accumulate_careful(uint32_t bits, float pivot, L
 // sum of four), far inside the 1e-6 budget on mu and sigma.
 template <bool SUM4_F32 = false>
 __device__ __forceinline__ uint32_t accumulate_quad(uint32_t b0, uint32_t b1, uint32_t b2,
-                                                    uint32_t b3, uint32_t pivot_bits, float pivot,
-                                                    LaneAcc &t)
+                                                    uint32_t b3, const Pivot &pv, LaneAcc &t)
 {
     const uint32_t a0 = b0 & 0x7fffffffu, a1 = b1 & 0x7fffffffu;
     const uint32_t a2 = b2 & 0x7fffffffu, a3 = b3 & 0x7fffffffu;
     const bool v0 = a0 != 0u, v1 = a1 != 0u, v2 = a2 != 0u, v3 = a3 != 0u;
-    // Zeros are replaced by the pivot magnitude BEFORE the logarithm, so they come out as an
+    // Zeros are replaced by the reference magnitude BEFORE the logarithm, so they come out as an
     // exact zero deviation (one integer select instead of masking a double afterwards).
-    const float f0 = __builtin_amdgcn_logf(__uint_as_float(v0 ? a0 : pivot_bits)) - pivot;
-    const float f1 = __builtin_amdgcn_logf(__uint_as_float(v1 ? a1 : pivot_bits)) - pivot;
-    const float f2 = __builtin_amdgcn_logf(__uint_as_float(v2 ? a2 : pivot_bits)) - pivot;
-    const float f3 = __builtin_amdgcn_logf(__uint_as_float(v3 ? a3 : pivot_bits)) - pivot;
+    const float f0 = __builtin_amdgcn_logf(__uint_as_float(v0 ? a0 : pv.bits) * pv.scale);
+    const float f1 = __builtin_amdgcn_logf(__uint_as_float(v1 ? a1 : pv.bits) * pv.scale);
+    const float f2 = __builtin_amdgcn_logf(__uint_as_float(v2 ? a2 : pv.bits) * pv.scale);
+    const float f3 = __builtin_amdgcn_logf(__uint_as_float(v3 ? a3 : pv.bits) * pv.scale);
     const uint32_t qmx = max(max(a0, a1), max(a2, a3));
     // -a is large for small a and 0 for a = 0 (unsigned): its maximum tracks the smallest non-zero
     const uint32_t qnmn = max(max(0u - a0, 0u - a1), max(0u - a2, 0u - a3));
-    // Inf / NaN have a >= 0x7f800000; a subnormal has 0 < a < 0x00800000
-    const bool odd = qmx >= 0x7f800000u || qnmn > 0xff800000u;
+    // Inf / NaN have a >= 0x7f800000; a subnormal has 0 < a < 0x00800000; the limits are tighter
+    // by |k| binades on one side, where the scaled value would leave the normal range
+    const bool odd = qmx >= pv.hi_lim || qnmn > pv.neg_lo_lim;
     if (__builtin_amdgcn_ballot_w64(odd) != 0ull) {
-        accumulate_careful(b0, pivot, t);
-        accumulate_careful(b1, pivot, t);
-        accumulate_careful(b2, pivot, t);
-        accumulate_careful(b3, pivot, t);
+        accumulate_careful(b0, pv.log2, t);
+        accumulate_careful(b1, pv.log2, t);
+        accumulate_careful(b2, pv.log2, t);
+        accumulate_careful(b3, pv.log2, t);
         return 0u;
     }
     const uint32_t cnt = (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(v0)) +
@@ -146,17 +161,16 @@ __device__ __forceinline__ uint32_t accumulate_quad(uint32_t b0, uint32_t b1, ui
 
 // 16 bytes = 4 fp32 or 8 bf16 elements
 template <int DTYPE>
-__device__ __forceinline__ uint32_t accumulate_vec(uint4 v, uint32_t pivot_bits, float pivot,
-                                                   LaneAcc &t)
+__device__ __forceinline__ uint32_t accumulate_vec(uint4 v, const Pivot &pv, LaneAcc &t)
 {
-    if (DTYPE == LGN_F32) return accumulate_quad(v.x, v.y, v.z, v.w, pivot_bits, pivot, t);
+    if (DTYPE == LGN_F32) return accumulate_quad(v.x, v.y, v.z, v.w, pv, t);
     uint32_t e[8];
     widen_pair<DTYPE>(v.x, e[0], e[1]);
     widen_pair<DTYPE>(v.y, e[2], e[3]);
     widen_pair<DTYPE>(v.z, e[4], e[5]);
     widen_pair<DTYPE>(v.w, e[6], e[7]);
-    return accumulate_quad<true>(e[0], e[1], e[2], e[3], pivot_bits, pivot, t) +
-           accumulate_quad<true>(e[4], e[5], e[6], e[7], pivot_bits, pivot, t);
+    return accumulate_quad<true>(e[0], e[1], e[2], e[3], pv, t) +
+           accumulate_quad<true>(e[4], e[5], e[6], e[7], pv, t);
 }
 
 template <typename T>
@@ -342,11 +356,11 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
     t.mx = 0u; t.nmn = 0u; t.slow_cnt = 0u; t.nonfinite = 0u;
     uint32_t cnt = 0;  // wave-uniform; one wave sees far fewer than 2^32 elements
 
-    // Pivot: 2^(mean log2 of the normal magnitudes in the wave's first row), 1.0 if there is none,
-    // and its log2 as the hardware instruction returns it.  The mean, not an extreme: one huge or
-    // tiny value in that row must not move the pivot away from the bulk, or the squares of the
-    // deviations grow and their low bits (summed in fp32 for the 16-bit types) start to matter.
-    uint32_t pivot_bits = 0x3f800000u;
+    // Reference point: 2^k, k = the mean log2 of the normal magnitudes in the wave's first row,
+    // rounded (0 if there is none).  The mean, not an extreme: one huge or tiny value in that row
+    // must not move it away from the bulk, or the squares of the deviations grow and their low
+    // bits (summed in fp32 for the 16-bit types) start to matter.
+    int k = 0;
     if (wave < nrows) {
         const R r = load_row<DTYPE, MASK>(gv, mask, wave * kWave + lane);
         const uint4 v = apply_mask<DTYPE, MASK>(r.g, r.m);
@@ -370,15 +384,18 @@ __device__ __forceinline__ void stage1_body(const void *__restrict__ g, const vo
             sum += __shfl_xor(sum, off);
             count += __shfl_xor(count, off);
         }
-        if (count != 0u) {
-            const float mean = fminf(fmaxf(sum / (float)count, -125.0f), 127.0f);  // 2^mean is a normal number
-            pivot_bits = __float_as_uint(__builtin_amdgcn_exp2f(mean));
-        }
-        pivot_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)pivot_bits);
+        if (count != 0u) k = (int)rintf(fminf(fmaxf(sum / (float)count, -126.0f), 126.0f));  // 2^k and 2^-k are normal
+        k = __builtin_amdgcn_readfirstlane(k);
     }
-    const float pivot = __builtin_amdgcn_logf(__uint_as_float(pivot_bits));
+    Pivot pv;
+    pv.bits = (uint32_t)(127 + k) << 23;
+    pv.scale = __uint_as_float((uint32_t)(127 - k) << 23);
+    pv.log2 = (float)k;
+    pv.hi_lim = k < 0 ? (uint32_t)(255 + k) << 23 : 0x7f800000u;
+    pv.neg_lo_lim = 0u - (k > 0 ? (uint32_t)(1 + k) << 23 : 0x00800000u);
+    const float pivot = pv.log2;
     auto reduce = [&](const R &r) {
-        cnt += accumulate_vec<DTYPE>(apply_mask<DTYPE, MASK>(r.g, r.m), pivot_bits, pivot, t);
+        cnt += accumulate_vec<DTYPE>(apply_mask<DTYPE, MASK>(r.g, r.m), pv, t);
     };
 
     // Full rows, wave-uniform control flow.  A batch is four CONSECUTIVE rows (4 KiB contiguous
