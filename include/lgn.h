@@ -73,7 +73,9 @@ extern "C" {
 #define LGN_ROUND_STOCHASTIC 1   /* up with probability (cut-off part)/(spacing), on a 2^-16 grid */
 
 /* what a quantizing call writes */
-#define LGN_OUT_VALUE 0  /* n elements of the input dtype holding 2^s * q                     */
+#define LGN_OUT_VALUE 0  /* n elements of the input dtype holding 2^s * q, rounded to        */
+                         /* nearest-even where the dtype cannot hold it (bf16 and fp16      */
+                         /* mantissas, subnormal results at very small scales)              */
 #define LGN_OUT_CODE8 1  /* n bytes, the N-bit code in the low bits                           */
 #define LGN_OUT_PACKED 2 /* little-endian bit stream, code i at bits [i*N, (i+1)*N),          */
                          /* lgn_packed_bytes(n, N) bytes, last byte zero padded               */

@@ -73,8 +73,13 @@ __device__ __forceinline__ uint32_t code_value_bits(uint32_t code, const QuantCo
     const uint32_t mant = k << (23 - q.m);
     if (ef >= 255) return sign | 0x7f800000u;
     if (ef >= 1) return sign | ((uint32_t)ef << 23) | mant;
-    const int sh = 1 - ef;  // result is subnormal in fp32
-    return sh > 24 ? sign : sign | ((0x800000u | mant) >> sh);
+    // The result is subnormal in fp32 and may need more bits than fp32 has there: rounded to
+    // nearest, ties to even, as a conversion of the exact value would (a carry gives 2^-126).
+    const int sh = 1 - ef;
+    if (sh > 24) return sign;  // below half of the smallest subnormal
+    const uint32_t x = 0x800000u | mant;
+    const uint32_t r = x >> sh, rem = x & ((1u << sh) - 1u), half = 1u << (sh - 1);
+    return sign | (r + ((rem > half || (rem == half && (r & 1u) != 0u)) ? 1u : 0u));
 }
 
 }  // namespace lgn

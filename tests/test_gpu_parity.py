@@ -460,6 +460,31 @@ def test_shard_invariance_and_dequantize(lgn):
             assert np.array_equal(got.view(want.dtype), want)
 
 
+def test_values_that_need_rounding_in_the_subnormal_range(lgn):
+    """At scales near 2^-149 the value 2^s q of a code with several mantissa bits is not an fp32
+    number: the output is that value rounded to nearest, ties to even (what the conversion of the
+    exact value gives), for the de-quantizer and for the VALUE output of the quantizer, every code of
+    several formats, every element type."""
+    for e, m in ((1, 5), (2, 5), (3, 4), (1, 2), (4, 3)):
+        nb = 1 + e + m
+        codes = np.arange(1 << nb, dtype=np.uint8)
+        for s in (-150, -149, -148, -147, -146, -140, -131, -127, -120):
+            f = dev_fp_params(lgn, e, m, s)
+            for dt, odt in ((lgn.LGN_F32, O.F32), (lgn.LGN_BF16, O.BF16), (lgn.LGN_F16, O.F16)):
+                want = O.dequantize(codes, e, m, s, odt)
+                deq = lgn.lgn_dequantize(to_dev(codes), codes.size, O.OUT_CODE8, f, dt)
+                got = to_host(deq.view(torch.int16) if dt != lgn.LGN_F32 else deq)
+                assert np.array_equal(got.view(np.uint16 if dt != lgn.LGN_F32 else np.uint32),
+                                      want.view(np.uint16 if dt != lgn.LGN_F32 else np.uint32)), (e, m, s, dt)
+            # the quantizer's own VALUE output, inputs across the format's range at this scale
+            x = (np.float64(2.0) ** s * np.linspace(0.0, 2.0 ** (1 << (e - 1)) * 1.5, 3001)).astype(np.float32)
+            x = np.concatenate([x, -x])
+            for rounding in (O.ROUND_NEAREST_EVEN, O.ROUND_STOCHASTIC):
+                w = O.fp_quantize(x, e, m, s, rounding, 77, 0, O.OUT_VALUE)
+                g = lgn.lgn_fp_quantize(to_dev(x), f, rounding, 77, 0, out_kind=O.OUT_VALUE)
+                assert np.array_equal(to_host(g).view(np.uint32), w.view(np.uint32)), (e, m, s, rounding)
+
+
 def test_chain_on_device_matches_oracle_chain(lgn):
     """stats -> threshold -> format -> fused, parameters never leaving the device."""
     cfg = SI.config_c1()
