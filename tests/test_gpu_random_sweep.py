@@ -1,7 +1,10 @@
 """Seeded random sweep of the streaming entry points: every argument drawn at random within its
 documented range (size, element type, threshold, format, scale, rounding, seed, element offset,
 output kind), the result compared bit for bit with the CPU oracle.  The fixed grids of the other
-parity files cover the corners; this one covers combinations nobody thought of."""
+parity files cover the corners; this one covers combinations nobody thought of.
+LGN_SWEEP_SEED (environment, an integer) moves every sweep to other draws."""
+import os
+
 import numpy as np
 import pytest
 
@@ -10,6 +13,8 @@ import synth_inputs as SI
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
+
+SEED_SHIFT = 1_000_003 * int(os.environ.get("LGN_SWEEP_SEED", "0"))
 
 
 @pytest.fixture(scope="module")
@@ -62,7 +67,7 @@ def draw_case(rng):
 
 
 def test_random_sweep_of_the_streaming_calls(lgn):
-    rng = np.random.default_rng(777)
+    rng = np.random.default_rng(777 + SEED_SHIFT)
     lgn_dtype = {SI.F32: lgn.LGN_F32, SI.BF16: lgn.LGN_BF16, SI.F16: lgn.LGN_F16}
     for case in range(160):
         dtype, g, alpha, e, m, s, rounding, seed, offset = draw_case(rng)
@@ -109,7 +114,7 @@ def test_random_sweep_of_statistics_and_parameters(lgn):
     mu and sigma to 1e-6; then threshold and format from the device's own statistics: the oracle's
     bits for alpha, its (e, m, s)."""
     import math
-    rng = np.random.default_rng(4242)
+    rng = np.random.default_rng(4242 + SEED_SHIFT)
     lgn_dtype = {SI.F32: lgn.LGN_F32, SI.BF16: lgn.LGN_BF16, SI.F16: lgn.LGN_F16}
     odt = {SI.F32: O.F32, SI.BF16: O.BF16, SI.F16: O.F16}
     for case in range(70):
@@ -159,3 +164,101 @@ def test_random_sweep_of_statistics_and_parameters(lgn):
         assert np.float32(gp.alpha).view(np.uint32) == np.float32(wp.alpha).view(np.uint32), ctx
         assert gp.status == wp.status, ctx
         assert (gf.e_bits, gf.m_bits, gf.scale_exp, gf.status) == (wf.e_bits, wf.m_bits, wf.scale_exp, wf.status), ctx
+
+
+SPECIAL_PATTERNS = {SI.F32: (0x7FC00000, 0xFF800000, 0x7F800000, 0x00000001, 0x807FFFFF, 0x80000000, 0x7F7FFFFF, 0x00800000),
+                    SI.BF16: (0x7FC0, 0xFF80, 0x7F80, 0x0001, 0x807F, 0x8000, 0x7F7F, 0x0080),
+                    SI.F16: (0x7E00, 0xFC00, 0x7C00, 0x0001, 0x83FF, 0x8000, 0x7BFF, 0x0400)}
+
+
+def test_random_sweep_over_the_whole_parameter_range(lgn):
+    """As the first sweep, but nothing is kept near the tensor's own scale: magnitudes from the
+    bottom to the top of the element type, scales from -150 to 125, thresholds anywhere in fp32,
+    NaN / Inf / subnormal / extreme patterns planted, all three output kinds and the two halves
+    of the composition for every case."""
+    rng = np.random.default_rng(8 + SEED_SHIFT)
+    lgn_dtype = {SI.F32: lgn.LGN_F32, SI.BF16: lgn.LGN_BF16, SI.F16: lgn.LGN_F16}
+    with np.errstate(over="ignore"):
+        for case in range(200):
+            dtype = (SI.F32, SI.BF16, SI.F16)[int(rng.integers(0, 3))]
+            n = int(rng.choice([rng.integers(1, 600), rng.integers(600, 9000), rng.integers(9000, 200_000)]))
+            lim = 9.0 if dtype == SI.F16 else 80.0
+            mu, sigma = float(rng.uniform(-lim, lim * 0.9)), float(rng.uniform(0.1, 6.0))
+            g = SI.lognormal_tensor(n, seed=int(rng.integers(0, 1 << 30)), mu=mu, sigma=sigma,
+                                    zero_frac=float(rng.uniform(0, 0.6)), dtype=dtype)
+            if n > 20:
+                g.view(np.uint32 if dtype == SI.F32 else np.uint16)[rng.choice(n, 8, replace=False)] = SPECIAL_PATTERNS[dtype]
+            nb = int(rng.integers(2, 9))
+            e = int(rng.integers(1, nb))
+            m = nb - 1 - e
+            s = int(rng.integers(-150, 126))
+            if rng.random() < 0.5:
+                s = max(-150, min(125, int(round(mu / np.log(2.0))) + int(rng.integers(-12, 13))))
+            a = float(np.float32(np.exp(rng.uniform(-103.0, 88.0)))) if rng.random() < 0.5 \
+                else float(np.float32(np.exp(mu + sigma * rng.uniform(-2, 3))))
+            a = alpha_in_dtype(min(a, 60000.0) if dtype == SI.F16 else a, dtype)
+            if not np.isfinite(a) or rng.random() < 0.08:
+                a = 0.0
+            rounding, seed = int(rng.integers(0, 2)), int(rng.integers(0, 1 << 63))
+            offset = int(rng.choice([0, 4 * rng.integers(0, 1 << 40), rng.integers(0, 1 << 34),
+                                     (1 << 34) - 4 * rng.integers(1, 2000), (1 << 34) - rng.integers(1, 300)]))
+            ctx = (case, dtype, n, a, e, m, s, rounding, seed, offset)
+            d = to_dev(g)
+            p = lgn.upload_struct(lgn.LgnPruneParams(a, 0, 0.0, 0.0))
+            f = lgn.upload_struct(lgn.LgnFpParams(nb, e, m, s, 0.0, 0, 0))
+            for kind in (O.OUT_CODE8, O.OUT_PACKED, O.OUT_VALUE):
+                want = O.prune_quantize(g, a, e, m, s, rounding, seed, offset, kind)
+                got = lgn.lgn_prune_quantize_fused(d, p, f, rounding, seed, offset, out_kind=kind, n_bits=nb,
+                                                   dtype=lgn_dtype[dtype])
+                if kind == O.OUT_VALUE:
+                    assert np.array_equal(raw(got, g), raw(_as_tensor(want), g)), (kind,) + ctx
+                else:
+                    assert np.array_equal(got.cpu().numpy(), want), (kind,) + ctx
+            gotp = lgn.lgn_prune(d, p, seed, offset, dtype=lgn_dtype[dtype])
+            assert np.array_equal(raw(gotp, g), raw(_as_tensor(O.prune(g, a, seed, offset)), g)), ctx
+            gotq = lgn.lgn_fp_quantize(d, f, rounding, seed, offset, out_kind=O.OUT_PACKED, n_bits=nb, dtype=lgn_dtype[dtype])
+            assert np.array_equal(gotq.cpu().numpy(), O.fp_quantize(g, e, m, s, rounding, seed, offset, O.OUT_PACKED)), ctx
+
+
+def test_random_sweep_of_statistics_over_the_whole_range(lgn):
+    """Statistics of tensors anywhere in the element type's range, spreads from 0.05 to 9, a stretch
+    of a very different magnitude somewhere, special patterns, all mask kinds: counts and extrema
+    exact, mu and sigma to 1e-6 of max(|mu|, sigma) and of sigma (mu may be near zero here)."""
+    rng = np.random.default_rng(3 + SEED_SHIFT)
+    code = {SI.F32: lgn.LGN_F32, SI.BF16: lgn.LGN_BF16, SI.F16: lgn.LGN_F16}
+    with np.errstate(over="ignore"):
+        for case in range(150):
+            dtype = (SI.F32, SI.BF16, SI.F16)[case % 3]
+            n = int(rng.choice([rng.integers(1, 3000), rng.integers(3000, 300_000), rng.integers(300_000, 2_000_000)]))
+            lim = 10.0 if dtype == SI.F16 else 86.0
+            mu = float(rng.uniform(-lim, lim))
+            sigma = float(rng.choice([rng.uniform(0.05, 0.5), rng.uniform(0.5, 3.0), rng.uniform(3.0, 9.0)]))
+            g = SI.lognormal_tensor(n, seed=int(rng.integers(0, 1 << 30)), mu=mu, sigma=sigma,
+                                    zero_frac=float(rng.uniform(0.0, 0.7)), dtype=dtype)
+            if rng.random() < 0.3 and n > 600:
+                at = int(rng.integers(0, n - 500))
+                length = int(rng.integers(1, min(n - at, 200_000)))
+                g[at:at + length] = SI.lognormal_tensor(length, seed=int(rng.integers(0, 1 << 30)), mu=float(rng.uniform(-lim, lim)),
+                                                        sigma=0.3, zero_frac=0.0, dtype=dtype)
+            if n > 50 and rng.random() < 0.5:
+                g.view(np.uint32 if dtype == SI.F32 else np.uint16)[rng.choice(n, 8, replace=False)] = SPECIAL_PATTERNS[dtype]
+            d = to_dev(g)
+            mode = int(rng.integers(0, 3))
+            if mode == 0:
+                mask = (rng.random(n) < 0.6).astype(np.uint8)
+                want, st = O.stats_masked(g, mask), lgn.lgn_stats_masked(d, torch.from_numpy(mask).cuda(), dtype=code[dtype])
+            elif mode == 1:
+                mask = g.copy()
+                mask.view(np.uint16 if dtype != SI.F32 else np.uint32)[rng.random(n) < 0.4] = 0
+                want, st = O.stats_masked(g, mask), lgn.lgn_stats_masked(d, to_dev(mask), dtype=code[dtype])
+            else:
+                want, st = O.stats(g), lgn.lgn_stats(d, dtype=code[dtype])
+            got = lgn.read_stats(st)
+            ctx = (case, dtype, n, mode, mu, sigma)
+            assert (got.n, got.nnz, got.n_nonfinite, got.status) == (want.n, want.nnz, want.n_nonfinite, want.status), ctx
+            assert np.float32(got.max_abs) == np.float32(want.max_abs), ctx
+            assert np.float32(got.min_abs_nz) == np.float32(want.min_abs_nz), ctx
+            if want.nnz == 0:
+                continue
+            assert abs(got.mu - want.mu) <= 1e-6 * max(abs(want.mu), want.sigma) + 1e-12, ctx
+            assert abs(got.sigma - want.sigma) <= 1e-6 * want.sigma + 1e-12, ctx
