@@ -509,3 +509,34 @@ def test_pruning_bias_of_the_16_bit_grid_is_bounded():
         total = sum(float(O.prune_one(x, alpha, k << 16)) for k in range(1 << 16))
         mean = total / 2 ** 16
         assert abs(mean - float(x)) <= float(alpha) * 2.0 ** -17 * (1 + 1e-6), (x, mean)
+
+
+def test_value_output_is_the_exact_value_rounded_to_the_type():
+    """2^s q written out from the code's fields in exact arithmetic (Fraction), then rounded to the
+    output type by numpy: at scales near 2^-149 the value needs more bits than an fp32 subnormal
+    has, and the de-quantizer's output is the nearest fp32 (ties to even), not a truncation; the
+    16-bit types round the same value once more."""
+    from fractions import Fraction
+    for e, m in ((1, 5), (2, 5), (3, 4), (4, 3), (1, 2)):
+        nb = 1 + e + m
+        codes = np.arange(1 << nb, dtype=np.uint8)
+        emax = 1 << (e - 1)
+        for s in (-150, -149, -148, -147, -140, -127, -20, 0, 100):
+            exact = []
+            for c in range(1 << nb):
+                mag = c & ((1 << (e + m)) - 1)
+                cexp, k = mag >> m, mag & ((1 << m) - 1)
+                # exponent codes 1 .. 2^e - 1 stand for 2^(1 - emax) .. 2^(emax - 1): symmetric about 1
+                v = Fraction(0) if cexp == 0 else (1 + Fraction(k, 1 << m)) * Fraction(2) ** (cexp - emax + s)
+                exact.append(-v if c >> (e + m) else v)
+            as_double = np.array([float(v) for v in exact])            # exact: at most 9 significant bits
+            assert all(Fraction(d) == v for d, v in zip(as_double, exact))
+            with np.errstate(over="ignore", under="ignore"):
+                want32 = as_double.astype(np.float32)
+            got32 = O.dequantize(codes, e, m, s, O.F32)
+            assert np.array_equal(got32.view(np.uint32) & 0x7FFFFFFF, want32.view(np.uint32) & 0x7FFFFFFF), (e, m, s)
+            assert np.array_equal(np.signbit(got32)[want32 != 0], np.signbit(want32)[want32 != 0])
+            got16 = O.dequantize(codes, e, m, s, O.F16)
+            with np.errstate(over="ignore", under="ignore"):
+                want16 = want32.astype(np.float16)
+            assert np.array_equal(got16.view(np.uint16) & 0x7FFF, want16.view(np.uint16) & 0x7FFF), (e, m, s)
